@@ -1,0 +1,255 @@
+"""Pins of the CPU oracle's hashing and attention functions (no GPU).
+
+Each pin checks the oracle against something it does not share code with: a
+closed form, a dense +-1 matrix product, exact rational arithmetic, a library
+routine.  The paper prints no worked numeric example for these operations, so
+the pins are what the mathematics of Eq. 1 / Eq. 3 fixes.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_06446_amd import workloads as wl
+
+
+def unpack_sigma(codes, nbits):
+    """Test-local unpack: uint64 [..., W] -> +-1 float64 [..., nbits] (bit j of word j//64)."""
+    codes = np.asarray(codes, dtype=np.uint64)
+    out = np.empty(codes.shape[:-1] + (nbits,), dtype=np.float64)
+    for j in range(nbits):
+        bit = (codes[..., j // 64] >> np.uint64(j % 64)) & np.uint64(1)
+        out[..., j] = np.where(bit == 1, 1.0, -1.0)
+    return out
+
+
+def pack_bits(bits):
+    """bool [..., nbits] -> uint64 [..., nbits//64]."""
+    bits = np.asarray(bits).astype(np.uint64)
+    nbits = bits.shape[-1]
+    W = nbits // 64
+    out = np.zeros(bits.shape[:-1] + (W,), dtype=np.uint64)
+    for j in range(nbits):
+        out[..., j // 64] |= bits[..., j] << np.uint64(j % 64)
+    return out
+
+
+# ---------------------------------------------------------------- Hamming ----
+
+def test_hamming_identity_exhaustive_low_bits():
+    """S = k - 2*popcount(a xor b) for all 2^8 x 2^8 pairs of low bytes, fixed high bits."""
+    hi = np.uint64(0xA5C3_0F96_1234_0000)
+    a = (np.arange(256, dtype=np.uint64) | hi).reshape(1, 1, 256, 1)
+    s = oracle.hamming_scores(a, a, 64)[0, 0]
+    for i in range(256):
+        for j in range(256):
+            assert s[i, j] == 64 - 2 * bin(i ^ j).count("1")
+
+
+@pytest.mark.parametrize("nbits", [64, 128, 256])
+def test_hamming_equals_dense_sigma_matmul(nbits):
+    q = wl.random_codes(1, (2, 3, 37), nbits)
+    k = wl.random_codes(2, (2, 3, 53), nbits)
+    s = oracle.hamming_scores(q, k, nbits)
+    ref = np.einsum("bhik,bhjk->bhij", unpack_sigma(q, nbits), unpack_sigma(k, nbits))
+    assert s.shape == (2, 3, 37, 53)
+    assert np.array_equal(s.astype(np.int64), ref.astype(np.int64))
+    # popcount form with Python's big-int popcount on the whole code
+    for (b, h, i, j) in [(0, 0, 0, 0), (1, 2, 36, 52), (0, 1, 5, 7)]:
+        x = 0
+        for w in range(nbits // 64):
+            x |= (int(q[b, h, i, w]) ^ int(k[b, h, j, w])) << (64 * w)
+        assert s[b, h, i, j] == nbits - 2 * bin(x).count("1")
+
+
+def test_hamming_special_cases():
+    nbits = 128
+    a = wl.random_codes(3, (1, 1, 16), nbits)
+    na = ~a
+    s_aa = oracle.hamming_scores(a, a, nbits)[0, 0]
+    s_an = oracle.hamming_scores(a, na, nbits)[0, 0]
+    assert np.all(np.diag(s_aa) == nbits)
+    assert np.all(np.diag(s_an) == -nbits)
+    assert np.array_equal(s_aa, s_aa.T)
+    assert np.all((s_aa.astype(np.int64) - nbits) % 2 == 0)
+    # one flipped bit at position 64*w + 5 lowers the score by exactly 2
+    b = a.copy()
+    b[..., 1] ^= np.uint64(1 << 5)
+    assert np.all(np.diag(oracle.hamming_scores(a, b, nbits)[0, 0]) == nbits - 2)
+
+
+# ---------------------------------------------------------------- binarize ---
+
+def test_binarize_sign_mode_and_zero():
+    x = np.array([0.0, -0.0, 1.0, -1.0, 1e-45, -1e-45, np.nan, np.inf] * 8, dtype=np.float32)
+    x = x.reshape(1, 1, 1, 64)
+    code = int(oracle.binarize(x, None, 64)[0, 0, 0, 0])
+    expect = [1, 1, 1, 0, 1, 0, 0, 1] * 8
+    assert [(code >> j) & 1 for j in range(64)] == expect
+
+
+def test_binarize_layout_and_identity_projection():
+    g = np.random.default_rng(5)
+    x = g.standard_normal((2, 5, 3, 64), dtype=np.float32)
+    c0 = oracle.binarize(x, None, 64)
+    assert c0.shape == (2, 3, 5, 1)                       # [B, H, N, W]
+    ref = pack_bits(np.transpose(x, (0, 2, 1, 3)) >= 0)
+    assert np.array_equal(c0, ref)
+    eye = np.eye(64, dtype=np.float32)
+    assert np.array_equal(oracle.binarize(x, eye, 64), c0)
+    assert np.array_equal(oracle.binarize(x, -eye, 64), ~c0)   # no exact zeros in x
+    assert np.array_equal(oracle.binarize(x * np.float32(2.0 ** -20), eye, 64), c0)
+
+
+def test_binarize_integer_projection_equals_exact_matmul():
+    """Small-integer x and proj: every fp32 operation is exact, so the bit is the
+    sign of the integer dot product; a transposed or mis-strided proj fails."""
+    g = np.random.default_rng(6)
+    x = g.integers(-8, 9, size=(1, 7, 2, 32)).astype(np.float32)
+    pr = g.integers(-8, 9, size=(32, 128)).astype(np.float32)
+    codes = oracle.binarize(x, pr, 128)
+    dots = np.einsum("bnhk,kj->bhnj", x.astype(np.int64), pr.astype(np.int64))
+    assert np.array_equal(codes, pack_bits(dots >= 0))
+
+
+def _round_fraction_to_f32(fr):
+    """Round an exact rational to the nearest fp32 (ties to even), normal range only."""
+    if fr == 0:
+        return Fraction(0)
+    sign = -1 if fr < 0 else 1
+    a = abs(fr)
+    e = math.floor(math.log2(float(a)))
+    while Fraction(2) ** e > a:
+        e -= 1
+    while Fraction(2) ** (e + 1) <= a:
+        e += 1
+    ulp = Fraction(2) ** (e - 23)
+    qf = a / ulp
+    lo = qf.numerator // qf.denominator
+    rem = qf - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return sign * lo * ulp
+
+
+def test_binarize_chain_order_by_exact_rational_fma():
+    """The defining fp32 chain acc = fma(x_k, r_kj, acc), k ascending, rebuilt with
+    exact rationals and one explicit rounding per step."""
+    g = np.random.default_rng(7)
+    d, nbits = 16, 64
+    x = g.standard_normal((1, 3, 1, d), dtype=np.float32)
+    pr = g.standard_normal((d, nbits), dtype=np.float32)
+    # make several projections cancel almost exactly so that the order matters
+    pr[d - 1, :] = (-(x[0, 0, 0, : d - 1].astype(np.float64) @ pr[: d - 1].astype(np.float64))
+                    / np.float64(x[0, 0, 0, d - 1])).astype(np.float32)
+    codes = oracle.binarize(x, pr, nbits)
+    for n in range(3):
+        for j in range(nbits):
+            acc = Fraction(0)
+            for k in range(d):
+                acc = _round_fraction_to_f32(
+                    Fraction(float(x[0, n, 0, k])) * Fraction(float(pr[k, j])) + acc)
+            assert ((int(codes[0, 0, n, 0]) >> j) & 1) == (1 if acc >= 0 else 0), (n, j)
+
+
+def test_binarize_matches_exact_sign_outside_error_bound():
+    cfg = wl.scaled_down(wl.C4, B=1, N=40)
+    q, _, _ = wl.qkv(cfg)
+    pr = wl.proj(cfg)
+    codes = oracle.binarize(q, pr, cfg.nbits)
+    x64 = q.astype(np.float64)
+    exact = np.einsum("bnhk,kj->bhnj", x64, pr.astype(np.float64))
+    bound = cfg.d * 2.0 ** -23 * np.einsum("bnhk,kj->bhnj", np.abs(x64), np.abs(pr.astype(np.float64)))
+    sure = np.abs(exact) > bound
+    assert sure.mean() > 0.999
+    bits = unpack_sigma(codes, cfg.nbits) > 0
+    assert np.array_equal(bits[sure], (exact >= 0)[sure])
+
+
+# ------------------------------------------------------- additive attention --
+
+def test_ktv_and_qkv_equal_dense_sigma_matmul():
+    B, H, Nq, Nk, nbits, dv = 2, 3, 19, 23, 128, 24
+    q = wl.random_codes(11, (B, H, Nq), nbits)
+    k = wl.random_codes(12, (B, H, Nk), nbits)
+    v = np.random.default_rng(13).standard_normal((B, Nk, H, dv), dtype=np.float32)
+    kv = oracle.ktv(k, v, nbits)
+    sk = unpack_sigma(k, nbits)                 # [B,H,Nk,nbits]
+    sq = unpack_sigma(q, nbits)
+    v64 = np.transpose(v.astype(np.float64), (0, 2, 1, 3))   # [B,H,Nk,dv]
+    kv_ref = np.matmul(np.swapaxes(sk, 2, 3), v64)           # [B,H,nbits,dv]
+    assert kv.shape == (B, H, nbits, dv)
+    np.testing.assert_allclose(kv, kv_ref, rtol=1e-13, atol=1e-11)
+    scale = 0.03125
+    o = oracle.qkv(q, kv, scale)
+    o_ref = np.transpose(scale * np.matmul(sq, kv_ref), (0, 2, 1, 3))   # [B,Nq,H,dv]
+    assert o.shape == (B, Nq, H, dv)
+    np.testing.assert_allclose(o, o_ref, rtol=1e-12, atol=1e-10)
+
+
+def test_linear_order_equals_quadratic_order_through_integer_scores():
+    """Q(K^T V) == (Q K^T) V with the integer Hamming matrix: ties the additive
+    kernels' definition to the score definition (Sec. 4.1, exchanged MatMul order)."""
+    B, H, Nq, Nk, nbits, dv = 1, 2, 31, 45, 64, 16
+    q = wl.random_codes(21, (B, H, Nq), nbits)
+    k = wl.random_codes(22, (B, H, Nk), nbits)
+    v = np.random.default_rng(23).standard_normal((B, Nk, H, dv), dtype=np.float32)
+    o, _ = oracle.additive_attention(q, k, v, nbits, 0.5)
+    s = oracle.hamming_scores(q, k, nbits).astype(np.float64)
+    ref = 0.5 * np.einsum("bhij,bjhc->bihc", s, v.astype(np.float64))
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-10)
+
+
+def test_additive_special_cases():
+    nbits, dv, Nk = 64, 8, 10
+    v = np.random.default_rng(31).standard_normal((1, Nk, 1, dv), dtype=np.float32)
+    ones = np.full((1, 1, Nk, 1), np.uint64(2**64 - 1))
+    kv = oracle.ktv(ones, v, nbits)
+    colsum = v.astype(np.float64).sum(axis=1)[0, 0]
+    np.testing.assert_allclose(kv[0, 0], np.tile(colsum, (nbits, 1)), rtol=1e-14)
+    o = oracle.qkv(ones[:, :, :3], kv, 0.25)
+    np.testing.assert_allclose(o[0, :, 0], np.tile(0.25 * nbits * colsum, (3, 1)), rtol=1e-14)
+    zeros = np.zeros_like(ones)
+    np.testing.assert_allclose(oracle.ktv(zeros, v, nbits), -kv, rtol=1e-14)
+    # Nk = 1 and Q = K: O = scale * nbits * v
+    c = wl.random_codes(32, (1, 1, 1), nbits)
+    o1, _ = oracle.additive_attention(c, c, v[:, :1], nbits, 2.0)
+    np.testing.assert_allclose(o1[0, 0, 0], 2.0 * nbits * v[0, 0, 0].astype(np.float64), rtol=1e-14)
+
+
+# ------------------------------------------------------- Hamming attention ---
+
+def test_hamming_attention_equals_textbook_softmax_attention():
+    B, H, Nq, Nk, nbits, dv = 2, 2, 17, 29, 128, 12
+    q = wl.random_codes(41, (B, H, Nq), nbits)
+    k = wl.random_codes(42, (B, H, Nk), nbits)
+    v = np.random.default_rng(43).standard_normal((B, Nk, H, dv), dtype=np.float32)
+    scale = float(np.float32(1.0 / math.sqrt(nbits)))
+    o = oracle.hamming_attention(q, k, v, nbits, scale)
+    tq = torch.from_numpy(unpack_sigma(q, nbits))
+    tk = torch.from_numpy(unpack_sigma(k, nbits))
+    tv = torch.from_numpy(np.transpose(v.astype(np.float64), (0, 2, 1, 3)).copy())
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=scale)
+    ref = ref.permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(o, ref, rtol=1e-10, atol=1e-12)
+
+
+def test_hamming_attention_special_cases():
+    nbits, dv, Nk = 64, 6, 9
+    v = np.random.default_rng(51).standard_normal((1, Nk, 1, dv), dtype=np.float32)
+    q = wl.random_codes(52, (1, 1, 4), nbits)
+    same = np.tile(wl.random_codes(53, (1, 1, 1), nbits), (1, 1, Nk, 1))
+    o = oracle.hamming_attention(q, same, v, nbits, 0.7)
+    mean = v.astype(np.float64).mean(axis=1)[0, 0]
+    np.testing.assert_allclose(o[0, :, 0], np.tile(mean, (4, 1)), rtol=1e-13)
+    # huge scale, one key equal to the query: softmax collapses onto that key
+    k = wl.random_codes(54, (1, 1, Nk), nbits)
+    k[0, 0, 3] = q[0, 0, 1]
+    o = oracle.hamming_attention(q, k, v, nbits, 50.0)
+    np.testing.assert_allclose(o[0, 1, 0], v[0, 3, 0].astype(np.float64), rtol=1e-9, atol=1e-12)
+    # scale 0: uniform weights
+    o = oracle.hamming_attention(q, k, v, nbits, 0.0)
+    np.testing.assert_allclose(o[0, :, 0], np.tile(mean, (4, 1)), rtol=1e-13)

@@ -1,0 +1,186 @@
+"""Pins of the CPU oracle's shift-layer, quantisation, routing and expert functions (no GPU)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_06446_amd import workloads as wl
+
+
+def decode_raw(neg, e):
+    """Test-local decode from the UNPACKED draws: W = s * 2^e as int64."""
+    return np.where(neg == 1, -1, 1).astype(np.int64) * (np.int64(1) << e.astype(np.int64))
+
+
+# ------------------------------------------------------------- shift layer ---
+
+@pytest.mark.parametrize("M,K,N", [(5, 16, 7), (33, 384, 40), (12, 1536, 9)])
+def test_shift_linear_equals_integer_matmul_with_decoded_weights(M, K, N):
+    neg, e = wl.shift_weight_raw(3, 4, N, K)
+    w4 = wl.pack_w4(neg, e)
+    assert w4.shape == (N, K // 2)
+    x = wl.int8_activations(3, M, K)
+    y = oracle.shift_linear(x, w4)
+    ref = x.astype(np.int64) @ decode_raw(neg, e).T
+    assert np.array_equal(y.astype(np.int64), ref)
+
+
+def test_shift_linear_nibble_order_by_one_hot_rows():
+    """x = unit vectors: row k of Y is column k of the decoded weights, so the
+    low nibble must be the even k."""
+    K, N = 8, 3
+    nib = np.array([[0x0, 0x9, 0x2, 0xB, 0x4, 0xD, 0x6, 0xF],
+                    [0x7, 0x8, 0x1, 0xA, 0x3, 0xC, 0x5, 0xE],
+                    [0xF, 0x0, 0xF, 0x0, 0x8, 0x7, 0x8, 0x7]], dtype=np.uint8)
+    w4 = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    x = np.eye(K, dtype=np.int8)
+    y = oracle.shift_linear(x, w4)
+    expect = np.where(nib & 8, -1, 1) * (1 << (nib & 7).astype(np.int64))
+    assert np.array_equal(y, expect.T)
+    assert y[1, 0] == -2 and y[7, 0] == -128 and y[0, 1] == 128 and y[0, 0] == 1
+
+
+def test_shift_linear_special_cases():
+    M, K, N = 6, 64, 5
+    x = wl.int8_activations(3, M, K, extra=1)
+    rows = x.astype(np.int64).sum(axis=1, keepdims=True)
+    w_plus0 = np.zeros((N, K // 2), dtype=np.uint8)                 # s=+1, e=0
+    assert np.array_equal(oracle.shift_linear(x, w_plus0), np.tile(rows, (1, N)))
+    w_plus7 = np.full((N, K // 2), 0x77, dtype=np.uint8)            # s=+1, e=7
+    assert np.array_equal(oracle.shift_linear(x, w_plus7), np.tile(128 * rows, (1, N)))
+    w = wl.shift_weights(3, 5, N, K)
+    y = oracle.shift_linear(x, w)
+    assert np.array_equal(oracle.shift_linear(x, w ^ np.uint8(0x88)), -y)      # flip every sign
+    x2 = wl.int8_activations(3, M, K, extra=2) // 2
+    x1 = x // 2
+    assert np.array_equal(oracle.shift_linear((x1 + x2).astype(np.int8), w),
+                          oracle.shift_linear(x1.astype(np.int8), w) + oracle.shift_linear(x2.astype(np.int8), w))
+    bias = np.arange(N, dtype=np.int32) * 1000 - 7
+    assert np.array_equal(oracle.shift_linear(x, w, bias), y + bias[None, :])
+    # worst case stays inside int32: |Y| <= 127 * 128 * K
+    xmax = np.full((1, 3072), 127, dtype=np.int8)
+    wmax = np.full((2, 1536), 0x77, dtype=np.uint8)
+    assert oracle.shift_linear(xmax, wmax)[0, 0] == 127 * 128 * 3072
+
+
+# ------------------------------------------------------------ quantisation ---
+
+def test_quantize_act_rounding_and_clamp():
+    x = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, 127.5, 300.0, -127.5, -1e9, 3.0, -0.0,
+                  np.nan, np.inf, -np.inf], dtype=np.float32)
+    q = oracle.quantize_act(x, 1.0)
+    assert q.tolist() == [0, 2, 2, 0, -2, -2, 126, 127, 127, -127, -127, 3, 0, 0, 127, -127]
+    ints = np.arange(-127, 128, dtype=np.float32)
+    assert np.array_equal(oracle.quantize_act(ints, 1.0), ints.astype(np.int8))
+    g = np.random.default_rng(1).standard_normal(4096).astype(np.float32)
+    s = np.float32(31.75)
+    ref = np.clip(np.rint(g * s), -127, 127).astype(np.int8)     # numpy rint = half to even
+    assert np.array_equal(oracle.quantize_act(g, float(s)), ref)
+
+
+def test_requant_lut():
+    lut = wl.activation_lut()
+    assert lut.shape == (256,) and lut.dtype == np.int8
+    y = np.array([0, 1, -1, 1000, -1000, 2**31 - 1, -2**31, 48, 80, 16777217], dtype=np.int32)
+    s = np.float32(1 / 32)
+    t = np.clip(np.rint(y.astype(np.float32) * s), -127, 127).astype(np.int64)
+    assert np.array_equal(oracle.requant_lut(y, float(s), lut), lut[t + 128])
+    ident = np.arange(-128, 128).astype(np.int8)
+    assert oracle.requant_lut(np.array([48, 80], np.int32), float(s), ident).tolist() == [2, 2]
+    # table shape: ~identity for large positive codes, ~0 for large negative, 0 at 0
+    assert lut[128] == 0 and lut[128 + 127] == 127 and lut[128 - 127] == 0 and lut[128 + 32] == 27
+
+
+# ----------------------------------------------------------------- routing ---
+
+def test_moe_dispatch_invariants_and_ties():
+    T = 1000
+    logits = wl.random_logits(1, T, tie_every=7)
+    perm, expert_of, counts, gate = oracle.moe_dispatch(logits)
+    assert np.array_equal(np.sort(perm), np.arange(T))
+    assert counts.sum() == T
+    assert counts[1] == int((logits[:, 1] > logits[:, 0]).sum())
+    assert np.array_equal(expert_of, (logits[:, 1] > logits[:, 0]).astype(np.int32))
+    assert np.all(expert_of[::7] == 0)                         # ties go to the Mult expert
+    c0 = counts[0]
+    assert np.all(np.diff(perm[:c0]) > 0) and np.all(np.diff(perm[c0:]) > 0)
+    assert np.all(expert_of[perm[:c0]] == 0) and np.all(expert_of[perm[c0:]] == 1)
+    ref = torch.softmax(torch.from_numpy(logits.astype(np.float64)), dim=1).max(dim=1).values.numpy()
+    np.testing.assert_allclose(gate, ref, rtol=1e-14)
+    assert np.all(gate >= 0.5) and np.all(gate < 1.0)
+    _, _, _, gate_swapped = oracle.moe_dispatch(np.ascontiguousarray(logits[:, ::-1]))
+    np.testing.assert_allclose(gate_swapped, gate, rtol=1e-15)
+
+
+@pytest.mark.parametrize("cfg", [wl.C1, wl.C4])
+def test_router_recipe_gives_the_stated_split(cfg):
+    logits = wl.router_logits(cfg)
+    _, expert_of, counts, _ = oracle.moe_dispatch(logits)
+    n_shift = int(math.floor(cfg.shift_frac * cfg.T + 0.5))
+    assert counts.tolist() == [cfg.T - n_shift, n_shift]
+    assert np.all(logits[:, 0] != logits[:, 1])
+    assert {1: (98, 99), 4: (3782, 8826)}[cfg.cfg_id] == tuple(counts.tolist())
+
+
+# ------------------------------------------------------------ Mult expert ----
+
+def test_round_to_half_matches_ieee_binary16():
+    g = np.random.default_rng(2)
+    x = np.concatenate([g.standard_normal(20000) * 10.0 ** g.uniform(-9, 5, 20000),
+                        [0.0, 65504.0, 65519.9, 65520.0, 1e6, -1e6, 2.0 ** -24, 2.0 ** -25,
+                         1.5 * 2.0 ** -25, 2.0 ** -14, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11]])
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).astype(np.float64)
+    assert np.array_equal(oracle.round_to_half(x), ref)
+
+
+def test_mult_mlp_equals_dense_fp64_mlp_on_half_rounded_operands():
+    E, hid, T = 24, 40, 9
+    g = np.random.default_rng(3)
+    x = g.standard_normal((T, E)).astype(np.float32)
+    w1 = (g.standard_normal((hid, E)) / math.sqrt(E)).astype(np.float16)
+    w2 = (g.standard_normal((E, hid)) / math.sqrt(hid)).astype(np.float16)
+    rows = np.array([8, 0, 3], dtype=np.int32)
+    y = oracle.mult_mlp(x, rows, w1, w2)
+    tx = torch.from_numpy(x[rows].astype(np.float16).astype(np.float64))
+    h = torch.nn.functional.gelu(tx @ torch.from_numpy(w1.astype(np.float64)).T)     # erf GELU
+    h = h.numpy().astype(np.float16).astype(np.float64)
+    ref = h @ w2.astype(np.float64).T
+    np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-13)
+    assert y.shape == (3, E)
+    np.testing.assert_allclose(oracle.mult_mlp(x, None, w1, w2)[rows], y, rtol=1e-15)
+
+
+def test_combine_scatters_gated_rows():
+    T, E = 7, 3
+    g = np.random.default_rng(4)
+    out = g.standard_normal((T, E))
+    perm = np.array([1, 4, 6, 0, 2, 3, 5], dtype=np.int32)
+    gate = g.uniform(0.5, 1.0, T)
+    y = oracle.combine(out, perm, gate)
+    ref = np.zeros((T, E))
+    ref[perm] = gate[perm, None] * out
+    np.testing.assert_allclose(y, ref, rtol=1e-15)
+
+
+def test_mlp_stage_composition_all_shift_and_moe():
+    """The composed MLP stage equals its parts chained by hand in numpy index arithmetic."""
+    cfg = wl.scaled_down(wl.C1, N=23)
+    p = wl.mlp_params(cfg)
+    x = wl.float_activations(1, cfg.T, cfg.E)
+    logits = wl.router_logits(cfg)
+    y = oracle.mlp_stage(x, logits, p)
+    perm, expert_of, counts, gate = oracle.moe_dispatch(logits)
+    xq = oracle.quantize_act(x, p.act_inv_scale)
+    for t in range(cfg.T):
+        if expert_of[t] == 1:
+            y2 = oracle.shift_mlp(xq[t:t + 1], p.w1, p.w2, p.requant_scale, p.lut)
+            ref = gate[t] * float(np.float32(p.out_scale)) * y2[0].astype(np.float64)
+        else:
+            ref = gate[t] * oracle.mult_mlp(x[t:t + 1], None, p.mw1, p.mw2)[0]
+        np.testing.assert_allclose(y[t], ref, rtol=1e-13, atol=1e-15)
+    y_all = oracle.mlp_stage(x, None, p)
+    y2 = oracle.shift_mlp(xq, p.w1, p.w2, p.requant_scale, p.lut)
+    np.testing.assert_allclose(y_all, float(np.float32(p.out_scale)) * y2, rtol=1e-15)
