@@ -1,0 +1,222 @@
+/*
+ * libshiftadd - the reparameterised transformer block of ShiftAddViT
+ * (arXiv 2306.06446) as hand-written HIP kernels for AMD gfx950 (MI355X).
+ *
+ * C ABI.  Every pointer named below is a DEVICE pointer unless it says
+ * "host".  The caller owns every buffer; the library never allocates, frees
+ * or keeps a pointer, and never synchronises: all work is enqueued on the
+ * caller's stream (a hipStream_t passed as void*, NULL = the default stream).
+ * Scratch memory comes from a caller-provided workspace whose size the
+ * matching *_workspace_bytes query returns.  Arguments are validated on the
+ * host before anything is launched, so error paths never touch the GPU.
+ *
+ * Every entry point returns SA_OK or a negative SA_ERR_* code; a text for the
+ * most recent error of the calling thread is available from sa_last_error().
+ * All device pointers must be 16-byte aligned (SA_ERR_ALIGN otherwise); row-id
+ * lists need 4-byte alignment only.
+ *
+ * Storage formats
+ *   code words  uint64 [B, H, N, W], W = nbits / 64; bit j of a code is bit
+ *               (j % 64) of word (j / 64), least significant bit first.
+ *               Bit 1 stands for +1, bit 0 for -1.
+ *   activations fp32 [B, N, H, d] (token-major, heads inner), so that
+ *               [B, N, H, dv] is also the [T, E] matrix of the MLP, T = B*N,
+ *               E = H*dv.
+ *   shift weight 4 bits: (neg << 3) | e, the weight is (neg ? -1 : +1) * 2^e,
+ *               e = P + 7 for the paper's exponent P in [-7, 0]; row n of a
+ *               layer holds K/2 bytes, even k in the low nibble.
+ */
+#ifndef SHIFTADD_H_
+#define SHIFTADD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SA_OK 0
+#define SA_ERR_INVALID (-1)     /* null pointer, negative size, bad enum value        */
+#define SA_ERR_SHAPE (-2)       /* a size the operation is not defined for            */
+#define SA_ERR_ALIGN (-3)       /* a pointer that is not 16-byte aligned              */
+#define SA_ERR_WORKSPACE (-4)   /* workspace missing or smaller than the query says   */
+#define SA_ERR_HIP (-5)         /* the HIP runtime refused a launch                   */
+#define SA_ERR_UNSUPPORTED (-6) /* defined, but no kernel is built for this size      */
+
+#define SA_VARIANT_VALU 0 /* shift-and-accumulate on the vector ALU                   */
+#define SA_VARIANT_MFMA 1 /* 4-bit weights decoded to int8, int8 matrix cores         */
+#define SA_VARIANT_AUTO 2 /* the faster of the two for the shape                      */
+
+int sa_version(void);
+/* Host string describing the last error returned on this thread ("" if none). */
+const char *sa_last_error(void);
+
+/*
+ * Hash rows of Q or K to packed binary codes (Sec. 4.1, binary quantisation
+ * of Q and K; appendix, "scaling factor clarification": vanilla sign
+ * quantisation or a set of hash functions).
+ *   proj == NULL : bit j = [x_j >= 0], requires nbits == d
+ *   proj != NULL : bit j = [sum_k x_k * proj[k][j] >= 0], proj fp32 [d, nbits]
+ * The sum is the fp32 chain acc = fma(x_k, proj[k][j], acc), k ascending from
+ * +0.0f; results are bit-exact with that definition.
+ *   x [B,N,H,d] fp32 in;  codes [B,H,N,nbits/64] uint64 out.
+ * nbits % 64 == 0; with proj, d in {32, 64, 128}; without, d % 64 == 0.
+ */
+int sa_binarize(const float *x, int B, int N, int H, int d, const float *proj, int nbits,
+                uint64_t *codes, void *stream);
+
+/*
+ * Linear attention with both MatMuls as Add layers (Eq. 3, O_Add; Sec. 4.1,
+ * order (QK)V -> Q(KV); appendix: the scale is applied after the adds).
+ *   phase 1:  kv[b,h,j,:]  = sum_n sigma(k_codes[b,h,n,j]) * v[b,n,h,:]
+ *   phase 2:  out[b,n,h,:] = scale * sum_j sigma(q_codes[b,h,n,j]) * kv[b,h,j,:]
+ * phases: 1 = phase 1 only, 2 = phase 2 only (kv is an input), 3 = both.
+ *   q_codes [B,H,Nq,W], k_codes [B,H,Nk,W], v [B,Nk,H,dv], out [B,Nq,H,dv],
+ *   kv [B,H,nbits,dv] fp32.  dv in {32, 64, 128}.
+ * Sums are fp32, in a fixed order (results are reproducible run to run).
+ */
+size_t sa_additive_attention_workspace_bytes(int B, int H, int Nk, int nbits, int dv);
+int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
+                          float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
+                          float scale, float *kv, int phases, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
+ * Quadratic attention on codes (Eq. 1 with Q K^T replaced by the Hamming
+ * similarity S[i,j] = nbits - 2 * popcount(q_i xor k_j) of the codes):
+ *   out[b,i,h,:] = sum_j softmax_j(scale * S[i,j]) * v[b,j,h,:]
+ * scores_or_null: if not NULL, S is also written as int16 [B,H,Nq,Nk]
+ * (bit-exact).  dv in {32, 64, 128}; fp32 softmax and accumulation.
+ */
+int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
+                         float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
+                         float scale, int16_t *scores_or_null, void *stream);
+
+/*
+ * Shift layer (Eq. 3, O_Shift = sum X * s * 2^P) on int8 activations with
+ * int32 accumulation:  y[m,n] = bias[n] + sum_k s[n,k] * (x[m,k] << e[n,k]).
+ *   x [M,K] int8, w4 [N,K/2] packed 4-bit, bias [N] int32 or NULL, y [M,N] int32.
+ * K % 32 == 0 (16-byte weight rows); the MFMA variant needs K % 64 == 0 (AUTO
+ * falls back to VALU).
+ * Both variants are bit-exact.
+ */
+int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t *bias_or_null, int32_t *y,
+                    long M, int K, int N, int variant, void *stream);
+
+/*
+ * Top-1 routing (Sec. 4.2: p = softmax(logits), G(x) = p_i * 1{p_i >= p_j}).
+ * Expert 0 = Mult, expert 1 = Shift.  The decision compares raw logits; ties
+ * go to the lowest index.  2 <= E <= 8.
+ *   logits [T,E] fp32 in
+ *   perm [T]      token ids, expert 0's in ascending order, then expert 1's, ...
+ *   expert_of [T] chosen expert per token
+ *   counts [E]    tokens per expert (device memory, like the others)
+ *   gate [T]      softmax probability of the chosen expert, fp32
+ */
+size_t sa_moe_dispatch_workspace_bytes(long T, int E);
+int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
+                    int32_t *counts, float *gate, void *workspace, size_t workspace_bytes,
+                    void *stream);
+
+/*
+ * Activation quantisation with a static per-tensor scale (appendix,
+ * integer-arithmetic quantisation):  q = clamp(rne(x * inv_scale), -127, 127),
+ * NaN -> 0.  One fp32 multiply and one round-to-nearest-even; bit-exact.
+ */
+int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *stream);
+
+/*
+ * Between the two shift linears of the Shift expert:
+ *   h = lut[clamp(rne(float(y) * s), -127, 127) + 128],  lut int8 [256].
+ */
+int sa_requant_lut(const int32_t *y, long n, float s, const int8_t *lut, int8_t *h, void *stream);
+
+/*
+ * Row selection.  Several calls below work on a subset of the rows of a
+ * [T, E] matrix.  rows_or_null lists the row ids (NULL = rows 0..max_rows-1).
+ * If counts_or_null is not NULL the list is expert `expert`'s segment of a
+ * dispatch result: rows = perm + sum(counts[0..expert-1]) and the number of
+ * rows is counts[expert], both read on the device (no host round trip);
+ * max_rows then only bounds the launch and the compact outputs.
+ */
+typedef struct sa_rows {
+    const int32_t *rows_or_null;   /* [max_rows] row ids, or perm [T] with counts  */
+    const int32_t *counts_or_null; /* [E] device, from sa_moe_dispatch             */
+    int expert;                    /* which segment, with counts                   */
+    long max_rows;                 /* upper bound on the rows processed            */
+} sa_rows;
+
+/*
+ * Shift expert (Sec. 4.2, the Shift expert; Sec. 4.1, MLPs as shift layers):
+ *   h  = lut[requant(shift_linear(xq[rows], w1), requant_scale)]
+ *   y2 = shift_linear(h, w2)                                     (int32, exact)
+ * Outputs, either or both:
+ *   y2_or_null  int32 [max_rows, E], row i belongs to rows[i]
+ *   y_or_null   fp32 [T, E]:  y[rows[i], :] = gate[rows[i]] * out_scale * y2[i, :]
+ *               (gate_or_null == NULL stands for gate 1)
+ *   xq [T,E] int8, w1 [hid, E/2], w2 [E, hid/2], lut int8 [256].
+ * Workspace holds the int8 hidden rows.  E % 64 == 0 and hid % 64 == 0.
+ */
+size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid);
+int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const uint8_t *w1,
+                 const uint8_t *w2, float requant_scale, const int8_t *lut, int32_t *y2_or_null,
+                 float *y_or_null, const float *gate_or_null, float out_scale, int variant,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Mult expert (Sec. 4.2): a dense two-layer MLP with erf-GELU in fp16 with
+ * fp32 accumulation.  x rows and the hidden activation are rounded to fp16.
+ *   out = W2 * half(gelu(W1 * half(x[rows])))      W1 [hid,E], W2 [E,hid] fp16
+ * Outputs as for sa_shift_mlp: out_or_null fp32 [max_rows, E] and / or
+ * y_or_null fp32 [T, E] with y[rows[i], :] = gate[rows[i]] * out[i, :].
+ * E % 32 == 0 and hid % 32 == 0.
+ */
+size_t sa_mult_mlp_workspace_bytes(long max_rows, int E, int hid);
+int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const void *w1_f16,
+                    const void *w2_f16, float *out_or_null, float *y_or_null,
+                    const float *gate_or_null, void *workspace, size_t workspace_bytes,
+                    void *stream);
+
+/* Plain row movement (Sec. 4.2, y = sum_i G(x) * E_i(x) with one non-zero term):
+ *   gather : dst[i, :] = src[rows[i], :]                 (row_bytes % 16 == 0)
+ *   combine: y[rows[i], :] = gate[rows[i]] * src[i, :]   (fp32, width E)      */
+int sa_gather_rows(const void *src, size_t row_bytes, const sa_rows *rows, void *dst,
+                   void *stream);
+int sa_combine_rows(const float *src, const sa_rows *rows, const float *gate_or_null, int E,
+                    float *y, void *stream);
+
+/*
+ * One pass of the block (Eq. 2 restricted to the reparameterised parts):
+ *   codes = binarize(Q), binarize(K)
+ *   O     = additive attention (linear) or Hamming attention (quadratic)
+ *   y     = MoE{Mult, Shift}(O) with top-1 dispatch, or Shift MLP(O) if no router
+ * Q, K, V enter as fp32 [B,N,H,d] / [B,N,H,dv]; O [B,N,H,dv] = [T,E] and
+ * y [T,E] leave as fp32.  All kernels are enqueued on one stream.
+ */
+typedef struct sa_block_desc {
+    int B, N, H, d, nbits, dv;
+    int attention;          /* 0 = linear additive, 1 = quadratic Hamming            */
+    int hid;                /* MLP hidden width; 0 = attention only                  */
+    int moe;                /* 1 = router + two experts, 0 = Shift MLP for all rows  */
+    int shift_variant;      /* SA_VARIANT_*                                          */
+    float attn_scale, act_inv_scale, requant_scale, out_scale;
+    const float *q, *k, *v; /* inputs                                                */
+    const float *proj;      /* [d, nbits] or NULL                                    */
+    const float *logits;    /* [T, 2] router logits (moe == 1)                       */
+    const uint8_t *w1, *w2; /* Shift expert, packed 4-bit                            */
+    const int8_t *lut;      /* [256]                                                 */
+    const void *mw1, *mw2;  /* Mult expert fp16 (moe == 1)                           */
+    float *o;               /* [T, E] attention output                               */
+    float *y;               /* [T, E] block output (hid > 0)                         */
+    void *workspace;
+    size_t workspace_bytes;
+} sa_block_desc;
+
+size_t sa_block_workspace_bytes(const sa_block_desc *desc /* host */);
+int sa_block_forward(const sa_block_desc *desc /* host */, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHIFTADD_H_ */

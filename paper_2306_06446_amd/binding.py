@@ -1,0 +1,267 @@
+"""ctypes binding of libshiftadd.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch supplies device memory and the
+stream, nothing else); every step of the path runs in the library's kernels.
+A missing library is an error: there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshiftadd.so")
+_lib = None
+
+SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO = 0, 1, 2
+
+EXPORTS = [
+    "sa_version", "sa_last_error", "sa_binarize", "sa_additive_attention_workspace_bytes",
+    "sa_additive_attention", "sa_hamming_attention", "sa_shift_linear",
+    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_requant_lut",
+    "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
+    "sa_mult_mlp_f16", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
+    "sa_block_forward",
+]
+
+
+class SAError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libshiftadd error %d: %s" % (code, text))
+        self.code = code
+
+
+class SaRows(ctypes.Structure):
+    _fields_ = [("rows_or_null", ctypes.c_void_p), ("counts_or_null", ctypes.c_void_p),
+                ("expert", ctypes.c_int), ("max_rows", ctypes.c_long)]
+
+
+class SaBlockDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("B", "N", "H", "d", "nbits", "dv", "attention", "hid", "moe", "shift_variant")] + \
+               [(n, ctypes.c_float) for n in
+                ("attn_scale", "act_inv_scale", "requant_scale", "out_scale")] + \
+               [(n, ctypes.c_void_p) for n in
+                ("q", "k", "v", "proj", "logits", "w1", "w2", "lut", "mw1", "mw2", "o", "y",
+                 "workspace")] + \
+               [("workspace_bytes", ctypes.c_size_t)]
+
+
+def load_library():
+    """Load the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libshiftadd.so is not built (%s): run `python -c 'import __graft_entry__ as g; "
+                "g.build()'` first; there is no fallback path" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.sa_last_error.restype = ctypes.c_char_p
+        for name in ("sa_additive_attention_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
+                     "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
+                     "sa_block_workspace_bytes"):
+            getattr(lib, name).restype = ctypes.c_size_t
+        _lib = lib
+    return _lib
+
+
+def _check(code):
+    if code != 0:
+        raise SAError(code, load_library().sa_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return ctypes.c_void_p(None)
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _f(x):
+    return ctypes.c_float(x)
+
+
+def _l(x):
+    return ctypes.c_long(x)
+
+
+def _z(x):
+    return ctypes.c_size_t(x)
+
+
+def _rows(rows=None, counts=None, expert=0, max_rows=0):
+    return SaRows(None if rows is None else rows.data_ptr(),
+                  None if counts is None else counts.data_ptr(), expert, max_rows)
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def sa_version():
+    return load_library().sa_version()
+
+
+def sa_binarize(x, proj, nbits, codes=None):
+    B, N, H, d = x.shape
+    if codes is None:
+        codes = torch.empty((B, H, N, nbits // 64), dtype=torch.int64, device=x.device)
+    _check(load_library().sa_binarize(_ptr(x), B, N, H, d, _ptr(proj), nbits, _ptr(codes), _stream()))
+    return codes
+
+
+def sa_additive_attention(q_codes, k_codes, v, scale, nbits, phases=3, kv=None, out=None,
+                          workspace=None):
+    lib = load_library()
+    B, H, Nq, W = q_codes.shape if q_codes is not None else k_codes.shape
+    Nk = k_codes.shape[2] if k_codes is not None else 0
+    dv = v.shape[3] if v is not None else kv.shape[3]
+    dev = (v if v is not None else kv).device
+    if kv is None:
+        kv = torch.empty((B, H, nbits, dv), dtype=torch.float32, device=dev)
+    if out is None and (phases & 2):
+        out = torch.empty((B, Nq, H, dv), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib.sa_additive_attention_workspace_bytes(B, H, Nk, nbits, dv), dev)
+    _check(lib.sa_additive_attention(_ptr(q_codes), _ptr(k_codes), _ptr(v), _ptr(out), B, H, Nq, Nk,
+                                     nbits, dv, _f(scale), _ptr(kv), phases, _ptr(workspace),
+                                     _z(workspace.numel()), _stream()))
+    return out, kv
+
+
+def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, out=None):
+    B, H, Nq, W = q_codes.shape
+    Nk = k_codes.shape[2]
+    dv = v.shape[3]
+    if out is None:
+        out = torch.empty((B, Nq, H, dv), dtype=torch.float32, device=v.device)
+    scores = torch.empty((B, H, Nq, Nk), dtype=torch.int16, device=v.device) if want_scores else None
+    _check(load_library().sa_hamming_attention(_ptr(q_codes), _ptr(k_codes), _ptr(v), _ptr(out), B, H,
+                                               Nq, Nk, nbits, dv, _f(scale), _ptr(scores), _stream()))
+    return (out, scores) if want_scores else out
+
+
+def sa_shift_linear(x, w4, bias=None, variant=SA_VARIANT_AUTO, y=None):
+    M, K = x.shape
+    N = w4.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.int32, device=x.device)
+    _check(load_library().sa_shift_linear(_ptr(x), _ptr(w4), _ptr(bias), _ptr(y), _l(M), K, N, variant,
+                                          _stream()))
+    return y
+
+
+def sa_moe_dispatch(logits):
+    lib = load_library()
+    T, E = logits.shape
+    dev = logits.device
+    perm = torch.empty(T, dtype=torch.int32, device=dev)
+    expert_of = torch.empty(T, dtype=torch.int32, device=dev)
+    counts = torch.empty(max(E, 4), dtype=torch.int32, device=dev)[:E]
+    gate = torch.empty(T, dtype=torch.float32, device=dev)
+    ws = _workspace(lib.sa_moe_dispatch_workspace_bytes(_l(T), E), dev)
+    _check(lib.sa_moe_dispatch(_ptr(logits), _l(T), E, _ptr(perm), _ptr(expert_of), _ptr(counts),
+                               _ptr(gate), _ptr(ws), _z(ws.numel()), _stream()))
+    return perm, expert_of, counts, gate
+
+
+def sa_quantize_act(x, inv_scale, q=None):
+    if q is None:
+        q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(load_library().sa_quantize_act(_ptr(x), _l(x.numel()), _f(inv_scale), _ptr(q), _stream()))
+    return q
+
+
+def sa_requant_lut(y, s, lut, h=None):
+    if h is None:
+        h = torch.empty(y.shape, dtype=torch.int8, device=y.device)
+    _check(load_library().sa_requant_lut(_ptr(y), _l(y.numel()), _f(s), _ptr(lut), _ptr(h), _stream()))
+    return h
+
+
+def sa_shift_mlp(xq, w1, w2, requant_scale, lut, rows=None, counts=None, expert=0, max_rows=None,
+                 want_y2=True, y=None, gate=None, out_scale=1.0, variant=SA_VARIANT_AUTO):
+    lib = load_library()
+    T, E = xq.shape
+    hid = w1.shape[0]
+    if max_rows is None:
+        max_rows = T if rows is None or counts is not None else rows.numel()
+    r = _rows(rows, counts, expert, max_rows)
+    y2 = torch.empty((max_rows, E), dtype=torch.int32, device=xq.device) if want_y2 else None
+    ws = _workspace(lib.sa_shift_mlp_workspace_bytes(_l(max_rows), E, hid), xq.device)
+    _check(lib.sa_shift_mlp(_ptr(xq), ctypes.byref(r), E, hid, _ptr(w1), _ptr(w2), _f(requant_scale),
+                            _ptr(lut), _ptr(y2), _ptr(y), _ptr(gate), _f(out_scale), variant, _ptr(ws),
+                            _z(ws.numel()), _stream()))
+    return y2
+
+
+def sa_mult_mlp_f16(x, w1, w2, rows=None, counts=None, expert=0, max_rows=None, want_out=True,
+                    y=None, gate=None):
+    lib = load_library()
+    T, E = x.shape
+    hid = w1.shape[0]
+    if max_rows is None:
+        max_rows = T if rows is None or counts is not None else rows.numel()
+    r = _rows(rows, counts, expert, max_rows)
+    out = torch.empty((max_rows, E), dtype=torch.float32, device=x.device) if want_out else None
+    ws = _workspace(lib.sa_mult_mlp_workspace_bytes(_l(max_rows), E, hid), x.device)
+    _check(lib.sa_mult_mlp_f16(_ptr(x), ctypes.byref(r), E, hid, _ptr(w1), _ptr(w2), _ptr(out), _ptr(y),
+                               _ptr(gate), _ptr(ws), _z(ws.numel()), _stream()))
+    return out
+
+
+def sa_gather_rows(src, rows=None, counts=None, expert=0, max_rows=None):
+    if max_rows is None:
+        max_rows = rows.numel()
+    r = _rows(rows, counts, expert, max_rows)
+    dst = torch.zeros((max_rows,) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
+    row_bytes = src[0].numel() * src.element_size()
+    _check(load_library().sa_gather_rows(_ptr(src), _z(row_bytes), ctypes.byref(r), _ptr(dst), _stream()))
+    return dst
+
+
+def sa_combine_rows(src, y, rows=None, counts=None, expert=0, max_rows=None, gate=None):
+    if max_rows is None:
+        max_rows = src.shape[0]
+    r = _rows(rows, counts, expert, max_rows)
+    _check(load_library().sa_combine_rows(_ptr(src), ctypes.byref(r), _ptr(gate), src.shape[1], _ptr(y),
+                                          _stream()))
+    return y
+
+
+class Block:
+    """Holds the descriptor and the workspace of one block configuration; forward() enqueues it."""
+
+    def __init__(self, *, B, N, H, d, nbits, dv, attention, hid, moe, attn_scale, act_inv_scale=1.0,
+                 requant_scale=1.0, out_scale=1.0, q, k, v, proj, logits=None, w1=None, w2=None,
+                 lut=None, mw1=None, mw2=None, shift_variant=SA_VARIANT_AUTO):
+        lib = load_library()
+        dev = q.device
+        T, E = B * N, H * dv
+        self.o = torch.empty((B, N, H, dv), dtype=torch.float32, device=dev)
+        self.y = torch.empty((T, E), dtype=torch.float32, device=dev) if hid else None
+        self._keep = (q, k, v, proj, logits, w1, w2, lut, mw1, mw2)
+        d_ = SaBlockDesc()
+        d_.B, d_.N, d_.H, d_.d, d_.nbits, d_.dv = B, N, H, d, nbits, dv
+        d_.attention, d_.hid, d_.moe, d_.shift_variant = attention, hid, int(moe), shift_variant
+        d_.attn_scale, d_.act_inv_scale = attn_scale, act_inv_scale
+        d_.requant_scale, d_.out_scale = requant_scale, out_scale
+        for name, t in (("q", q), ("k", k), ("v", v), ("proj", proj), ("logits", logits), ("w1", w1),
+                        ("w2", w2), ("lut", lut), ("mw1", mw1), ("mw2", mw2), ("o", self.o),
+                        ("y", self.y)):
+            setattr(d_, name, None if t is None else t.data_ptr())
+        nbytes = lib.sa_block_workspace_bytes(ctypes.byref(d_))
+        self.ws = _workspace(nbytes, dev)
+        d_.workspace = self.ws.data_ptr()
+        d_.workspace_bytes = self.ws.numel()
+        self.desc = d_
+
+    def forward(self):
+        _check(load_library().sa_block_forward(ctypes.byref(self.desc), _stream()))
+        return self.o, self.y

@@ -1,0 +1,117 @@
+// sa_block_forward: one pass of the reparameterised block (Eq. 2 restricted to the
+// attention MatMuls and the MLP): hash Q and K, additive or Hamming attention, then the
+// Shift MLP or the two-expert MoE.  Pure composition of the library's own entry points
+// on one stream; the expert row counts stay on the device (no host round trip).
+#include "common.h"
+
+namespace {
+
+struct Layout {
+    size_t qc, kc, kv, attn_ws, xq, perm, expert_of, counts, gate, disp_ws, shift_ws, mult_ws, total;
+    size_t attn_ws_bytes, disp_ws_bytes, shift_ws_bytes, mult_ws_bytes;
+};
+
+size_t up(size_t x) { return (x + 255) / 256 * 256; }
+
+int plan(const sa_block_desc *d, Layout *L) {
+    SA_REQUIRE(d != nullptr, SA_ERR_INVALID, "block: descriptor is NULL");
+    SA_REQUIRE(d->B > 0 && d->N > 0 && d->H > 0 && d->d > 0 && d->nbits > 0 && d->dv > 0, SA_ERR_INVALID,
+               "block: sizes must be positive");
+    SA_REQUIRE(d->nbits % 64 == 0, SA_ERR_SHAPE, "block: nbits must be a multiple of 64");
+    SA_REQUIRE(d->attention == 0 || d->attention == 1, SA_ERR_INVALID, "block: attention must be 0 or 1");
+    SA_REQUIRE(d->hid >= 0, SA_ERR_INVALID, "block: hid < 0");
+    const size_t T = (size_t)d->B * d->N, E = (size_t)d->H * d->dv;
+    SA_REQUIRE(T < (1ull << 31), SA_ERR_SHAPE, "block: too many tokens");
+    size_t off = 0;
+    const size_t code_bytes = up((size_t)d->B * d->H * d->N * (d->nbits / 64) * 8);
+    L->qc = off; off += code_bytes;
+    L->kc = off; off += code_bytes;
+    L->kv = off;
+    L->attn_ws_bytes = 0;
+    if (d->attention == 0) {
+        off += up((size_t)d->B * d->H * d->nbits * d->dv * 4);
+        L->attn_ws_bytes = sa_additive_attention_workspace_bytes(d->B, d->H, d->N, d->nbits, d->dv);
+    }
+    L->attn_ws = off; off += up(L->attn_ws_bytes);
+    L->xq = off;
+    L->disp_ws_bytes = L->shift_ws_bytes = L->mult_ws_bytes = 0;
+    L->perm = L->expert_of = L->counts = L->gate = L->disp_ws = L->shift_ws = L->mult_ws = off;
+    if (d->hid > 0) {
+        off += up(T * E);
+        L->shift_ws_bytes = sa_shift_mlp_workspace_bytes((long)T, (int)E, d->hid);
+        L->shift_ws = off; off += up(L->shift_ws_bytes);
+        if (d->moe) {
+            L->perm = off; off += up(T * 4);
+            L->expert_of = off; off += up(T * 4);
+            L->counts = off; off += 256;
+            L->gate = off; off += up(T * 4);
+            L->disp_ws_bytes = sa_moe_dispatch_workspace_bytes((long)T, 2);
+            L->disp_ws = off; off += up(L->disp_ws_bytes);
+            L->mult_ws_bytes = sa_mult_mlp_workspace_bytes((long)T, (int)E, d->hid);
+            L->mult_ws = off; off += up(L->mult_ws_bytes);
+        }
+    }
+    L->total = off;
+    return SA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t sa_block_workspace_bytes(const sa_block_desc *desc) {
+    Layout L;
+    if (plan(desc, &L) != SA_OK) return 0;
+    return L.total;
+}
+
+extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
+    sa::clear_error();
+    Layout L;
+    int rc = plan(d, &L);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(d->q && d->k && d->v && d->o, SA_ERR_INVALID, "block: q, k, v and o are required");
+    SA_REQUIRE(d->workspace != nullptr && d->workspace_bytes >= L.total, SA_ERR_WORKSPACE,
+               "block: workspace of %zu bytes needed, %zu given", L.total, d->workspace_bytes);
+    SA_REQUIRE(sa::aligned16(d->workspace), SA_ERR_ALIGN, "block: workspace must be 16-byte aligned");
+    if (d->hid > 0) {
+        SA_REQUIRE(d->w1 && d->w2 && d->lut && d->y, SA_ERR_INVALID, "block: w1, w2, lut and y are required");
+        if (d->moe) SA_REQUIRE(d->logits && d->mw1 && d->mw2, SA_ERR_INVALID, "block: logits, mw1, mw2 are required");
+    }
+    uint8_t *ws = static_cast<uint8_t *>(d->workspace);
+    uint64_t *qc = reinterpret_cast<uint64_t *>(ws + L.qc), *kc = reinterpret_cast<uint64_t *>(ws + L.kc);
+    const long T = (long)d->B * d->N;
+    const int E = d->H * d->dv;
+
+    rc = sa_binarize(d->q, d->B, d->N, d->H, d->d, d->proj, d->nbits, qc, stream);
+    if (rc != SA_OK) return rc;
+    rc = sa_binarize(d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, kc, stream);
+    if (rc != SA_OK) return rc;
+    if (d->attention == 0) {
+        rc = sa_additive_attention(qc, kc, d->v, d->o, d->B, d->H, d->N, d->N, d->nbits, d->dv, d->attn_scale,
+                                   reinterpret_cast<float *>(ws + L.kv), 3, ws + L.attn_ws, L.attn_ws_bytes, stream);
+    } else {
+        rc = sa_hamming_attention(qc, kc, d->v, d->o, d->B, d->H, d->N, d->N, d->nbits, d->dv, d->attn_scale,
+                                  nullptr, stream);
+    }
+    if (rc != SA_OK || d->hid == 0) return rc;
+
+    int8_t *xq = reinterpret_cast<int8_t *>(ws + L.xq);
+    rc = sa_quantize_act(d->o, T * E, d->act_inv_scale, xq, stream);
+    if (rc != SA_OK) return rc;
+    if (!d->moe) {
+        const sa_rows all{nullptr, nullptr, 0, T};
+        return sa_shift_mlp(xq, &all, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, nullptr,
+                            d->out_scale, d->shift_variant, ws + L.shift_ws, L.shift_ws_bytes, stream);
+    }
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
+    int32_t *expert_of = reinterpret_cast<int32_t *>(ws + L.expert_of);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
+    float *gate = reinterpret_cast<float *>(ws + L.gate);
+    rc = sa_moe_dispatch(d->logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes, stream);
+    if (rc != SA_OK) return rc;
+    const sa_rows mult_rows{perm, counts, 0, T}, shift_rows{perm, counts, 1, T};
+    rc = sa_mult_mlp_f16(d->o, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, ws + L.mult_ws,
+                         L.mult_ws_bytes, stream);
+    if (rc != SA_OK) return rc;
+    return sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
+                        d->out_scale, d->shift_variant, ws + L.shift_ws, L.shift_ws_bytes, stream);
+}

@@ -1,0 +1,56 @@
+// Internal helpers of libshiftadd (host-side validation, error text, launch checks).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "shiftadd.h"
+
+namespace sa {
+
+// Records a message for sa_last_error() and returns `code`.
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+// Turns the status of the launch just issued into an SA code.
+int check_launch(const char *what);
+
+// Zero-fills `bytes` (a multiple of 4) with a kernel (safe under graph capture).
+int launch_zero(void *p, size_t bytes, hipStream_t st);
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+constexpr int kWave = 64;
+
+// Resolves an sa_rows descriptor inside a kernel (all lanes get the same values).
+struct RowSel {
+    const int32_t *rows;    // may be null: identity
+    const int32_t *counts;  // may be null: n_rows = max_rows
+    int expert;
+    long max_rows;
+};
+
+__device__ inline void resolve_rows(const RowSel &sel, const int32_t *&rows, long &n_rows) {
+    rows = sel.rows;
+    n_rows = sel.max_rows;
+    if (sel.counts != nullptr) {
+        long off = 0;
+        for (int e = 0; e < sel.expert; ++e) off += sel.counts[e];
+        long cnt = sel.counts[sel.expert];
+        rows = sel.rows + off;
+        n_rows = cnt < sel.max_rows ? cnt : sel.max_rows;
+    }
+}
+
+int validate_rows(const sa_rows *rows, RowSel *out);
+
+}  // namespace sa
+
+#define SA_REQUIRE(cond, code, ...) \
+    do {                            \
+        if (!(cond)) return ::sa::fail((code), __VA_ARGS__); \
+    } while (0)

@@ -1,0 +1,42 @@
+// Shared pieces of the two matrix-core kernels (int8 shift expert, fp16 Mult expert):
+// the output-side epilogues and the accumulator-to-coordinate map of a 32x32 MFMA tile.
+#pragma once
+
+#include "common.h"
+
+namespace sa {
+
+enum EpiMode : int {
+    kEpiInt32 = 0,     // y[m, n] = acc (+ bias[n])                              int32
+    kEpiRequantLut,    // h[m, n] = lut[clamp(rne(float(acc) * rq)) + 128]        int8
+    kEpiScatterI32,    // yf[rows[m], n] = gate[rows[m]] * (out_scale * float(acc))
+    kEpiFloat,         // of[m, n] = acc                                          fp32
+    kEpiGeluHalf,      // hh[m, n] = half(gelu(acc))                              fp16
+    kEpiScatterF32,    // yf[rows[m], n] = gate[rows[m]] * acc
+};
+
+struct Epilogue {
+    int32_t *y = nullptr;          // compact int32 out [max_rows, N]
+    const int32_t *bias = nullptr;
+    int8_t *h = nullptr;           // compact int8 out
+    float rq = 1.0f;
+    const int8_t *lut = nullptr;
+    float *yf = nullptr;           // scattered fp32 out [T, N]
+    const float *gate = nullptr;
+    float out_scale = 1.0f;
+    float *of = nullptr;           // compact fp32 out
+    _Float16 *hh = nullptr;        // compact fp16 out
+};
+
+__device__ inline int8_t requant_code(float t) {
+    // clamp(rne(t), -127, 127), NaN -> 0; t is the already rounded fp32 product
+    t = __builtin_rintf(t);
+    t = t < -127.0f ? -127.0f : t;
+    t = t > 127.0f ? 127.0f : t;
+    return (t != t) ? (int8_t)0 : (int8_t)t;
+}
+
+// Row of the 32x32 accumulator tile that register r of lane `lane` holds; the column is lane % 32.
+__device__ inline int mfma32_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+}  // namespace sa

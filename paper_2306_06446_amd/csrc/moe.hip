@@ -1,0 +1,199 @@
+// sa_moe_dispatch, sa_gather_rows, sa_combine_rows: top-1 routing between the Mult and
+// the Shift expert (Sec. 4.2: p = softmax(router logits), G(x) = p_i * 1{p_i >= p_j}).
+//
+// Dispatch is a stable partition of the token ids by expert, built without atomics so
+// that the lists are unique and reproducible: (1) every workgroup of 256 tokens takes
+// the decisions (raw-logit argmax, ties to the lowest index), the gate values and its
+// per-expert histogram; (2) one small workgroup turns the histograms into start offsets;
+// (3) every workgroup ranks its tokens with wavefront ballots / popcounts and writes them.
+#include "common.h"
+
+namespace {
+
+using namespace sa;
+constexpr int kMaxE = 8;
+constexpr int kTok = 256;   // tokens per workgroup
+
+__device__ inline uint64_t lanemask_lt(int lane) { return (lane == 0) ? 0ull : (~0ull >> (64 - lane)); }
+
+__global__ __launch_bounds__(kTok) void route_kernel(const float *__restrict__ logits, long T, int E,
+                                                     int32_t *__restrict__ expert_of,
+                                                     float *__restrict__ gate,
+                                                     int32_t *__restrict__ block_counts) {
+    __shared__ int32_t wave_cnt[kTok / 64][kMaxE];
+    const long t = (long)blockIdx.x * kTok + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int best = -1;
+    if (t < T) {
+        const float *l = logits + (size_t)t * E;
+        best = 0;
+        float lb = l[0];
+        for (int e = 1; e < E; ++e) {
+            const float le = l[e];
+            if (le > lb) { lb = le; best = e; }
+        }
+        float den = 0.0f;
+        for (int e = 0; e < E; ++e) den += __expf(l[e] - lb);
+        expert_of[t] = best;
+        gate[t] = 1.0f / den;
+    }
+    for (int e = 0; e < E; ++e) {
+        const uint64_t m = __ballot(best == e);
+        if (lane == 0) wave_cnt[wave][e] = __builtin_popcountll(m);
+    }
+    __syncthreads();
+    if (threadIdx.x < E) {
+        int s = 0;
+        for (int w = 0; w < kTok / 64; ++w) s += wave_cnt[w][threadIdx.x];
+        block_counts[(size_t)blockIdx.x * E + threadIdx.x] = s;
+    }
+}
+
+// block_base[blk][e] = first position in perm of expert e's tokens of workgroup blk.
+__global__ __launch_bounds__(64) void offsets_kernel(const int32_t *__restrict__ block_counts,
+                                                     int32_t *__restrict__ block_base,
+                                                     int32_t *__restrict__ counts, long n_blocks, int E) {
+    __shared__ int32_t total[kMaxE];
+    const int e = threadIdx.x;
+    if (e < E) {
+        int s = 0;
+        for (long b = 0; b < n_blocks; ++b) s += block_counts[(size_t)b * E + e];
+        total[e] = s;
+        counts[e] = s;
+    }
+    __syncthreads();
+    if (e < E) {
+        int start = 0;
+        for (int i = 0; i < e; ++i) start += total[i];
+        for (long b = 0; b < n_blocks; ++b) {
+            block_base[(size_t)b * E + e] = start;
+            start += block_counts[(size_t)b * E + e];
+        }
+    }
+}
+
+__global__ __launch_bounds__(kTok) void scatter_kernel(const int32_t *__restrict__ expert_of, long T, int E,
+                                                       const int32_t *__restrict__ block_base,
+                                                       int32_t *__restrict__ perm) {
+    __shared__ int32_t wave_cnt[kTok / 64][kMaxE];
+    const long t = (long)blockIdx.x * kTok + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int mine = (t < T) ? expert_of[t] : -1;
+    int rank = 0;
+    for (int e = 0; e < E; ++e) {
+        const uint64_t m = __ballot(mine == e);
+        if (mine == e) rank = __builtin_popcountll(m & lanemask_lt(lane));
+        if (lane == 0) wave_cnt[wave][e] = __builtin_popcountll(m);
+    }
+    __syncthreads();
+    if (mine >= 0) {
+        int before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_cnt[w][mine];
+        perm[block_base[(size_t)blockIdx.x * E + mine] + before + rank] = (int32_t)t;
+    }
+}
+
+__global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ src, int chunks_per_row,
+                                                     RowSel sel, uint4 *__restrict__ dst) {
+    const int32_t *rows;
+    long n_rows;
+    resolve_rows(sel, rows, n_rows);
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long i = idx / chunks_per_row;
+    const int c = (int)(idx % chunks_per_row);
+    if (i >= n_rows) return;
+    const long s = rows ? rows[i] : i;
+    dst[(size_t)i * chunks_per_row + c] = src[(size_t)s * chunks_per_row + c];
+}
+
+__global__ __launch_bounds__(256) void combine_kernel(const float4 *__restrict__ src, int E4, RowSel sel,
+                                                      const float *__restrict__ gate,
+                                                      float4 *__restrict__ y) {
+    const int32_t *rows;
+    long n_rows;
+    resolve_rows(sel, rows, n_rows);
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long i = idx / E4;
+    const int c = (int)(idx % E4);
+    if (i >= n_rows) return;
+    const long t = rows ? rows[i] : i;
+    const float g = gate ? gate[t] : 1.0f;
+    const float4 v = src[(size_t)i * E4 + c];
+    y[(size_t)t * E4 + c] = make_float4(g * v.x, g * v.y, g * v.z, g * v.w);
+}
+
+}  // namespace
+
+extern "C" size_t sa_moe_dispatch_workspace_bytes(long T, int E) {
+    if (T <= 0 || E <= 0) return 0;
+    const size_t n_blocks = (size_t)((T + kTok - 1) / kTok);
+    return (2 * n_blocks * E * sizeof(int32_t) + 255) / 256 * 256;
+}
+
+extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
+                               int32_t *counts, float *gate, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(T >= 0, SA_ERR_INVALID, "sa_moe_dispatch: T < 0");
+    SA_REQUIRE(E >= 2 && E <= kMaxE, SA_ERR_SHAPE, "sa_moe_dispatch: E must be in [2, %d] (got %d)", kMaxE, E);
+    SA_REQUIRE(T < (1L << 31), SA_ERR_SHAPE, "sa_moe_dispatch: T >= 2^31");
+    SA_REQUIRE(counts != nullptr, SA_ERR_INVALID, "sa_moe_dispatch: counts is NULL");
+    SA_REQUIRE(sa::aligned16(logits) && sa::aligned16(perm) && sa::aligned16(expert_of) &&
+                   sa::aligned16(counts) && sa::aligned16(gate) && sa::aligned16(workspace),
+               SA_ERR_ALIGN, "sa_moe_dispatch: pointers must be 16-byte aligned");
+    hipStream_t st = sa::as_stream(stream);
+    if (T == 0) return sa::launch_zero(counts, ((size_t)E * 4 + 3) / 4 * 4, st);
+    SA_REQUIRE(logits && perm && expert_of && gate, SA_ERR_INVALID, "sa_moe_dispatch: NULL buffer");
+    const size_t need = sa_moe_dispatch_workspace_bytes(T, E);
+    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
+               "sa_moe_dispatch: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    const long n_blocks = (T + kTok - 1) / kTok;
+    int32_t *block_counts = static_cast<int32_t *>(workspace);
+    int32_t *block_base = block_counts + (size_t)n_blocks * E;
+    route_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(logits, T, E, expert_of, gate, block_counts);
+    int rc = sa::check_launch("sa_moe_dispatch(route)");
+    if (rc != SA_OK) return rc;
+    offsets_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, block_base, counts, n_blocks, E);
+    rc = sa::check_launch("sa_moe_dispatch(offsets)");
+    if (rc != SA_OK) return rc;
+    scatter_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(expert_of, T, E, block_base, perm);
+    return sa::check_launch("sa_moe_dispatch(scatter)");
+}
+
+extern "C" int sa_gather_rows(const void *src, size_t row_bytes, const sa_rows *rows, void *dst, void *stream) {
+    sa::clear_error();
+    sa::RowSel sel;
+    int rc = sa::validate_rows(rows, &sel);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(row_bytes > 0 && row_bytes % 16 == 0, SA_ERR_SHAPE, "sa_gather_rows: row_bytes must be a positive multiple of 16");
+    if (sel.max_rows == 0) return SA_OK;
+    SA_REQUIRE(src && dst, SA_ERR_INVALID, "sa_gather_rows: NULL buffer");
+    SA_REQUIRE(sa::aligned16(src) && sa::aligned16(dst) && sa::aligned4(sel.rows), SA_ERR_ALIGN,
+               "sa_gather_rows: pointers must be 16-byte aligned");
+    const int cpr = (int)(row_bytes / 16);
+    const long total = sel.max_rows * cpr;
+    const long blocks = (total + 255) / 256;
+    SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_gather_rows: too large");
+    gather_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(
+        static_cast<const uint4 *>(src), cpr, sel, static_cast<uint4 *>(dst));
+    return sa::check_launch("sa_gather_rows");
+}
+
+extern "C" int sa_combine_rows(const float *src, const sa_rows *rows, const float *gate_or_null, int E,
+                               float *y, void *stream) {
+    sa::clear_error();
+    sa::RowSel sel;
+    int rc = sa::validate_rows(rows, &sel);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(E > 0 && E % 4 == 0, SA_ERR_SHAPE, "sa_combine_rows: E must be a positive multiple of 4");
+    if (sel.max_rows == 0) return SA_OK;
+    SA_REQUIRE(src && y, SA_ERR_INVALID, "sa_combine_rows: NULL buffer");
+    SA_REQUIRE(sa::aligned16(src) && sa::aligned16(y) && sa::aligned16(gate_or_null) && sa::aligned4(sel.rows),
+               SA_ERR_ALIGN, "sa_combine_rows: pointers must be 16-byte aligned");
+    const long total = sel.max_rows * (E / 4);
+    const long blocks = (total + 255) / 256;
+    SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_combine_rows: too large");
+    combine_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(
+        reinterpret_cast<const float4 *>(src), E / 4, sel, gate_or_null, reinterpret_cast<float4 *>(y));
+    return sa::check_launch("sa_combine_rows");
+}

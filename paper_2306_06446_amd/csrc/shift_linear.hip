@@ -1,0 +1,409 @@
+// Shift layers (Eq. 3, O_Shift = sum X * s * 2^P) on int8 activations, int32 accumulation,
+// 4-bit weights (neg << 3) | e with value (neg ? -1 : +1) << e.
+//
+// Two bit-exact variants:
+//   VALU  : true shift-and-accumulate.  -(x << e) = ((~x) << e) + (1 << e), so a
+//           negative weight is "xor the activation with all-ones, shift, add" and
+//           the (1 << e) terms, which depend on the weights only, are summed once
+//           per output column through a virtual all-zero activation row.
+//   MFMA  : the 4-bit weights are decoded on the fly to two int8 planes,
+//           A = s * 2^min(e,6) and B = s * 64 * [e == 7] (+128 is not an int8),
+//           and both planes go through v_mfma_i32_32x32x32_i8 into one accumulator.
+// Both share the epilogues (plain int32, requantise + table, gated fp32 scatter).
+#include "common.h"
+#include "gemm_common.h"
+
+namespace {
+
+using namespace sa;
+
+template <int MODE>
+__device__ inline void epi_store(const Epilogue &e, long m, int n, int N, int32_t acc,
+                                 const int32_t *rows) {
+    if (MODE == kEpiInt32) {
+        e.y[(size_t)m * N + n] = acc + (e.bias ? e.bias[n] : 0);
+    } else if (MODE == kEpiRequantLut) {
+        const float t = (float)acc * e.rq;
+        e.h[(size_t)m * N + n] = e.lut[(int)requant_code(t) + 128];
+    } else {
+        const long t = rows ? rows[m] : m;
+        const float g = e.gate ? e.gate[t] : 1.0f;
+        e.yf[(size_t)t * N + n] = g * (e.out_scale * (float)acc);
+    }
+}
+
+// ------------------------------------------------------------------ VALU variant ----
+// thread <-> output column n; MT activation rows per workgroup pass, their bytes
+// arrive through scalar loads (they are the same for every lane).
+constexpr int kValuRows = 8;
+
+template <int MODE>
+__global__ __launch_bounds__(256) void shift_valu_kernel(const int8_t *__restrict__ x,
+                                                         const uint8_t *__restrict__ w4,
+                                                         RowSel sel, bool gather, int K, int N,
+                                                         Epilogue epi) {
+    const int32_t *rows;
+    long n_rows;
+    resolve_rows(sel, rows, n_rows);
+    const long m0 = (long)blockIdx.y * kValuRows;
+    if (m0 >= n_rows) return;
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n_ld = min(n, N - 1);
+    const uint4 *wrow = reinterpret_cast<const uint4 *>(w4 + (size_t)n_ld * (K / 2));
+
+    const int8_t *xr[kValuRows];
+#pragma unroll
+    for (int i = 0; i < kValuRows; ++i) {
+        const long m = min(m0 + i, n_rows - 1);
+        const long src = (gather && rows) ? rows[m] : m;
+        xr[i] = x + (size_t)src * K;                      // wave-uniform
+    }
+    uint32_t acc[kValuRows + 1];
+#pragma unroll
+    for (int i = 0; i <= kValuRows; ++i) acc[i] = 0u;
+
+    const int k32 = K / 32;
+    for (int kb = 0; kb < k32; ++kb) {
+        const uint4 wv = wrow[kb];
+        const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t e = (wd[q] >> (4 * i)) & 7u;
+                const uint32_t msk = (uint32_t)((int32_t)(wd[q] << (28 - 4 * i)) >> 31);   // 0 or ~0
+                const int k = kb * 32 + q * 8 + i;
+#pragma unroll
+                for (int r = 0; r < kValuRows; ++r) {
+                    const uint32_t xv = (uint32_t)(int32_t)xr[r][k];
+                    acc[r] += (xv ^ msk) << e;
+                }
+                acc[kValuRows] += msk << e;               // the virtual row x = 0
+            }
+        }
+    }
+    // K % 32 tail, one byte (two weights) at a time
+    for (int k = k32 * 32; k < K; k += 2) {
+        const uint32_t byte = w4[(size_t)n_ld * (K / 2) + (k >> 1)];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t nib = (byte >> (4 * i)) & 15u;
+            const uint32_t e = nib & 7u;
+            const uint32_t msk = (nib & 8u) ? ~0u : 0u;
+#pragma unroll
+            for (int r = 0; r < kValuRows; ++r) {
+                const uint32_t xv = (uint32_t)(int32_t)xr[r][k + i];
+                acc[r] += (xv ^ msk) << e;
+            }
+            acc[kValuRows] += msk << e;
+        }
+    }
+    if (n < N) {
+#pragma unroll
+        for (int r = 0; r < kValuRows; ++r)
+            if (m0 + r < n_rows)
+                epi_store<MODE>(epi, m0 + r, n, N, (int32_t)(acc[r] - acc[kValuRows]), rows);
+    }
+}
+
+// ------------------------------------------------------------------ MFMA variant ----
+constexpr int BM = 128, BN = 128, BK = 64;     // workgroup tile; BK in int8 elements
+constexpr int LDS_STRIDE = BK + 16;            // bytes per tile row (padding spreads the banks)
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__device__ inline uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+    return __builtin_amdgcn_perm(hi, lo, sel);
+}
+
+// 8 nibbles of `x` (k ascending from bit 0) -> 8 int8 of plane A and 8 of plane B, k order.
+__device__ inline void decode8(uint32_t x, uint32_t outA[2], uint32_t outB[2]) {
+    // magnitude tables indexed by e: bytes 0..3 in the low word, 4..7 in the high word
+    constexpr uint32_t TA_LO = 0x08040201u, TA_HI = 0x40402010u;   // 1 2 4 8 | 16 32 64 64
+    constexpr uint32_t TB_LO = 0x00000000u, TB_HI = 0x40000000u;   // 0 .. 0 64
+    const uint32_t nibs[2] = {x & 0x0F0F0F0Fu, (x >> 4) & 0x0F0F0F0Fu};   // even k, odd k
+    uint32_t a[2], b[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const uint32_t sel = nibs[p] & 0x07070707u;
+        const uint32_t s1 = (nibs[p] >> 3) & 0x01010101u;          // 1 where negative
+        const uint32_t m = s1 * 0xFFu;                             // 0xFF where negative
+        const uint32_t pa = perm(TA_HI, TA_LO, sel);
+        const uint32_t pb = perm(TB_HI, TB_LO, sel);
+        a[p] = (pa ^ m) + s1;                 // per byte: ~pa + 1 = -pa (pa >= 1: no carry)
+        b[p] = pb | (m & (pb << 1));          // 0x40 -> 0xC0 = -64 where negative
+    }
+    // interleave even / odd back into k order: k0 k1 k2 k3 | k4 k5 k6 k7
+    outA[0] = perm(a[1], a[0], 0x05010400u);
+    outA[1] = perm(a[1], a[0], 0x07030602u);
+    outB[0] = perm(b[1], b[0], 0x05010400u);
+    outB[1] = perm(b[1], b[0], 0x07030602u);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void shift_mfma_kernel(const int8_t *__restrict__ x,
+                                                         const uint8_t *__restrict__ w4,
+                                                         RowSel sel, bool gather, int K, int N,
+                                                         Epilogue epi) {
+    __shared__ __attribute__((aligned(16))) uint8_t As[BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint8_t Ba[BN * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint8_t Bb[BN * LDS_STRIDE];
+
+    const int32_t *rows;
+    long n_rows;
+    resolve_rows(sel, rows, n_rows);
+    const long m0 = (long)blockIdx.y * BM;
+    if (m0 >= n_rows) return;
+    const int n0 = blockIdx.x * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+
+    // global -> LDS assignments
+    // A: 128 rows x 4 chunks of 16 B; thread handles chunks tid and tid + 256
+    const int8_t *a_src[2];
+    bool a_ok[2];
+    int a_dst[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid + 256 * i;
+        const int r = c >> 2, col = (c & 3) * 16;
+        const long m = m0 + r;
+        a_ok[i] = m < n_rows;
+        const long src = a_ok[i] ? ((gather && rows) ? (long)rows[m] : m) : 0;
+        a_src[i] = x + (size_t)src * K + col;
+        a_dst[i] = r * LDS_STRIDE + col;
+    }
+    // W: 128 rows x 2 chunks of 16 B (32 weights); thread handles row tid/2, half tid%2
+    const int w_r = tid >> 1, w_half = tid & 1;
+    const bool w_ok = (n0 + w_r) < N;
+    const uint8_t *w_src = w4 + (size_t)(w_ok ? n0 + w_r : 0) * (K / 2) + w_half * 16;
+    const int w_dst = w_r * LDS_STRIDE + w_half * 32;
+
+    v16i acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 16;
+
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        uint4 av[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            av[i] = a_ok[i] ? *reinterpret_cast<const uint4 *>(a_src[i] + k0) : make_uint4(0, 0, 0, 0);
+        const uint4 wv = w_ok ? *reinterpret_cast<const uint4 *>(w_src + (k0 >> 1)) : make_uint4(0, 0, 0, 0);
+        __syncthreads();           // everyone is done reading the previous tile
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4 *>(As + a_dst[i]) = av[i];
+        {
+            const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+            uint32_t oa[8], ob[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) decode8(wd[q], oa + 2 * q, ob + 2 * q);
+            if (!w_ok) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) { oa[q] = 0; ob[q] = 0; }
+            }
+            *reinterpret_cast<uint4 *>(Ba + w_dst) = make_uint4(oa[0], oa[1], oa[2], oa[3]);
+            *reinterpret_cast<uint4 *>(Ba + w_dst + 16) = make_uint4(oa[4], oa[5], oa[6], oa[7]);
+            *reinterpret_cast<uint4 *>(Bb + w_dst) = make_uint4(ob[0], ob[1], ob[2], ob[3]);
+            *reinterpret_cast<uint4 *>(Bb + w_dst + 16) = make_uint4(ob[4], ob[5], ob[6], ob[7]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 32) {
+            v4i af[2], ba[2], bb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                af[i] = *reinterpret_cast<const v4i *>(As + (wm + i * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                ba[j] = *reinterpret_cast<const v4i *>(Ba + (wn + j * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
+                bb[j] = *reinterpret_cast<const v4i *>(Bb + (wn + j * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], ba[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bb[j], acc[i][j], 0, 0, 0);
+                }
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const long m = m0 + wm + i * 32 + mfma32_row(r, lane);
+                if (m < n_rows && n < N) epi_store<MODE>(epi, m, n, N, acc[i][j][r], rows);
+            }
+        }
+}
+
+__global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__ x, long n,
+                                                       float inv_scale, int8_t *__restrict__ q) {
+    const long i4 = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i4 + 3 < n) {
+        const float4 v = *reinterpret_cast<const float4 *>(x + i4);
+        const uint32_t b0 = (uint8_t)requant_code(v.x * inv_scale), b1 = (uint8_t)requant_code(v.y * inv_scale);
+        const uint32_t b2 = (uint8_t)requant_code(v.z * inv_scale), b3 = (uint8_t)requant_code(v.w * inv_scale);
+        *reinterpret_cast<uint32_t *>(q + i4) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+    } else {
+        for (long i = i4; i < n; ++i) q[i] = requant_code(x[i] * inv_scale);
+    }
+}
+
+__global__ __launch_bounds__(256) void requant_lut_kernel(const int32_t *__restrict__ y, long n, float s,
+                                                          const int8_t *__restrict__ lut,
+                                                          int8_t *__restrict__ h) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) h[i] = lut[(int)requant_code((float)y[i] * s) + 128];
+}
+
+template <int MODE>
+int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &sel, bool gather, int K,
+                 int N, const Epilogue &epi, hipStream_t st) {
+    if (sel.max_rows == 0 || N == 0) return SA_OK;
+    if (variant == SA_VARIANT_AUTO) variant = (K % BK == 0) ? SA_VARIANT_MFMA : SA_VARIANT_VALU;
+    if (variant == SA_VARIANT_MFMA) {
+        SA_REQUIRE(K % BK == 0, SA_ERR_SHAPE, "shift layer: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
+        const long gy = (sel.max_rows + BM - 1) / BM;
+        SA_REQUIRE(gy < 65536, SA_ERR_SHAPE, "shift layer: too many rows for one launch");
+        const dim3 grid((N + BN - 1) / BN, (unsigned)gy);
+        shift_mfma_kernel<MODE><<<grid, dim3(256), 0, st>>>(x, w4, sel, gather, K, N, epi);
+        return check_launch("shift layer (MFMA)");
+    }
+    const long gy = (sel.max_rows + kValuRows - 1) / kValuRows;
+    SA_REQUIRE(gy < 65536, SA_ERR_SHAPE, "shift layer: too many rows for one launch");
+    const dim3 grid((N + 255) / 256, (unsigned)gy);
+    shift_valu_kernel<MODE><<<grid, dim3(256), 0, st>>>(x, w4, sel, gather, K, N, epi);
+    return check_launch("shift layer (VALU)");
+}
+
+}  // namespace
+
+extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t *bias_or_null,
+                               int32_t *y, long M, int K, int N, int variant, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(M >= 0 && K >= 0 && N >= 0, SA_ERR_INVALID, "sa_shift_linear: negative size");
+    SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_shift_linear: unknown variant %d", variant);
+    SA_REQUIRE(K % 2 == 0, SA_ERR_SHAPE, "sa_shift_linear: K (%d) must be even (two weights per byte)", K);
+    SA_REQUIRE(K <= 131072, SA_ERR_SHAPE, "sa_shift_linear: K too large for int32 accumulation");
+    SA_REQUIRE(M < (1L << 31), SA_ERR_SHAPE, "sa_shift_linear: M >= 2^31");
+    if (M == 0 || N == 0) return SA_OK;
+    SA_REQUIRE(x && w4 && y, SA_ERR_INVALID, "sa_shift_linear: NULL buffer");
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w4) && sa::aligned16(y) && sa::aligned16(bias_or_null),
+               SA_ERR_ALIGN, "sa_shift_linear: pointers must be 16-byte aligned");
+    SA_REQUIRE(K % 32 == 0, SA_ERR_SHAPE, "sa_shift_linear: K (%d) must be a multiple of 32 (16-byte weight rows)", K);
+    sa::RowSel sel{nullptr, nullptr, 0, M};
+    sa::Epilogue epi;
+    epi.y = y;
+    epi.bias = bias_or_null;
+    // 65535 row tiles per launch: split very tall inputs
+    const long rows_per_launch = 65535L * kValuRows;
+    for (long m = 0; m < M; m += rows_per_launch) {
+        sa::RowSel s2 = sel;
+        s2.max_rows = (M - m) < rows_per_launch ? (M - m) : rows_per_launch;
+        sa::Epilogue e2 = epi;
+        e2.y = y + (size_t)m * N;
+        int rc = launch_shift<sa::kEpiInt32>(variant, x + (size_t)m * K, w4, s2, false, K, N, e2,
+                                             sa::as_stream(stream));
+        if (rc != SA_OK) return rc;
+    }
+    return SA_OK;
+}
+
+extern "C" int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(n >= 0, SA_ERR_INVALID, "sa_quantize_act: n < 0");
+    if (n == 0) return SA_OK;
+    SA_REQUIRE(x && q, SA_ERR_INVALID, "sa_quantize_act: NULL buffer");
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(q), SA_ERR_ALIGN, "sa_quantize_act: pointers must be 16-byte aligned");
+    const long blocks = ((n + 3) / 4 + 255) / 256;
+    SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_quantize_act: n too large");
+    quantize_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(x, n, inv_scale, q);
+    return sa::check_launch("sa_quantize_act");
+}
+
+extern "C" int sa_requant_lut(const int32_t *y, long n, float s, const int8_t *lut, int8_t *h, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(n >= 0, SA_ERR_INVALID, "sa_requant_lut: n < 0");
+    if (n == 0) return SA_OK;
+    SA_REQUIRE(y && lut && h, SA_ERR_INVALID, "sa_requant_lut: NULL buffer");
+    SA_REQUIRE(sa::aligned16(y) && sa::aligned16(h) && sa::aligned16(lut), SA_ERR_ALIGN,
+               "sa_requant_lut: pointers must be 16-byte aligned");
+    const long blocks = (n + 255) / 256;
+    SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_requant_lut: n too large");
+    requant_lut_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(y, n, s, lut, h);
+    return sa::check_launch("sa_requant_lut");
+}
+
+extern "C" size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid) {
+    if (max_rows <= 0 || hid <= 0) return 0;
+    return (((size_t)max_rows * hid) + 255) / 256 * 256;
+}
+
+extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const uint8_t *w1,
+                            const uint8_t *w2, float requant_scale, const int8_t *lut,
+                            int32_t *y2_or_null, float *y_or_null, const float *gate_or_null,
+                            float out_scale, int variant, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+    sa::clear_error();
+    sa::RowSel sel;
+    int rc = sa::validate_rows(rows, &sel);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(E > 0 && hid > 0, SA_ERR_INVALID, "sa_shift_mlp: E and hid must be positive");
+    SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_shift_mlp: unknown variant %d", variant);
+    SA_REQUIRE(E % 64 == 0 && hid % 64 == 0, SA_ERR_SHAPE,
+               "sa_shift_mlp: E (%d) and hid (%d) must be multiples of 64", E, hid);
+    SA_REQUIRE(E <= 131072 && hid <= 131072, SA_ERR_SHAPE, "sa_shift_mlp: width too large");
+    if (sel.max_rows == 0) return SA_OK;
+    SA_REQUIRE(xq && w1 && w2 && lut, SA_ERR_INVALID, "sa_shift_mlp: NULL buffer");
+    SA_REQUIRE(y2_or_null || y_or_null, SA_ERR_INVALID, "sa_shift_mlp: no output requested");
+    SA_REQUIRE(sa::aligned16(xq) && sa::aligned16(w1) && sa::aligned16(w2) && sa::aligned16(lut) &&
+                   sa::aligned16(y2_or_null) && sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) &&
+                   sa::aligned16(workspace) && sa::aligned4(sel.rows),
+               SA_ERR_ALIGN, "sa_shift_mlp: pointers must be 16-byte aligned");
+    const size_t need = sa_shift_mlp_workspace_bytes(sel.max_rows, E, hid);
+    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
+               "sa_shift_mlp: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    SA_REQUIRE((sel.max_rows + kValuRows - 1) / kValuRows < 65536 || variant != SA_VARIANT_VALU, SA_ERR_SHAPE,
+               "sa_shift_mlp: too many rows for the VALU variant in one call");
+    SA_REQUIRE((sel.max_rows + BM - 1) / BM < 65536, SA_ERR_SHAPE, "sa_shift_mlp: too many rows");
+    hipStream_t st = sa::as_stream(stream);
+    int8_t *hbuf = static_cast<int8_t *>(workspace);
+
+    sa::Epilogue e1;
+    e1.h = hbuf;
+    e1.rq = requant_scale;
+    e1.lut = lut;
+    rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, st);
+    if (rc != SA_OK) return rc;
+
+    if (y2_or_null) {
+        sa::Epilogue e2;
+        e2.y = y2_or_null;
+        rc = launch_shift<sa::kEpiInt32>(variant, hbuf, w2, sel, false, hid, E, e2, st);
+        if (rc != SA_OK) return rc;
+    }
+    if (y_or_null) {
+        sa::Epilogue e3;
+        e3.yf = y_or_null;
+        e3.gate = gate_or_null;
+        e3.out_scale = out_scale;
+        rc = launch_shift<sa::kEpiScatterI32>(variant, hbuf, w2, sel, false, hid, E, e3, st);
+        if (rc != SA_OK) return rc;
+    }
+    return SA_OK;
+}

@@ -1,0 +1,96 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares and
+rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "shiftadd.h")
+LIB = os.path.join(ROOT, "paper_2306_06446_amd", "libshiftadd.so")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sa_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import sys
+        sys.path.insert(0, ROOT)
+        from paper_2306_06446_amd import build
+        build.build_library(verbose=False)
+    lib = ctypes.CDLL(LIB)
+    lib.sa_last_error.restype = ctypes.c_char_p
+    return lib
+
+
+def test_header_declares_the_north_star_calls():
+    names = declared_functions()
+    for n in ("sa_binarize", "sa_additive_attention", "sa_hamming_attention", "sa_shift_linear",
+              "sa_moe_dispatch", "sa_block_forward"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2306_06446_amd import binding
+    names = declared_functions()
+    assert len(names) >= 19
+    for n in names:
+        assert hasattr(lib, n), "libshiftadd.so does not export %s" % n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version(lib):
+    assert lib.sa_version() >= 100
+
+
+def test_argument_errors_are_reported_without_a_gpu(lib):
+    null = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    # nbits not a multiple of 64
+    assert lib.sa_binarize(fake, 1, 1, 1, 64, fake, 65, fake, null) == -2
+    assert b"nbits" in lib.sa_last_error()
+    # without proj nbits must equal d
+    assert lib.sa_binarize(fake, 1, 1, 1, 64, null, 128, fake, null) == -2
+    # misaligned pointer
+    assert lib.sa_binarize(odd, 1, 1, 1, 64, fake, 64, fake, null) == -3
+    # unsupported head dim
+    assert lib.sa_binarize(fake, 1, 1, 1, 48, fake, 64, fake, null) == -6
+    # empty problem is fine and launches nothing
+    assert lib.sa_binarize(null, 0, 5, 1, 64, null, 64, null, null) == 0
+    assert lib.sa_last_error() == b""
+    # additive attention: bad phases, bad dv, missing workspace
+    f = ctypes.c_float(1.0)
+    assert lib.sa_additive_attention(fake, fake, fake, fake, 1, 1, 4, 4, 64, 64, f, fake, 0, null,
+                                     ctypes.c_size_t(0), null) == -1
+    assert lib.sa_additive_attention(fake, fake, fake, fake, 1, 1, 4, 4, 64, 48, f, fake, 3, null,
+                                     ctypes.c_size_t(0), null) == -6
+    lib.sa_additive_attention_workspace_bytes.restype = ctypes.c_size_t
+    need = lib.sa_additive_attention_workspace_bytes(8, 4, 16384, 256, 64)
+    assert need > 0 and need % (8 * 4 * 256 * 64 * 4) == 0
+    assert lib.sa_additive_attention(fake, fake, fake, fake, 8, 4, 16384, 16384, 256, 64, f, fake, 3, null,
+                                     ctypes.c_size_t(0), null) == -4
+    # hamming: zero keys, non-finite scale
+    assert lib.sa_hamming_attention(fake, fake, fake, fake, 1, 1, 4, 0, 64, 64, f, null, null) == -2
+    assert lib.sa_hamming_attention(fake, fake, fake, fake, 1, 1, 4, 4, 64, 64, ctypes.c_float(float("nan")),
+                                    null, null) == -1
+    # shift linear: odd K, unknown variant, MFMA with K % 64 != 0
+    M = ctypes.c_long(4)
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 33, 8, 0, null) == -2
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 64, 8, 7, null) == -1
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 96, 8, 1, null) == -2
+    assert lib.sa_shift_linear(null, fake, null, fake, M, 64, 8, 0, null) == -1
+    # dispatch: E out of range, missing workspace
+    T = ctypes.c_long(100)
+    assert lib.sa_moe_dispatch(fake, T, 1, fake, fake, fake, fake, null, ctypes.c_size_t(0), null) == -2
+    assert lib.sa_moe_dispatch(fake, T, 2, fake, fake, fake, fake, null, ctypes.c_size_t(0), null) == -4
+    # block: NULL descriptor
+    lib.sa_block_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.sa_block_workspace_bytes(null) == 0
+    assert lib.sa_block_forward(null, null) == -1
