@@ -1,0 +1,310 @@
+#!/usr/bin/env python3
+"""Block throughput of libshiftadd on one MI355X, with roofline and CPU-oracle baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c4]
+
+A step is one pass of the whole block (hash Q and K, attention, activation
+quantisation, routing, both experts, combine) over one batch of seeded synthetic
+input that is already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+PEAK_TFLOPS = {                  # dense peaks of MI355X
+    "alu_fp32": 157.3,           # fp32 vector FMA: 256 CU x 128 lanes x 2 flop x 2.4 GHz (needs packed ops)
+    "alu_int": 39.3,             # 32-bit integer vector ops: 256 CU x 64 lanes x 2.4 GHz
+    "mfma_i8": 5000.0,
+    "mfma_f16": 2500.0,
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c4", "c5"])
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="input/workspace sets cycled through (0 = enough to exceed the 256 MiB last-level cache)")
+    ap.add_argument("--shift-variant", type=int, default=2, choices=[0, 1, 2])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    return ap.parse_args()
+
+
+def kernel_table(cfg, p, counts):
+    """Algorithmic bytes and operations of every kernel of the block (what the method must move and
+    compute: packed codes, 4-bit weights, int8 activations; never the dense fp32 work it avoids)."""
+    T, E, H, N, B = cfg.T, cfg.E, cfg.H, cfg.N, cfg.B
+    rows = T * H
+    tab = []
+    bin_bytes = rows * cfg.d * 4 + cfg.d * cfg.nbits * 4 + rows * cfg.nbits // 8
+    bin_flop = 2 * rows * cfg.nbits * cfg.d
+    for name in ("binarize_q", "binarize_k"):
+        tab.append(dict(name=name, bytes=bin_bytes, ops=bin_flop, compute="alu_fp32"))
+    code_b = rows * cfg.nbits // 8
+    v_b = rows * cfg.dv * 4
+    if cfg.attention == "linear":
+        kv_b = B * H * cfg.nbits * cfg.dv * 4
+        adds = rows * cfg.nbits * cfg.dv          # one accumulate per (token, bit, column)
+        tab.append(dict(name="ktv", bytes=code_b + v_b + kv_b, ops=adds, compute="alu_fp32"))
+        tab.append(dict(name="qkv", bytes=code_b + kv_b + v_b, ops=adds, compute="alu_fp32"))
+    else:
+        pairs = B * H * N * N
+        tab.append(dict(name="hamming", bytes=2 * code_b + 2 * v_b, ops=2 * pairs * cfg.dv, compute="alu_fp32"))
+    if cfg.E:
+        tab.append(dict(name="quantize", bytes=T * E * 5, ops=2 * T * E, compute="alu_fp32"))
+        t_shift, t_mult = (counts[1], counts[0]) if counts is not None else (T, 0)
+        if counts is not None:
+            tab.append(dict(name="dispatch", bytes=T * (8 + 12), ops=4 * T, compute="alu_fp32"))
+            tab.append(dict(name="mult_fc1", bytes=t_mult * E * 4 + E * cfg.hid * 2 + t_mult * cfg.hid * 2,
+                            ops=2 * t_mult * E * cfg.hid, compute="mfma_f16"))
+            tab.append(dict(name="mult_fc2", bytes=t_mult * cfg.hid * 2 + E * cfg.hid * 2 + t_mult * E * 4,
+                            ops=2 * t_mult * E * cfg.hid, compute="mfma_f16"))
+        tab.append(dict(name="shift_fc1", bytes=t_shift * E + E * cfg.hid // 2 + t_shift * cfg.hid,
+                        ops=2 * t_shift * E * cfg.hid, compute="mfma_i8"))
+        tab.append(dict(name="shift_fc2", bytes=t_shift * cfg.hid + E * cfg.hid // 2 + t_shift * E * 4,
+                        ops=2 * t_shift * E * cfg.hid, compute="mfma_i8"))
+    return tab
+
+
+def floors_us(k, shift_variant):
+    comp = k["compute"]
+    if comp == "mfma_i8" and shift_variant == 0:
+        comp = "alu_int"
+    t_hbm = k["bytes"] / (HBM_PEAK_GBS * 1e9) * 1e6
+    t_cmp = k["ops"] / (PEAK_TFLOPS[comp] * 1e12) * 1e6
+    return t_hbm, t_cmp, comp
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (got --gpus %d)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2306_06446_amd import binding as sa, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    sa.load_library()
+    cfg = {"c1": wl.C1, "c2": wl.C2, "c4": wl.C4, "c5": wl.C5}[args.config]
+    moe = cfg.E > 0 and cfg.shift_frac is not None
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint64:
+            a = a.view(np.int64)
+        return torch.from_numpy(a).cuda()
+
+    # ---- inputs (host, seeded) and device copies
+    q, k, v = wl.qkv(cfg)
+    pr = wl.proj(cfg)
+    scale = wl.attention_scale(cfg)
+    p = wl.mlp_params(cfg) if cfg.E else None
+    logits = wl.router_logits(cfg) if moe else None
+    shared = dict(proj=dev(pr))
+    if p is not None:
+        shared.update(w1=dev(p.w1), w2=dev(p.w2), lut=dev(p.lut))
+        if moe:
+            shared.update(mw1=dev(p.mw1), mw2=dev(p.mw2))
+    per_set_bytes = (q.nbytes + k.nbytes + v.nbytes) + 2 * cfg.T * max(cfg.E, cfg.H * cfg.dv) * 4
+    n_sets = args.rotate or max(1, min(8, math.ceil(600e6 / per_set_bytes)))
+    blocks = []
+    for _ in range(n_sets):
+        kw = dict(B=cfg.B, N=cfg.N, H=cfg.H, d=cfg.d, nbits=cfg.nbits, dv=cfg.dv,
+                  attention=0 if cfg.attention == "linear" else 1, hid=cfg.hid, moe=moe, attn_scale=scale,
+                  q=dev(q), k=dev(k), v=dev(v), proj=shared["proj"], shift_variant=args.shift_variant)
+        if p is not None:
+            kw.update(act_inv_scale=p.act_inv_scale, requant_scale=p.requant_scale, out_scale=p.out_scale,
+                      w1=shared["w1"], w2=shared["w2"], lut=shared["lut"])
+            if moe:
+                kw.update(logits=dev(logits), mw1=shared["mw1"], mw2=shared["mw2"])
+        blocks.append((sa.Block(**kw), kw))
+
+    # ---- the timed region: W warm-up steps, then exactly K steps
+    for i in range(args.warmup):
+        blocks[i % n_sets][0].forward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        blocks[i % n_sets][0].forward()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations, HIP events on the launch stream, same buffers, same rotation
+    counts = None
+    if moe:
+        n_shift = int(math.floor(cfg.shift_frac * cfg.T + 0.5))
+        counts = (cfg.T - n_shift, n_shift)
+    table = kernel_table(cfg, p, counts)
+    kernels = {}
+    if not args.no_kernels:
+        stage_sets = [make_stages(sa, torch, cfg, kw, p, moe, args.shift_variant) for _, kw in blocks]
+        for name in [t["name"] for t in table]:
+            for s in stage_sets:              # warm-up, also fills the intermediates later stages read
+                s[name]()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                stage_sets[i % n_sets][name]()
+            e1.record()
+            torch.cuda.synchronize()
+            kernels[name] = e0.elapsed_time(e1) * 1e3 / args.steps      # us per launch
+
+    report = []
+    for t in table:
+        t_hbm, t_cmp, comp = floors_us(t, args.shift_variant)
+        us = kernels.get(t["name"])
+        row = dict(name=t["name"], us=None if us is None else round(us, 2), bytes=t["bytes"], ops=t["ops"],
+                   hbm_floor_us=round(t_hbm, 2), compute_floor_us=round(t_cmp, 2),
+                   bound="hbm" if t_hbm >= t_cmp else ("mfma" if comp.startswith("mfma") else "alu"),
+                   compute_peak=comp)
+        if us:
+            row["hbm_frac"] = round(t_hbm / us, 4)
+            row["binding_frac"] = round(max(t_hbm, t_cmp) / us, 4)
+        report.append(row)
+
+    roofline = None
+    timed = [r for r in report if r["us"]]
+    if timed:
+        dom = max(timed, key=lambda r: r["us"])
+        if dom["bound"] == "hbm":
+            ach, peak, unit = dom["bytes"] / (dom["us"] * 1e-6) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = dom["ops"] / (dom["us"] * 1e-6) / 1e12, PEAK_TFLOPS[dom["compute_peak"]], "TFLOP/s"
+        roofline = dict(kernel=dom["name"], bound=dom["bound"], achieved=round(ach, 3), peak=peak, unit=unit,
+                        frac=round(ach / peak, 4), traffic=read_traffic(args.config, dom["name"]),
+                        us_per_launch=dom["us"])
+    block_bytes = sum(t["bytes"] for t in table)
+    block_hbm_frac = block_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, args.cpu_sample_batch)
+
+    out = {
+        "metric": "block tokens/s (additive attn + shift MLP) at 1 GPU; % HBM roofline",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32+u64 codes+i8/i32 shift+f16 mult",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "N": cfg.N, "H": cfg.H, "d": cfg.d, "nbits": cfg.nbits,
+                   "E": cfg.E, "hid": cfg.hid, "attention": cfg.attention,
+                   "mlp": ("moe %.0f%% shift / %.0f%% fp16 mult" % (100 * cfg.shift_frac, 100 - 100 * cfg.shift_frac))
+                   if moe else ("shift" if cfg.E else "none"),
+                   "input_sets_rotated": n_sets, "shift_variant": args.shift_variant},
+        "block_hbm_roofline_frac": round(block_hbm_frac, 4),
+        "block_algorithmic_bytes": block_bytes,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": report,
+    }
+    print(json.dumps(out))
+
+
+def make_stages(sa, torch, cfg, kw, p, moe, variant):
+    """One callable per kernel of the block, on buffers of its own (same shapes as the block's)."""
+    T, E = cfg.T, cfg.E
+    d = kw["q"].device
+    qc = torch.empty((cfg.B, cfg.H, cfg.N, cfg.W), dtype=torch.int64, device=d)
+    kc = torch.empty_like(qc)
+    o = torch.empty((cfg.B, cfg.N, cfg.H, cfg.dv), dtype=torch.float32, device=d)
+    lib = sa.load_library()
+    st = {"binarize_q": lambda: sa.sa_binarize(kw["q"], kw["proj"], cfg.nbits, codes=qc),
+          "binarize_k": lambda: sa.sa_binarize(kw["k"], kw["proj"], cfg.nbits, codes=kc)}
+    if cfg.attention == "linear":
+        kv = torch.empty((cfg.B, cfg.H, cfg.nbits, cfg.dv), dtype=torch.float32, device=d)
+        ws = torch.empty(max(16, lib.sa_additive_attention_workspace_bytes(cfg.B, cfg.H, cfg.N, cfg.nbits, cfg.dv)),
+                         dtype=torch.uint8, device=d)
+        st["ktv"] = lambda: sa.sa_additive_attention(None, kc, kw["v"], kw["attn_scale"], cfg.nbits, phases=1,
+                                                     kv=kv, workspace=ws)
+        st["qkv"] = lambda: sa.sa_additive_attention(qc, None, None, kw["attn_scale"], cfg.nbits, phases=2,
+                                                     kv=kv, out=o, workspace=ws)
+    else:
+        st["hamming"] = lambda: sa.sa_hamming_attention(qc, kc, kw["v"], kw["attn_scale"], cfg.nbits, out=o)
+    if not E:
+        return st
+    x = o.view(T, E)
+    xq = torch.empty((T, E), dtype=torch.int8, device=d)
+    y = torch.empty((T, E), dtype=torch.float32, device=d)
+    st["quantize"] = lambda: sa.sa_quantize_act(x, p.act_inv_scale, q=xq)
+    sws = torch.empty(max(16, lib.sa_shift_mlp_workspace_bytes(sa._l(T), E, cfg.hid)), dtype=torch.uint8, device=d)
+    rows = dict()
+    if moe:
+        outs = (torch.empty(T, dtype=torch.int32, device=d), torch.empty(T, dtype=torch.int32, device=d),
+                torch.empty(4, dtype=torch.int32, device=d)[:2], torch.empty(T, dtype=torch.float32, device=d))
+        dws = torch.empty(max(16, lib.sa_moe_dispatch_workspace_bytes(sa._l(T), 2)), dtype=torch.uint8, device=d)
+        st["dispatch"] = lambda: sa.sa_moe_dispatch(kw["logits"], out=outs, workspace=dws)
+        mws = torch.empty(max(16, lib.sa_mult_mlp_workspace_bytes(sa._l(T), E, cfg.hid)), dtype=torch.uint8, device=d)
+        mrows = dict(rows=outs[0], counts=outs[2], expert=0, max_rows=T, gate=outs[3])
+        st["mult_fc1"] = lambda: sa.sa_mult_mlp_f16(x, kw["mw1"], kw["mw2"], want_out=False, y=y, stages=1,
+                                                    workspace=mws, **mrows)
+        st["mult_fc2"] = lambda: sa.sa_mult_mlp_f16(x, kw["mw1"], kw["mw2"], want_out=False, y=y, stages=2,
+                                                    workspace=mws, **mrows)
+        rows = dict(rows=outs[0], counts=outs[2], expert=1, max_rows=T, gate=outs[3])
+    for name, stage in (("shift_fc1", 1), ("shift_fc2", 2)):
+        st[name] = (lambda stage=stage: sa.sa_shift_mlp(xq, kw["w1"], kw["w2"], p.requant_scale, kw["lut"],
+                                                        want_y2=False, y=y, out_scale=p.out_scale, variant=variant,
+                                                        stages=stage, workspace=sws, **rows))
+    return st
+
+
+def read_traffic(config, kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), kept as text in
+    profiles/; None when no measurement is stored for this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % config)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel:
+            try:
+                return int(float(parts[1]))
+            except ValueError:
+                return None
+    return None
+
+
+def cpu_baseline(cfg, sample_batch):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload (same widths, fewer
+    batch elements), on this host's cores."""
+    import numpy as np
+
+    import oracle
+    from paper_2306_06446_amd import workloads as wl
+
+    default = {1: 1, 2: 2, 4: 8, 5: 1}[cfg.cfg_id]
+    sb = sample_batch or default
+    n = cfg.N if cfg.cfg_id != 5 else 2048
+    small = wl.scaled_down(cfg, B=sb, N=n)
+    q, k, v = wl.qkv(small)
+    pr, scale = wl.proj(small), wl.attention_scale(small)
+    p = wl.mlp_params(small) if small.E else None
+    logits = wl.router_logits(small) if (small.E and small.shift_frac is not None) else None
+    oracle.build()
+    t0 = time.perf_counter()
+    oracle.block_forward(small, q, k, v, pr, scale, logits, p)
+    dt = time.perf_counter() - t0
+    return {"value": round(small.T / dt, 2), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%s with B=%d, N=%d (%d tokens), one pass, %.2f s" % (cfg.name, sb, n, small.T, dt)}
+
+
+if __name__ == "__main__":
+    main()

@@ -157,12 +157,14 @@ typedef struct sa_rows {
  *               (gate_or_null == NULL stands for gate 1)
  *   xq [T,E] int8, w1 [hid, E/2], w2 [E, hid/2], lut int8 [256].
  * Workspace holds the int8 hidden rows.  E % 64 == 0 and hid % 64 == 0.
+ * stages: 1 = first layer only (fills the workspace), 2 = second layer only
+ * (reads the workspace a stage-1 call with the same rows filled), 3 = both.
  */
 size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid);
 int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const uint8_t *w1,
                  const uint8_t *w2, float requant_scale, const int8_t *lut, int32_t *y2_or_null,
                  float *y_or_null, const float *gate_or_null, float out_scale, int variant,
-                 void *workspace, size_t workspace_bytes, void *stream);
+                 int stages, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Mult expert (Sec. 4.2): a dense two-layer MLP with erf-GELU in fp16 with
@@ -170,13 +172,14 @@ int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const ui
  *   out = W2 * half(gelu(W1 * half(x[rows])))      W1 [hid,E], W2 [E,hid] fp16
  * Outputs as for sa_shift_mlp: out_or_null fp32 [max_rows, E] and / or
  * y_or_null fp32 [T, E] with y[rows[i], :] = gate[rows[i]] * out[i, :].
- * E % 32 == 0 and hid % 32 == 0.
+ * E % 32 == 0 and hid % 32 == 0.  stages as for sa_shift_mlp (the workspace
+ * holds the fp16 hidden rows).
  */
 size_t sa_mult_mlp_workspace_bytes(long max_rows, int E, int hid);
 int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const void *w1_f16,
                     const void *w2_f16, float *out_or_null, float *y_or_null,
-                    const float *gate_or_null, void *workspace, size_t workspace_bytes,
-                    void *stream);
+                    const float *gate_or_null, int stages, void *workspace,
+                    size_t workspace_bytes, void *stream);
 
 /* Plain row movement (Sec. 4.2, y = sum_i G(x) * E_i(x) with one non-zero term):
  *   gather : dst[i, :] = src[rows[i], :]                 (row_bytes % 16 == 0)

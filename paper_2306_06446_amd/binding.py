@@ -157,15 +157,20 @@ def sa_shift_linear(x, w4, bias=None, variant=SA_VARIANT_AUTO, y=None):
     return y
 
 
-def sa_moe_dispatch(logits):
+def sa_moe_dispatch(logits, out=None, workspace=None):
     lib = load_library()
     T, E = logits.shape
     dev = logits.device
-    perm = torch.empty(T, dtype=torch.int32, device=dev)
-    expert_of = torch.empty(T, dtype=torch.int32, device=dev)
-    counts = torch.empty(max(E, 4), dtype=torch.int32, device=dev)[:E]
-    gate = torch.empty(T, dtype=torch.float32, device=dev)
-    ws = _workspace(lib.sa_moe_dispatch_workspace_bytes(_l(T), E), dev)
+    if out is None:
+        perm = torch.empty(T, dtype=torch.int32, device=dev)
+        expert_of = torch.empty(T, dtype=torch.int32, device=dev)
+        counts = torch.empty(max(E, 4), dtype=torch.int32, device=dev)[:E]
+        gate = torch.empty(T, dtype=torch.float32, device=dev)
+    else:
+        perm, expert_of, counts, gate = out
+    ws = workspace
+    if ws is None:
+        ws = _workspace(lib.sa_moe_dispatch_workspace_bytes(_l(T), E), dev)
     _check(lib.sa_moe_dispatch(_ptr(logits), _l(T), E, _ptr(perm), _ptr(expert_of), _ptr(counts),
                                _ptr(gate), _ptr(ws), _z(ws.numel()), _stream()))
     return perm, expert_of, counts, gate
@@ -186,7 +191,8 @@ def sa_requant_lut(y, s, lut, h=None):
 
 
 def sa_shift_mlp(xq, w1, w2, requant_scale, lut, rows=None, counts=None, expert=0, max_rows=None,
-                 want_y2=True, y=None, gate=None, out_scale=1.0, variant=SA_VARIANT_AUTO):
+                 want_y2=True, y=None, gate=None, out_scale=1.0, variant=SA_VARIANT_AUTO, stages=3,
+                 workspace=None):
     lib = load_library()
     T, E = xq.shape
     hid = w1.shape[0]
@@ -194,15 +200,17 @@ def sa_shift_mlp(xq, w1, w2, requant_scale, lut, rows=None, counts=None, expert=
         max_rows = T if rows is None or counts is not None else rows.numel()
     r = _rows(rows, counts, expert, max_rows)
     y2 = torch.empty((max_rows, E), dtype=torch.int32, device=xq.device) if want_y2 else None
-    ws = _workspace(lib.sa_shift_mlp_workspace_bytes(_l(max_rows), E, hid), xq.device)
+    ws = workspace
+    if ws is None:
+        ws = _workspace(lib.sa_shift_mlp_workspace_bytes(_l(max_rows), E, hid), xq.device)
     _check(lib.sa_shift_mlp(_ptr(xq), ctypes.byref(r), E, hid, _ptr(w1), _ptr(w2), _f(requant_scale),
-                            _ptr(lut), _ptr(y2), _ptr(y), _ptr(gate), _f(out_scale), variant, _ptr(ws),
-                            _z(ws.numel()), _stream()))
+                            _ptr(lut), _ptr(y2), _ptr(y), _ptr(gate), _f(out_scale), variant, stages,
+                            _ptr(ws), _z(ws.numel()), _stream()))
     return y2
 
 
 def sa_mult_mlp_f16(x, w1, w2, rows=None, counts=None, expert=0, max_rows=None, want_out=True,
-                    y=None, gate=None):
+                    y=None, gate=None, stages=3, workspace=None):
     lib = load_library()
     T, E = x.shape
     hid = w1.shape[0]
@@ -210,9 +218,11 @@ def sa_mult_mlp_f16(x, w1, w2, rows=None, counts=None, expert=0, max_rows=None, 
         max_rows = T if rows is None or counts is not None else rows.numel()
     r = _rows(rows, counts, expert, max_rows)
     out = torch.empty((max_rows, E), dtype=torch.float32, device=x.device) if want_out else None
-    ws = _workspace(lib.sa_mult_mlp_workspace_bytes(_l(max_rows), E, hid), x.device)
+    ws = workspace
+    if ws is None:
+        ws = _workspace(lib.sa_mult_mlp_workspace_bytes(_l(max_rows), E, hid), x.device)
     _check(lib.sa_mult_mlp_f16(_ptr(x), ctypes.byref(r), E, hid, _ptr(w1), _ptr(w2), _ptr(out), _ptr(y),
-                               _ptr(gate), _ptr(ws), _z(ws.numel()), _stream()))
+                               _ptr(gate), stages, _ptr(ws), _z(ws.numel()), _stream()))
     return out
 
 

@@ -100,7 +100,7 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     if (!d->moe) {
         const sa_rows all{nullptr, nullptr, 0, T};
         return sa_shift_mlp(xq, &all, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, nullptr,
-                            d->out_scale, d->shift_variant, ws + L.shift_ws, L.shift_ws_bytes, stream);
+                            d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
     }
     int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
     int32_t *expert_of = reinterpret_cast<int32_t *>(ws + L.expert_of);
@@ -109,9 +109,9 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     rc = sa_moe_dispatch(d->logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes, stream);
     if (rc != SA_OK) return rc;
     const sa_rows mult_rows{perm, counts, 0, T}, shift_rows{perm, counts, 1, T};
-    rc = sa_mult_mlp_f16(d->o, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, ws + L.mult_ws,
+    rc = sa_mult_mlp_f16(d->o, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3, ws + L.mult_ws,
                          L.mult_ws_bytes, stream);
     if (rc != SA_OK) return rc;
     return sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
-                        d->out_scale, d->shift_variant, ws + L.shift_ws, L.shift_ws_bytes, stream);
+                        d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
 }

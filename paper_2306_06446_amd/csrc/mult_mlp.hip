@@ -155,8 +155,8 @@ extern "C" size_t sa_mult_mlp_workspace_bytes(long max_rows, int E, int hid) {
 
 extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const void *w1_f16,
                                const void *w2_f16, float *out_or_null, float *y_or_null,
-                               const float *gate_or_null, void *workspace, size_t workspace_bytes,
-                               void *stream) {
+                               const float *gate_or_null, int stages, void *workspace,
+                               size_t workspace_bytes, void *stream) {
     sa::clear_error();
     sa::RowSel sel;
     int rc = sa::validate_rows(rows, &sel);
@@ -166,7 +166,8 @@ extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int h
                "sa_mult_mlp_f16: E (%d) and hid (%d) must be multiples of 32", E, hid);
     if (sel.max_rows == 0) return SA_OK;
     SA_REQUIRE(x && w1_f16 && w2_f16, SA_ERR_INVALID, "sa_mult_mlp_f16: NULL buffer");
-    SA_REQUIRE(out_or_null || y_or_null, SA_ERR_INVALID, "sa_mult_mlp_f16: no output requested");
+    SA_REQUIRE(stages >= 1 && stages <= 3, SA_ERR_INVALID, "sa_mult_mlp_f16: stages must be 1, 2 or 3");
+    SA_REQUIRE(!(stages & 2) || out_or_null || y_or_null, SA_ERR_INVALID, "sa_mult_mlp_f16: no output requested");
     SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w1_f16) && sa::aligned16(w2_f16) && sa::aligned16(out_or_null) &&
                    sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) && sa::aligned16(workspace) && sa::aligned4(sel.rows),
                SA_ERR_ALIGN, "sa_mult_mlp_f16: pointers must be 16-byte aligned");
@@ -179,12 +180,15 @@ extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int h
     _Float16 *hbuf = static_cast<_Float16 *>(workspace);
     const _Float16 *w1 = static_cast<const _Float16 *>(w1_f16), *w2 = static_cast<const _Float16 *>(w2_f16);
 
-    sa::Epilogue e1;
-    e1.hh = hbuf;
-    mult_gemm_kernel<true, sa::kEpiGeluHalf><<<dim3((hid + BN - 1) / BN, (unsigned)gy), dim3(256), 0, st>>>(
-        x, w1, sel, E, hid, e1);
-    rc = sa::check_launch("sa_mult_mlp_f16(fc1)");
-    if (rc != SA_OK) return rc;
+    if (stages & 1) {
+        sa::Epilogue e1;
+        e1.hh = hbuf;
+        mult_gemm_kernel<true, sa::kEpiGeluHalf><<<dim3((hid + BN - 1) / BN, (unsigned)gy), dim3(256), 0, st>>>(
+            x, w1, sel, E, hid, e1);
+        rc = sa::check_launch("sa_mult_mlp_f16(fc1)");
+        if (rc != SA_OK) return rc;
+    }
+    if (!(stages & 2)) return SA_OK;
     const dim3 grid2((E + BN - 1) / BN, (unsigned)gy);
     if (out_or_null) {
         sa::Epilogue e2;

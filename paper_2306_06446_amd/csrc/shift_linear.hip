@@ -357,8 +357,8 @@ extern "C" size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid) {
 extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const uint8_t *w1,
                             const uint8_t *w2, float requant_scale, const int8_t *lut,
                             int32_t *y2_or_null, float *y_or_null, const float *gate_or_null,
-                            float out_scale, int variant, void *workspace, size_t workspace_bytes,
-                            void *stream) {
+                            float out_scale, int variant, int stages, void *workspace,
+                            size_t workspace_bytes, void *stream) {
     sa::clear_error();
     sa::RowSel sel;
     int rc = sa::validate_rows(rows, &sel);
@@ -370,7 +370,8 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     SA_REQUIRE(E <= 131072 && hid <= 131072, SA_ERR_SHAPE, "sa_shift_mlp: width too large");
     if (sel.max_rows == 0) return SA_OK;
     SA_REQUIRE(xq && w1 && w2 && lut, SA_ERR_INVALID, "sa_shift_mlp: NULL buffer");
-    SA_REQUIRE(y2_or_null || y_or_null, SA_ERR_INVALID, "sa_shift_mlp: no output requested");
+    SA_REQUIRE(stages >= 1 && stages <= 3, SA_ERR_INVALID, "sa_shift_mlp: stages must be 1, 2 or 3");
+    SA_REQUIRE(!(stages & 2) || y2_or_null || y_or_null, SA_ERR_INVALID, "sa_shift_mlp: no output requested");
     SA_REQUIRE(sa::aligned16(xq) && sa::aligned16(w1) && sa::aligned16(w2) && sa::aligned16(lut) &&
                    sa::aligned16(y2_or_null) && sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) &&
                    sa::aligned16(workspace) && sa::aligned4(sel.rows),
@@ -384,12 +385,15 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     hipStream_t st = sa::as_stream(stream);
     int8_t *hbuf = static_cast<int8_t *>(workspace);
 
-    sa::Epilogue e1;
-    e1.h = hbuf;
-    e1.rq = requant_scale;
-    e1.lut = lut;
-    rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, st);
-    if (rc != SA_OK) return rc;
+    if (stages & 1) {
+        sa::Epilogue e1;
+        e1.h = hbuf;
+        e1.rq = requant_scale;
+        e1.lut = lut;
+        rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, st);
+        if (rc != SA_OK) return rc;
+    }
+    if (!(stages & 2)) return SA_OK;
 
     if (y2_or_null) {
         sa::Epilogue e2;
