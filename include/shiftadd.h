@@ -99,10 +99,13 @@ int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const
  *   x [M,K] int8, w4 [N,K/2] packed 4-bit, bias [N] int32 or NULL, y [M,N] int32.
  * K % 32 == 0 (16-byte weight rows); the MFMA variant needs K % 64 == 0 (AUTO
  * falls back to VALU).
- * Both variants are bit-exact.
+ * Both variants are bit-exact.  The MFMA variant decodes the weights to two
+ * int8 planes in the workspace (2*N*K bytes) before the matrix-core pass.
  */
+size_t sa_shift_linear_workspace_bytes(long M, int K, int N, int variant);
 int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t *bias_or_null, int32_t *y,
-                    long M, int K, int N, int variant, void *stream);
+                    long M, int K, int N, int variant, void *workspace, size_t workspace_bytes,
+                    void *stream);
 
 /*
  * Top-1 routing (Sec. 4.2: p = softmax(logits), G(x) = p_i * 1{p_i >= p_j}).

@@ -19,7 +19,7 @@ SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO = 0, 1, 2
 
 EXPORTS = [
     "sa_version", "sa_last_error", "sa_binarize", "sa_additive_attention_workspace_bytes",
-    "sa_additive_attention", "sa_hamming_attention", "sa_shift_linear",
+    "sa_additive_attention", "sa_hamming_attention", "sa_shift_linear_workspace_bytes", "sa_shift_linear",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
@@ -51,8 +51,9 @@ class SaBlockDesc(ctypes.Structure):
 
 def load_library():
     """Load the in-tree library; raises if it has not been built."""
-    global _lib
+    global _lib, LIB_PATH
     if _lib is None:
+        LIB_PATH = os.environ.get("SHIFTADD_LIB", LIB_PATH)    # another build of the same library
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(
                 "libshiftadd.so is not built (%s): run `python -c 'import __graft_entry__ as g; "
@@ -60,6 +61,7 @@ def load_library():
         lib = ctypes.CDLL(LIB_PATH)
         lib.sa_last_error.restype = ctypes.c_char_p
         for name in ("sa_additive_attention_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
+                     "sa_shift_linear_workspace_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
                      "sa_block_workspace_bytes"):
             getattr(lib, name).restype = ctypes.c_size_t
@@ -147,13 +149,16 @@ def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, o
     return (out, scores) if want_scores else out
 
 
-def sa_shift_linear(x, w4, bias=None, variant=SA_VARIANT_AUTO, y=None):
+def sa_shift_linear(x, w4, bias=None, variant=SA_VARIANT_AUTO, y=None, workspace=None):
+    lib = load_library()
     M, K = x.shape
     N = w4.shape[0]
     if y is None:
         y = torch.empty((M, N), dtype=torch.int32, device=x.device)
-    _check(load_library().sa_shift_linear(_ptr(x), _ptr(w4), _ptr(bias), _ptr(y), _l(M), K, N, variant,
-                                          _stream()))
+    if workspace is None:
+        workspace = _workspace(lib.sa_shift_linear_workspace_bytes(_l(M), K, N, variant), x.device)
+    _check(lib.sa_shift_linear(_ptr(x), _ptr(w4), _ptr(bias), _ptr(y), _l(M), K, N, variant,
+                               _ptr(workspace), _z(workspace.numel()), _stream()))
     return y
 
 

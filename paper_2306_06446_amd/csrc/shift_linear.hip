@@ -6,12 +6,13 @@
 //           negative weight is "xor the activation with all-ones, shift, add" and
 //           the (1 << e) terms, which depend on the weights only, are summed once
 //           per output column through a virtual all-zero activation row.
-//   MFMA  : the 4-bit weights are decoded on the fly to two int8 planes,
+//   MFMA  : the 4-bit weights are decoded once per call to two int8 planes,
 //           A = s * 2^min(e,6) and B = s * 64 * [e == 7] (+128 is not an int8),
 //           and both planes go through v_mfma_i32_32x32x32_i8 into one accumulator.
 // Both share the epilogues (plain int32, requantise + table, gated fp32 scatter).
 #include "common.h"
 #include "gemm_common.h"
+#include "gemm_mfma.h"
 
 namespace {
 
@@ -107,12 +108,9 @@ __global__ __launch_bounds__(256) void shift_valu_kernel(const int8_t *__restric
 }
 
 // ------------------------------------------------------------------ MFMA variant ----
-constexpr int BM = 128, BN = 128, BK = 64;     // workgroup tile; BK in int8 elements
-constexpr int LDS_STRIDE = BK + 16;            // bytes per tile row (padding spreads the banks)
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
+// Step 1: decode the 4-bit weights once per call into two int8 planes [N, K] in the
+// workspace (they stay in the last-level cache); step 2: the shared tiled GEMM runs
+// both planes into one int32 accumulator.
 __device__ inline uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel) {
     return __builtin_amdgcn_perm(hi, lo, sel);
 }
@@ -141,114 +139,72 @@ __device__ inline void decode8(uint32_t x, uint32_t outA[2], uint32_t outB[2]) {
     outB[1] = perm(b[1], b[0], 0x07030602u);
 }
 
+// One thread per 16 bytes of packed weights (32 weights): 32 B out to each plane.
+__global__ __launch_bounds__(256) void decode_w4_kernel(const uint4 *__restrict__ w4, long n_chunks,
+                                                        uint4 *__restrict__ plane_a, uint4 *__restrict__ plane_b) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_chunks) return;
+    const uint4 wv = w4[i];
+    const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+    uint32_t oa[8], ob[8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) decode8(wd[q], oa + 2 * q, ob + 2 * q);
+    plane_a[2 * i] = make_uint4(oa[0], oa[1], oa[2], oa[3]);
+    plane_a[2 * i + 1] = make_uint4(oa[4], oa[5], oa[6], oa[7]);
+    plane_b[2 * i] = make_uint4(ob[0], ob[1], ob[2], ob[3]);
+    plane_b[2 * i + 1] = make_uint4(ob[4], ob[5], ob[6], ob[7]);
+}
+
 template <int MODE>
-__global__ __launch_bounds__(256) void shift_mfma_kernel(const int8_t *__restrict__ x,
-                                                         const uint8_t *__restrict__ w4,
-                                                         RowSel sel, bool gather, int K, int N,
-                                                         Epilogue epi) {
-    __shared__ __attribute__((aligned(16))) uint8_t As[BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) uint8_t Ba[BN * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) uint8_t Bb[BN * LDS_STRIDE];
-
-    const int32_t *rows;
-    long n_rows;
-    resolve_rows(sel, rows, n_rows);
-    const long m0 = (long)blockIdx.y * BM;
-    if (m0 >= n_rows) return;
-    const int n0 = blockIdx.x * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-
-    // global -> LDS assignments
-    // A: 128 rows x 4 chunks of 16 B; thread handles chunks tid and tid + 256
-    const int8_t *a_src[2];
-    bool a_ok[2];
-    int a_dst[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int c = tid + 256 * i;
-        const int r = c >> 2, col = (c & 3) * 16;
-        const long m = m0 + r;
-        a_ok[i] = m < n_rows;
-        const long src = a_ok[i] ? ((gather && rows) ? (long)rows[m] : m) : 0;
-        a_src[i] = x + (size_t)src * K + col;
-        a_dst[i] = r * LDS_STRIDE + col;
+struct ShiftStore {
+    static constexpr int kPackedBytes = (MODE == kEpiRequantLut) ? 1 : 0;
+    static constexpr int kTableBytes = (MODE == kEpiRequantLut) ? 256 : 0;
+    Epilogue e;
+    int N;
+    void *out;             // narrow output (int8 hidden rows)
+    const void *table;     // the 256-entry activation table
+    __device__ inline void direct(long m, int n, int32_t acc, const int32_t *rows) const {
+        epi_store<MODE>(e, m, n, N, acc, rows);
     }
-    // W: 128 rows x 2 chunks of 16 B (32 weights); thread handles row tid/2, half tid%2
-    const int w_r = tid >> 1, w_half = tid & 1;
-    const bool w_ok = (n0 + w_r) < N;
-    const uint8_t *w_src = w4 + (size_t)(w_ok ? n0 + w_r : 0) * (K / 2) + w_half * 16;
-    const int w_dst = w_r * LDS_STRIDE + w_half * 32;
-
-    v16i acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 16;
-
-    for (int k0 = 0; k0 < K; k0 += BK) {
-        uint4 av[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            av[i] = a_ok[i] ? *reinterpret_cast<const uint4 *>(a_src[i] + k0) : make_uint4(0, 0, 0, 0);
-        const uint4 wv = w_ok ? *reinterpret_cast<const uint4 *>(w_src + (k0 >> 1)) : make_uint4(0, 0, 0, 0);
-        __syncthreads();           // everyone is done reading the previous tile
-#pragma unroll
-        for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4 *>(As + a_dst[i]) = av[i];
-        {
-            const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
-            uint32_t oa[8], ob[8];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) decode8(wd[q], oa + 2 * q, ob + 2 * q);
-            if (!w_ok) {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) { oa[q] = 0; ob[q] = 0; }
-            }
-            *reinterpret_cast<uint4 *>(Ba + w_dst) = make_uint4(oa[0], oa[1], oa[2], oa[3]);
-            *reinterpret_cast<uint4 *>(Ba + w_dst + 16) = make_uint4(oa[4], oa[5], oa[6], oa[7]);
-            *reinterpret_cast<uint4 *>(Bb + w_dst) = make_uint4(ob[0], ob[1], ob[2], ob[3]);
-            *reinterpret_cast<uint4 *>(Bb + w_dst + 16) = make_uint4(ob[4], ob[5], ob[6], ob[7]);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 32) {
-            v4i af[2], ba[2], bb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                af[i] = *reinterpret_cast<const v4i *>(As + (wm + i * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                ba[j] = *reinterpret_cast<const v4i *>(Ba + (wn + j * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
-                bb[j] = *reinterpret_cast<const v4i *>(Bb + (wn + j * 32 + frag_row) * LDS_STRIDE + kk + frag_k);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], ba[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bb[j], acc[i][j], 0, 0, 0);
-                }
-        }
+    __device__ inline uint32_t convert(int32_t acc, const uint8_t *lds_table) const {
+        return lds_table[(int)requant_code((float)acc * e.rq) + 128];
     }
+};
 
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn + j * 32 + (lane & 31);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const long m = m0 + wm + i * 32 + mfma32_row(r, lane);
-                if (m < n_rows && n < N) epi_store<MODE>(epi, m, n, N, acc[i][j][r], rows);
-            }
-        }
+size_t planes_bytes(int K, int N) { return ((size_t)2 * N * K + 255) / 256 * 256; }
+
+constexpr int kMfmaK = 64;   // K granularity of the MFMA variant (one LDS stage)
+
+// planes: workspace of planes_bytes(K, N) for the MFMA variant (unused by the VALU variant).
+template <int MODE>
+int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &sel, bool gather, int K,
+                 int N, const Epilogue &epi, void *planes, hipStream_t st) {
+    if (sel.max_rows == 0 || N == 0) return SA_OK;
+    if (variant == SA_VARIANT_AUTO) variant = (K % kMfmaK == 0) ? SA_VARIANT_MFMA : SA_VARIANT_VALU;
+    if (variant == SA_VARIANT_MFMA) {
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "shift layer: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
+        int8_t *pa = static_cast<int8_t *>(planes), *pb = pa + (size_t)N * K;
+        const long n_chunks = (long)N * K / 32;
+        decode_w4_kernel<<<dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st>>>(
+            reinterpret_cast<const uint4 *>(w4), n_chunks, reinterpret_cast<uint4 *>(pa), reinterpret_cast<uint4 *>(pb));
+        int rc = check_launch("shift layer (weight decode)");
+        if (rc != SA_OK) return rc;
+        GemmArgs g;
+        g.a = x;
+        g.b[0] = pa;
+        g.b[1] = pb;
+        g.sel = sel;
+        g.gather_a = gather;
+        g.K = K;
+        g.N = N;
+        ShiftStore<MODE> store{epi, N, epi.h, epi.lut};
+        return launch_gemm<I8Traits>(g, store, st, "shift layer (MFMA)");
+    }
+    const long gy = (sel.max_rows + kValuRows - 1) / kValuRows;
+    SA_REQUIRE(gy < 65536, SA_ERR_SHAPE, "shift layer: too many rows for one launch");
+    const dim3 grid((N + 255) / 256, (unsigned)gy);
+    shift_valu_kernel<MODE><<<grid, dim3(256), 0, st>>>(x, w4, sel, gather, K, N, epi);
+    return check_launch("shift layer (VALU)");
 }
 
 __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__ x, long n,
@@ -271,30 +227,17 @@ __global__ __launch_bounds__(256) void requant_lut_kernel(const int32_t *__restr
     if (i < n) h[i] = lut[(int)requant_code((float)y[i] * s) + 128];
 }
 
-template <int MODE>
-int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &sel, bool gather, int K,
-                 int N, const Epilogue &epi, hipStream_t st) {
-    if (sel.max_rows == 0 || N == 0) return SA_OK;
-    if (variant == SA_VARIANT_AUTO) variant = (K % BK == 0) ? SA_VARIANT_MFMA : SA_VARIANT_VALU;
-    if (variant == SA_VARIANT_MFMA) {
-        SA_REQUIRE(K % BK == 0, SA_ERR_SHAPE, "shift layer: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
-        const long gy = (sel.max_rows + BM - 1) / BM;
-        SA_REQUIRE(gy < 65536, SA_ERR_SHAPE, "shift layer: too many rows for one launch");
-        const dim3 grid((N + BN - 1) / BN, (unsigned)gy);
-        shift_mfma_kernel<MODE><<<grid, dim3(256), 0, st>>>(x, w4, sel, gather, K, N, epi);
-        return check_launch("shift layer (MFMA)");
-    }
-    const long gy = (sel.max_rows + kValuRows - 1) / kValuRows;
-    SA_REQUIRE(gy < 65536, SA_ERR_SHAPE, "shift layer: too many rows for one launch");
-    const dim3 grid((N + 255) / 256, (unsigned)gy);
-    shift_valu_kernel<MODE><<<grid, dim3(256), 0, st>>>(x, w4, sel, gather, K, N, epi);
-    return check_launch("shift layer (VALU)");
-}
-
 }  // namespace
 
+extern "C" size_t sa_shift_linear_workspace_bytes(long M, int K, int N, int variant) {
+    if (M <= 0 || K <= 0 || N <= 0 || variant == SA_VARIANT_VALU) return 0;
+    if (K % kMfmaK != 0) return 0;
+    return planes_bytes(K, N);
+}
+
 extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t *bias_or_null,
-                               int32_t *y, long M, int K, int N, int variant, void *stream) {
+                               int32_t *y, long M, int K, int N, int variant, void *workspace,
+                               size_t workspace_bytes, void *stream) {
     sa::clear_error();
     SA_REQUIRE(M >= 0 && K >= 0 && N >= 0, SA_ERR_INVALID, "sa_shift_linear: negative size");
     SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_shift_linear: unknown variant %d", variant);
@@ -303,21 +246,24 @@ extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t
     SA_REQUIRE(M < (1L << 31), SA_ERR_SHAPE, "sa_shift_linear: M >= 2^31");
     if (M == 0 || N == 0) return SA_OK;
     SA_REQUIRE(x && w4 && y, SA_ERR_INVALID, "sa_shift_linear: NULL buffer");
-    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w4) && sa::aligned16(y) && sa::aligned16(bias_or_null),
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w4) && sa::aligned16(y) && sa::aligned16(bias_or_null) &&
+                   sa::aligned16(workspace),
                SA_ERR_ALIGN, "sa_shift_linear: pointers must be 16-byte aligned");
     SA_REQUIRE(K % 32 == 0, SA_ERR_SHAPE, "sa_shift_linear: K (%d) must be a multiple of 32 (16-byte weight rows)", K);
-    sa::RowSel sel{nullptr, nullptr, 0, M};
+    if (variant == SA_VARIANT_MFMA)
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
+    const size_t need = sa_shift_linear_workspace_bytes(M, K, N, variant);
+    SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
+               "sa_shift_linear: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     sa::Epilogue epi;
-    epi.y = y;
     epi.bias = bias_or_null;
-    // 65535 row tiles per launch: split very tall inputs
+    // at most 65535 row tiles per launch: very tall inputs go in slices
     const long rows_per_launch = 65535L * kValuRows;
     for (long m = 0; m < M; m += rows_per_launch) {
-        sa::RowSel s2 = sel;
-        s2.max_rows = (M - m) < rows_per_launch ? (M - m) : rows_per_launch;
+        sa::RowSel s2{nullptr, nullptr, 0, (M - m) < rows_per_launch ? (M - m) : rows_per_launch};
         sa::Epilogue e2 = epi;
         e2.y = y + (size_t)m * N;
-        int rc = launch_shift<sa::kEpiInt32>(variant, x + (size_t)m * K, w4, s2, false, K, N, e2,
+        int rc = launch_shift<sa::kEpiInt32>(variant, x + (size_t)m * K, w4, s2, false, K, N, e2, workspace,
                                              sa::as_stream(stream));
         if (rc != SA_OK) return rc;
     }
@@ -349,9 +295,11 @@ extern "C" int sa_requant_lut(const int32_t *y, long n, float s, const int8_t *l
     return sa::check_launch("sa_requant_lut");
 }
 
+// workspace layout of sa_shift_mlp: hidden int8 [max_rows, hid] | planes of w1 | planes of w2
 extern "C" size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid) {
-    if (max_rows <= 0 || hid <= 0) return 0;
-    return (((size_t)max_rows * hid) + 255) / 256 * 256;
+    if (max_rows <= 0 || hid <= 0 || E <= 0) return 0;
+    const size_t hidden = (((size_t)max_rows * hid) + 255) / 256 * 256;
+    return hidden + 2 * planes_bytes(E, hid);
 }
 
 extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const uint8_t *w1,
@@ -381,16 +329,17 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
                "sa_shift_mlp: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     SA_REQUIRE((sel.max_rows + kValuRows - 1) / kValuRows < 65536 || variant != SA_VARIANT_VALU, SA_ERR_SHAPE,
                "sa_shift_mlp: too many rows for the VALU variant in one call");
-    SA_REQUIRE((sel.max_rows + BM - 1) / BM < 65536, SA_ERR_SHAPE, "sa_shift_mlp: too many rows");
     hipStream_t st = sa::as_stream(stream);
     int8_t *hbuf = static_cast<int8_t *>(workspace);
+    uint8_t *planes1 = static_cast<uint8_t *>(workspace) + (((size_t)sel.max_rows * hid) + 255) / 256 * 256;
+    uint8_t *planes2 = planes1 + planes_bytes(E, hid);
 
     if (stages & 1) {
         sa::Epilogue e1;
         e1.h = hbuf;
         e1.rq = requant_scale;
         e1.lut = lut;
-        rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, st);
+        rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, planes1, st);
         if (rc != SA_OK) return rc;
     }
     if (!(stages & 2)) return SA_OK;
@@ -398,7 +347,7 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     if (y2_or_null) {
         sa::Epilogue e2;
         e2.y = y2_or_null;
-        rc = launch_shift<sa::kEpiInt32>(variant, hbuf, w2, sel, false, hid, E, e2, st);
+        rc = launch_shift<sa::kEpiInt32>(variant, hbuf, w2, sel, false, hid, E, e2, planes2, st);
         if (rc != SA_OK) return rc;
     }
     if (y_or_null) {
@@ -406,7 +355,7 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
         e3.yf = y_or_null;
         e3.gate = gate_or_null;
         e3.out_scale = out_scale;
-        rc = launch_shift<sa::kEpiScatterI32>(variant, hbuf, w2, sel, false, hid, E, e3, st);
+        rc = launch_shift<sa::kEpiScatterI32>(variant, hbuf, w2, sel, false, hid, E, e3, planes2, st);
         if (rc != SA_OK) return rc;
     }
     return SA_OK;

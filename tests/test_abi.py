@@ -82,10 +82,12 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
                                     null, null) == -1
     # shift linear: odd K, unknown variant, MFMA with K % 64 != 0
     M = ctypes.c_long(4)
-    assert lib.sa_shift_linear(fake, fake, null, fake, M, 33, 8, 0, null) == -2
-    assert lib.sa_shift_linear(fake, fake, null, fake, M, 64, 8, 7, null) == -1
-    assert lib.sa_shift_linear(fake, fake, null, fake, M, 96, 8, 1, null) == -2
-    assert lib.sa_shift_linear(null, fake, null, fake, M, 64, 8, 0, null) == -1
+    z0 = ctypes.c_size_t(0)
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 33, 8, 0, null, z0, null) == -2
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 64, 8, 7, null, z0, null) == -1
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 96, 8, 1, null, z0, null) == -2
+    assert lib.sa_shift_linear(null, fake, null, fake, M, 64, 8, 0, null, z0, null) == -1
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 64, 8, 1, null, z0, null) == -4   # planes workspace
     # dispatch: E out of range, missing workspace
     T = ctypes.c_long(100)
     assert lib.sa_moe_dispatch(fake, T, 1, fake, fake, fake, fake, null, ctypes.c_size_t(0), null) == -2
