@@ -65,6 +65,13 @@ const char *sa_last_error(void);
  */
 int sa_binarize(const float *x, int B, int N, int H, int d, const float *proj, int nbits,
                 uint64_t *codes, void *stream);
+/* The same with the kernel chosen by hand (both give the same bits):
+ *   SA_VARIANT_VALU  every bit through the defining chain on the vector ALU
+ *   SA_VARIANT_MFMA  matrix-core pre-pass; bits whose sign it cannot settle (a rigorous
+ *                    margin test) are re-run through the defining chain
+ *   SA_VARIANT_AUTO  what sa_binarize uses                                          */
+int sa_binarize_ex(const float *x, int B, int N, int H, int d, const float *proj, int nbits,
+                   uint64_t *codes, int variant, void *stream);
 
 /*
  * Linear attention with both MatMuls as Add layers (Eq. 3, O_Add; Sec. 4.1,

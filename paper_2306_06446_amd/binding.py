@@ -18,7 +18,7 @@ _lib = None
 SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO = 0, 1, 2
 
 EXPORTS = [
-    "sa_version", "sa_last_error", "sa_binarize", "sa_additive_attention_workspace_bytes",
+    "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_additive_attention_workspace_bytes",
     "sa_additive_attention", "sa_hamming_attention", "sa_shift_linear_workspace_bytes", "sa_shift_linear",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
@@ -110,11 +110,15 @@ def sa_version():
     return load_library().sa_version()
 
 
-def sa_binarize(x, proj, nbits, codes=None):
+def sa_binarize(x, proj, nbits, codes=None, variant=None):
     B, N, H, d = x.shape
     if codes is None:
         codes = torch.empty((B, H, N, nbits // 64), dtype=torch.int64, device=x.device)
-    _check(load_library().sa_binarize(_ptr(x), B, N, H, d, _ptr(proj), nbits, _ptr(codes), _stream()))
+    lib = load_library()
+    if variant is None:
+        _check(lib.sa_binarize(_ptr(x), B, N, H, d, _ptr(proj), nbits, _ptr(codes), _stream()))
+    else:
+        _check(lib.sa_binarize_ex(_ptr(x), B, N, H, d, _ptr(proj), nbits, _ptr(codes), variant, _stream()))
     return codes
 
 

@@ -68,7 +68,13 @@ __global__ __launch_bounds__(256) void binarize_sign_kernel(const float *__restr
 
 extern "C" int sa_binarize(const float *x, int B, int N, int H, int d, const float *proj,
                            int nbits, uint64_t *codes, void *stream) {
+    return sa_binarize_ex(x, B, N, H, d, proj, nbits, codes, SA_VARIANT_AUTO, stream);
+}
+
+extern "C" int sa_binarize_ex(const float *x, int B, int N, int H, int d, const float *proj,
+                              int nbits, uint64_t *codes, int variant, void *stream) {
     sa::clear_error();
+    SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_binarize: unknown variant %d", variant);
     SA_REQUIRE(B >= 0 && N >= 0 && H >= 0 && d > 0 && nbits > 0, SA_ERR_INVALID,
                "sa_binarize: negative size");
     SA_REQUIRE(nbits % 64 == 0, SA_ERR_SHAPE, "sa_binarize: nbits %d is not a multiple of 64", nbits);
@@ -91,6 +97,10 @@ extern "C" int sa_binarize(const float *x, int B, int N, int H, int d, const flo
         binarize_sign_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, codes, N, H, d, n_words);
         return sa::check_launch("sa_binarize(sign)");
     }
+    if (variant != SA_VARIANT_VALU && sa::binarize_mfma_supported(d, nbits))
+        return sa::launch_binarize_mfma(x, proj, codes, rows, N, H, d, nbits, st);
+    SA_REQUIRE(variant != SA_VARIANT_MFMA, SA_ERR_UNSUPPORTED,
+               "sa_binarize: the matrix-core variant needs d in {32, 64, 128} (got %d)", d);
     const int n_chunks = (N + 63) / 64;
     const long n_tasks = (long)B * H * n_chunks * W;
     const long blocks = (n_tasks + 3) / 4;

@@ -1,0 +1,330 @@
+// Hashing through the matrix cores, still bit-exact (Sec. 4.1, binary quantisation of Q / K).
+//
+// The code bit is DEFINED as the sign of the fp32 chain acc = fma(x_k, r_kj, acc), k ascending.
+// For almost every (row, bit) that sign is decided long before rounding matters, so the kernel
+//   1. computes z~ = x . r^_j on the bf16 matrix cores, r^_j = r_j / |r_j|, with a three-product
+//      split (x = xh + xl, r^ = rh + rl, z~ = xh rh + xh rl + xl rh: ~2^-15 relative accuracy),
+//   2. keeps sign(z~) wherever |z~| > 2^-12 * |x| (|x| |r^_j| is the Cauchy-Schwarz bound of
+//      sum |x_k r^_kj|; the chain's own error is at most 64 * 2^-24 of that sum, the split's and
+//      the normalisation's about 2^-15, so the margin is more than an order of magnitude), and
+//   3. re-runs the defining chain, one (row, bit) per lane, for the rest (about 0.2 % of the bits
+//      on Gaussian data; every bit if the data is degenerate) and flips the stored bit if needed.
+// NaN / Inf / denormal-range sums fail the test in step 2 and take step 3, which is the definition.
+//
+// Tiles are 32 consecutive rows of the flattened [B*N*H, d] input (one contiguous 32*d*4-byte
+// read).  The MFMA computes the TRANSPOSED tile (hash bits down, rows across), so that a lane ends
+// up with 16 bits of one row per 32-bit group: signs are packed with two integer operations per
+// bit, the margin test is one multiply and one compare per bit against a per-lane threshold, and
+// the two half-wavefronts exchange their halves with one shuffle per group.  The hash matrix
+// lives in LDS as ready-made bf16 MFMA fragments; wavefronts stride over the tiles and park their
+// unsettled bits in LDS lists that one wavefront per workgroup works off at the end.
+#include "common.h"
+
+namespace sa {
+
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kListCap = 192;                 // unsettled bits parked per wavefront
+constexpr float kKeepFactor = 6.26e-8f;       // (2^-12)^2 * 1.05
+constexpr float kKeepFloor = 1e-37f;          // |z~| below ~3e-19: the relative error model does not hold
+
+struct RowMap {
+    int N, H, W;
+    __device__ inline size_t word_index(long row, int col) const {
+        const long nh = (long)N * H;
+        const long b = row / nh, rem = row - b * nh;
+        const long n = rem / H, h = rem - n * H;
+        return (((size_t)b * H + h) * N + n) * W + (col >> 6);
+    }
+};
+
+__device__ inline void split_bf16(float f, __bf16 &hi, __bf16 &lo) {
+    hi = (__bf16)f;
+    lo = (__bf16)(f - (float)hi);
+}
+
+// Re-runs the defining chain for one parked (row, bit) entry and flips the stored bit where the
+// pre-pass had it wrong.
+template <int D>
+__device__ inline void settle_entry(uint64_t e, const float *__restrict__ x, const float *__restrict__ proj,
+                                    uint64_t *codes, const RowMap &map, int nbits) {
+    const long row = (long)(e & 0xffffffffu);
+    const int col = (int)((e >> 32) & 0xffffu);
+    const bool prov = (e >> 48) & 1u;
+    const float *xr = x + (size_t)row * D;
+    const float *pc = proj + col;
+    float acc = 0.0f;
+    // 32 steps of the chain per round trip: loads first, then the fmas in their defined order
+#pragma unroll 1
+    for (int k0 = 0; k0 < D; k0 += 32) {
+        float xv[32], rv[32];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float4 t4 = *reinterpret_cast<const float4 *>(xr + k0 + 4 * q);
+            xv[4 * q] = t4.x; xv[4 * q + 1] = t4.y; xv[4 * q + 2] = t4.z; xv[4 * q + 3] = t4.w;
+        }
+#pragma unroll
+        for (int k = 0; k < 32; ++k) rv[k] = pc[(size_t)(k0 + k) * nbits];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) acc = __builtin_fmaf(xv[k], rv[k], acc);
+    }
+    const bool exact = acc >= 0.0f;
+    if (exact != prov)
+        atomicXor(reinterpret_cast<unsigned long long *>(codes + map.word_index(row, col)), 1ull << (col & 63));
+}
+
+// One wavefront's list, worked off 64 entries at a time.  Kept out of line: inside the tile loop it is
+// the rare path (degenerate data) and must not cost the loop its registers.
+template <int D>
+__device__ __attribute__((noinline)) void work_off_list(const uint64_t *list, int cnt, const float *__restrict__ x,
+                                                        const float *__restrict__ proj, uint64_t *codes,
+                                                        RowMap map, int nbits) {
+    const int lane = threadIdx.x & 63;
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // the words these bits live in have been stored
+    for (int t0 = 0; t0 < cnt; t0 += 64)
+        if (t0 + lane < cnt) settle_entry<D>(list[t0 + lane], x, proj, codes, map, nbits);
+}
+
+// D: head dim; G: hash columns handled by one workgroup (blockIdx.y selects the group).
+template <int D, int G>
+__global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__restrict__ x,
+                                                               const float *__restrict__ proj, uint64_t *codes,
+                                                               long rows, RowMap map, int nbits, long n_tiles) {
+    constexpr int S = D / 16;      // MFMA steps along k
+    constexpr int JT = G / 32;     // 32-bit groups of hash columns
+    constexpr int HALF = D / 2;    // k values one lane owns (the other half-wavefront owns the rest)
+    __shared__ __attribute__((aligned(16))) uint4 bfr_s[S * JT * 2 * 64];
+    __shared__ uint64_t list_s[4][kListCap];
+    __shared__ int cnt_s[4];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i_loc = lane & 31, g = lane >> 5;
+    const int c0 = blockIdx.y * G;
+
+    // ---- hash matrix -> normalised bf16 fragments in LDS: fragment (s, jt, hi/lo), lane L holds
+    //      r^[k = (L/32)*HALF + s*8 + e][c0 + jt*32 + L%32], e = 0..7.
+    //      Thread (column c = tid % G, slice q = tid / G) loads the D / TPC consecutive k of its column
+    //      (coalesced across c), which are exactly the elements of STEPS whole fragments.
+    constexpr int TPC = 256 / G;           // threads per column
+    constexpr int KPT = D / TPC;           // k values per thread
+    constexpr int STEPS = KPT / 8;         // fragments (per hi / lo) per thread
+    static_assert(KPT % 8 == 0 && HALF % KPT == 0, "a thread's k slice must lie inside one half");
+    __shared__ float cn2_s[TPC][G];
+    {
+        const int c = tid % G, qs = tid / G;
+        const int k_first = qs * KPT;
+        const int fg = k_first / HALF, s_first = (k_first % HALF) / 8;
+        const int jt = c / 32, L = fg * 32 + (c & 31);
+        float rv[KPT];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) rv[k] = proj[(size_t)(k_first + k) * nbits + c0 + c];
+        float s2 = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) s2 += rv[k] * rv[k];
+        cn2_s[qs][c] = s2;
+        __syncthreads();
+        float n2 = 0.0f;
+#pragma unroll
+        for (int t = 0; t < TPC; ++t) n2 += cn2_s[t][c];
+        const float inv = 1.0f / __builtin_sqrtf(n2);      // 0 or Inf for a dead / overflowing column: all parked
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            v8bf vh, vl;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                __bf16 hi, lo;
+                split_bf16(rv[st * 8 + e] * inv, hi, lo);
+                vh[e] = hi;
+                vl[e] = lo;
+            }
+            const int s = s_first + st;
+            bfr_s[((s * JT + jt) * 2 + 0) * 64 + L] = __builtin_bit_cast(uint4, vh);
+            bfr_s[((s * JT + jt) * 2 + 1) * 64 + L] = __builtin_bit_cast(uint4, vl);
+        }
+    }
+    __syncthreads();
+
+    int cnt = 0;                   // parked entries of this wavefront (wave-uniform)
+    uint64_t *list = list_s[wave];
+
+    // the next tile's rows are in flight while the current tile is multiplied and packed
+    auto load_tile = [&](long tile, float (&dst)[HALF]) {
+        const long row_ld = min(tile * 32 + i_loc, rows - 1);
+        const float *xr = x + (size_t)row_ld * D + g * HALF;
+#pragma unroll
+        for (int q = 0; q < HALF / 4; ++q) {
+            const float4 t4 = *reinterpret_cast<const float4 *>(xr + 4 * q);
+            dst[4 * q] = t4.x; dst[4 * q + 1] = t4.y; dst[4 * q + 2] = t4.z; dst[4 * q + 3] = t4.w;
+        }
+    };
+    const long tile_step = (long)gridDim.x * 4;
+    float xn[HALF];
+    {
+        const long first = (long)blockIdx.x * 4 + wave;
+        if (first < n_tiles) load_tile(first, xn);
+    }
+    for (long tile = (long)blockIdx.x * 4 + wave; tile < n_tiles; tile += tile_step) {
+        const long r0 = tile * 32;
+        float xv[HALF];
+#pragma unroll
+        for (int k = 0; k < HALF; ++k) xv[k] = xn[k];
+        if (tile + tile_step < n_tiles) load_tile(tile + tile_step, xn);
+        float nx2 = 0.0f;
+#pragma unroll
+        for (int k = 0; k < HALF; ++k) nx2 += xv[k] * xv[k];
+        nx2 += __shfl_xor(nx2, 32);                                // |x_row|^2, row = r0 + i_loc
+        const float thr = __builtin_fmaxf(kKeepFactor * nx2, kKeepFloor);
+
+        // z~^T: accumulator (jt, r) of lane (i_loc, g) = hash bit jt*32 + 8*(r/4) + 4*g + r%4 of row i_loc
+        v16f acc[JT];
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            v8bf xh, xl;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                __bf16 hi, lo;
+                split_bf16(xv[s * 8 + e], hi, lo);
+                xh[e] = hi;
+                xl[e] = lo;
+            }
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) {
+                const v8bf rh = __builtin_bit_cast(v8bf, bfr_s[((s * JT + jt) * 2 + 0) * 64 + lane]);
+                const v8bf rl = __builtin_bit_cast(v8bf, bfr_s[((s * JT + jt) * 2 + 1) * 64 + lane]);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xh, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl, xh, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xl, acc[jt], 0, 0, 0);
+            }
+            // keep the steps apart: hoisting every fragment read of the tile to the top costs
+            // 128 registers and one wavefront of occupancy
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // provisional bits (sign of z~; -0 and NaN are parked anyway) and the unsettled ones,
+        // one mask bit per accumulator register, per 32-bit group
+        const bool row_ok = (r0 + i_loc) < rows;
+        uint32_t bits[JT], park[JT];
+        uint32_t any_park = 0;
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) {
+            uint32_t neg = 0, pk = 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float z = acc[jt][r];
+                const int pos = 8 * (r >> 2) + (r & 3);                       // + 4 * g, applied below
+                neg |= (__builtin_bit_cast(uint32_t, z) >> 31) << pos;
+                pk |= (uint32_t)(!(z * z > thr)) << pos;
+            }
+            bits[jt] = (~neg & 0x0f0f0f0fu) << (4 * g);
+            park[jt] = row_ok ? (pk << (4 * g)) : 0u;
+            any_park |= park[jt];
+        }
+        // the other half-wavefront holds the other 16 bits of each group of the same row
+        uint32_t word[JT];
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) word[jt] = bits[jt] | (uint32_t)__shfl_xor((int)bits[jt], 32);
+        if (lane < 32 && row_ok) {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(codes + map.word_index(r0 + lane, c0));
+            if (JT == 4)
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(word[0], word[1], word[2], word[3]);
+            else
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(word[0], word[JT - 1]);
+        }
+
+        // park the unsettled bits.  The list may be worked off at any point from here on: this
+        // tile's words are on their way to memory and the accumulators are dead.
+        while (__ballot(any_park != 0) != 0) {                    // wave-uniform; rarely more than 2 rounds
+            int jt = 0;
+#pragma unroll
+            for (int t = JT - 1; t >= 0; --t) jt = park[t] ? t : jt;
+            const bool parked = any_park != 0;
+            uint32_t mine = 0;                                    // this lane's first non-empty group
+#pragma unroll
+            for (int t = 0; t < JT; ++t) mine = (t == jt) ? park[t] : mine;
+            const int pos = parked ? __builtin_ctz(mine) : 0;
+            const uint64_t pm = __ballot(parked);
+            if (cnt + 64 > kListCap) {
+                work_off_list<D>(list, cnt, x, proj, codes, map, nbits);
+                cnt = 0;
+            }
+            if (parked) {
+                const int slot = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(pm >> 32),
+                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)pm, 0u));
+                uint32_t b = 0;
+#pragma unroll
+                for (int t = 0; t < JT; ++t) b = (t == jt) ? bits[t] : b;
+                list[slot] = (uint64_t)(uint32_t)(r0 + i_loc) | ((uint64_t)(c0 + jt * 32 + pos) << 32) |
+                             ((uint64_t)((b >> pos) & 1u) << 48);
+                const uint32_t cleared = mine & (mine - 1u);
+#pragma unroll
+                for (int t = 0; t < JT; ++t) park[t] = (t == jt) ? cleared : park[t];
+                any_park = 0;
+#pragma unroll
+                for (int t = 0; t < JT; ++t) any_park |= park[t];
+            }
+            cnt += __builtin_popcountll(pm);
+        }
+    }
+
+    // The four wavefronts' leftovers are worked off together by wavefront 0: the cost of a pass is
+    // its uncoalesced loads, so one full pass beats four nearly empty ones.
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's words have been stored
+    if (lane == 0) cnt_s[wave] = cnt;
+    __syncthreads();
+    if (wave == 0) {
+        const int n0 = cnt_s[0], n1 = n0 + cnt_s[1], n2 = n1 + cnt_s[2], n3 = n2 + cnt_s[3];
+        for (int t0 = 0; t0 < n3; t0 += 64) {
+            const int t = t0 + lane;
+            if (t < n3) {
+                const int w = (t >= n0) + (t >= n1) + (t >= n2);
+                const int base = w == 0 ? 0 : (w == 1 ? n0 : (w == 2 ? n1 : n2));
+                settle_entry<D>(list_s[w][t - base], x, proj, codes, map, nbits);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+bool binarize_mfma_supported(int d, int nbits) {
+    return (d == 32 || d == 64 || d == 128) && nbits % 64 == 0;
+}
+
+template <int D, int G>
+int launch_one(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int nbits,
+               hipStream_t st) {
+    const long n_tiles = (rows + 31) / 32;
+    // about two workgroups of 4 wavefronts per CU (what the registers allow), every wavefront the
+    // same number of tiles
+    const long tiles_per_wave = (n_tiles + 4 * 512 - 1) / (4 * 512);
+    const long blocks = (n_tiles + 4 * tiles_per_wave - 1) / (4 * tiles_per_wave);
+    const dim3 grid((unsigned)blocks, (unsigned)(nbits / G));
+    RowMap map{N, H, nbits / 64};
+    binarize_mfma_kernel<D, G><<<grid, dim3(256), 0, st>>>(x, proj, codes, rows, map, nbits, n_tiles);
+    return check_launch("sa_binarize(mfma)");
+}
+
+int launch_binarize_mfma(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int d,
+                         int nbits, hipStream_t st) {
+    const bool g128 = (nbits % 128 == 0);
+    switch (d) {
+        case 32:
+            return g128 ? launch_one<32, 128>(x, proj, codes, rows, N, H, nbits, st)
+                        : launch_one<32, 64>(x, proj, codes, rows, N, H, nbits, st);
+        case 64:
+            return g128 ? launch_one<64, 128>(x, proj, codes, rows, N, H, nbits, st)
+                        : launch_one<64, 64>(x, proj, codes, rows, N, H, nbits, st);
+        default:
+            return launch_one<128, 64>(x, proj, codes, rows, N, H, nbits, st);
+    }
+}
+
+}  // namespace sa

@@ -48,6 +48,11 @@ __device__ inline void resolve_rows(const RowSel &sel, const int32_t *&rows, lon
 
 int validate_rows(const sa_rows *rows, RowSel *out);
 
+// Hash pre-pass on the matrix cores with exact fallback (binarize_mfma.hip).
+bool binarize_mfma_supported(int d, int nbits);
+int launch_binarize_mfma(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int d,
+                         int nbits, hipStream_t st);
+
 }  // namespace sa
 
 #define SA_REQUIRE(cond, code, ...) \

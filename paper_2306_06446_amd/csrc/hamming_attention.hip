@@ -2,79 +2,127 @@
 // replaced by the Hamming similarity S = nbits - 2 * popcount(q xor k) of the
 // codes; V stays fp32, Sec. 4.1).
 //
-// Lane i <-> query i.  Keys stream by: a key's code words and its V row are
-// the same for every lane, so they arrive through scalar loads; each lane
-// XORs the key code with its own query code, counts bits, turns the distance
-// into an un-normalised softmax weight and accumulates weight * V row.  The
-// score matrix never exists in memory (an optional second kernel dumps it).
+// The scores are integer work for the vector ALU (XOR + popcount, then one exp2 per
+// pair); the second MatMul P * V is the dense fp32 contraction of this kernel and
+// runs on the matrix cores (v_mfma_f32_32x32x2_f32).  The two meet in registers:
+// the A operand of that MFMA is one P value per lane - query (lane % 32), key
+// (k0 + lane / 32) - which is exactly the pair whose score the lane has just
+// computed, so P never exists in memory.  A workgroup owns one (batch, head) and up
+// to 256 queries (one 32-query tile per wavefront); key codes and V rows are staged
+// through LDS in chunks of 128 (64 for dv = 128) keys.  Row sums ride along in the lanes and meet in
+// the epilogue.
 //
-// softmax(scale*S)_j = exp(-2*scale*(dist_j - dist_ref)) / sum, with dist_ref
-// the distance of the largest score.  When scale >= 0 and the exponent range
-// cannot underflow, dist_ref = 0 is used (no pass over the keys to find the
-// row maximum); otherwise a first pass finds it per query.
+// softmax(scale*S)_j = exp2(c2 * (dist_j - dist_ref)) / sum, c2 = -2*scale*log2(e),
+// dist_ref = the distance of the largest score.  When scale >= 0 and the exponent
+// range cannot underflow, dist_ref = 0 (no first pass); otherwise a first pass over
+// the key codes finds it per query.
 #include "common.h"
 
 namespace {
 
 using sa::kWave;
 
+constexpr int kMaxWaves = 8;       // 32-query tiles per workgroup
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int W>
+__device__ inline int distance(const uint64_t (&q)[W], const uint64_t *k) {
+    int dist = 0;
+#pragma unroll
+    for (int w = 0; w < W; ++w) dist += __builtin_popcountll(q[w] ^ k[w]);
+    return dist;
+}
+
 template <int DV, int W, bool ROWREF>
-__global__ __launch_bounds__(256) void hamming_kernel(const uint64_t *__restrict__ q_codes,
-                                                      const uint64_t *__restrict__ k_codes,
-                                                      const float *__restrict__ v,
-                                                      float *__restrict__ out, int H, int Nq,
-                                                      int Nk, int n_chunks, long n_tasks,
-                                                      float c2 /* -2*scale*log2(e) */) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const long task = (long)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (task >= n_tasks) return;
-    const int chunk = (int)(task % n_chunks);
-    const long bh = task / n_chunks;
+__global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
+    const uint64_t *__restrict__ q_codes, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
+    float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2) {
+    constexpr int JT = DV / 32;
+    constexpr int kKeyChunk = DV > 64 ? 64 : 128;     // keys staged in LDS at a time (<= 40 KB)
+    __shared__ __attribute__((aligned(16))) uint64_t kc_s[kKeyChunk * W];
+    __shared__ __attribute__((aligned(16))) float v_s[kKeyChunk * DV];
+    __shared__ float den_s[kMaxWaves * 32];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_threads = blockDim.x;
+    const long bh = blockIdx.x / q_chunks;
+    const int chunk = blockIdx.x % q_chunks;
     const int b = (int)(bh / H), h = (int)(bh % H);
-    const int i = chunk * 64 + lane;
-    const int i_ld = min(i, Nq - 1);
+    const int i_loc = lane & 31, kk = lane >> 5;
+    const int qi = chunk * (kMaxWaves * 32) + wave * 32 + i_loc;      // this lane's query
+    const int qi_ld = min(qi, Nq - 1);
 
     uint64_t q[W];
 #pragma unroll
-    for (int w = 0; w < W; ++w) q[w] = q_codes[((size_t)bh * Nq + i_ld) * W + w];
+    for (int w = 0; w < W; ++w) q[w] = q_codes[((size_t)bh * Nq + qi_ld) * W + w];
+    const uint64_t *kc_g = k_codes + (size_t)bh * Nk * W;
 
-    const uint64_t *kc = k_codes + (size_t)bh * Nk * W;
     int dref = 0;
     if (ROWREF) {
-        // the distance whose score scale*S is largest: smallest if scale >= 0 (c2 <= 0)
+        // the distance whose score scale*S is largest: the smallest if scale >= 0 (c2 <= 0)
         int dmin = 1 << 30, dmax = -1;
-        for (int j = 0; j < Nk; ++j) {
-            int dist = 0;
-#pragma unroll
-            for (int w = 0; w < W; ++w) dist += __builtin_popcountll(q[w] ^ kc[(size_t)j * W + w]);
-            dmin = min(dmin, dist);
-            dmax = max(dmax, dist);
+        for (int j0 = 0; j0 < Nk; j0 += kKeyChunk) {
+            const int n = min(kKeyChunk, Nk - j0);
+            __syncthreads();
+            for (int t = tid; t < n * W; t += n_threads) kc_s[t] = kc_g[(size_t)j0 * W + t];
+            __syncthreads();
+            for (int j = 0; j < n; ++j) {
+                const int dist = distance<W>(q, kc_s + j * W);
+                dmin = min(dmin, dist);
+                dmax = max(dmax, dist);
+            }
         }
         dref = (c2 <= 0.0f) ? dmin : dmax;
     }
 
-    float acc[DV];
+    v16f acc[JT];
 #pragma unroll
-    for (int c = 0; c < DV; ++c) acc[c] = 0.0f;
+    for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
     float den = 0.0f;
-    for (int j = 0; j < Nk; ++j) {
-        int dist = 0;
+
+    for (int j0 = 0; j0 < Nk; j0 += kKeyChunk) {
+        const int n = min(kKeyChunk, Nk - j0);
+        const int n_pad = (n + 1) & ~1;
+        __syncthreads();                           // the previous chunk has been consumed
+        for (int t = tid; t < n_pad * W; t += n_threads) kc_s[t] = (t < n * W) ? kc_g[(size_t)j0 * W + t] : 0ull;
+        for (int t = tid; t < n_pad * (DV / 4); t += n_threads) {
+            const int j = t / (DV / 4), c4 = t % (DV / 4);
+            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);   // rows past the last key must be finite: 0 * v
+            if (j < n) val = *reinterpret_cast<const float4 *>(v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c4 * 4);
+            *reinterpret_cast<float4 *>(v_s + j * DV + c4 * 4) = val;
+        }
+        __syncthreads();
+        for (int k0 = 0; k0 < n_pad; k0 += 2) {
+            const int j = k0 + kk;                 // lanes 0..31 take key k0, lanes 32..63 key k0 + 1
+            const int dist = distance<W>(q, kc_s + j * W);
+            float p = __builtin_amdgcn_exp2f(c2 * (float)(dist - dref));
+            p = (j < n) ? p : 0.0f;
+            den += p;
 #pragma unroll
-        for (int w = 0; w < W; ++w) dist += __builtin_popcountll(q[w] ^ kc[(size_t)j * W + w]);   // kc: uniform
-        const float p = __builtin_amdgcn_exp2f(c2 * (float)(dist - dref));
-        den += p;
-        const float *vr = v + (((size_t)b * Nk + j) * H + h) * DV;                                // uniform
-#pragma unroll
-        for (int c = 0; c < DV; ++c) acc[c] = __builtin_fmaf(p, vr[c], acc[c]);
+            for (int jt = 0; jt < JT; ++jt)
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(p, v_s[j * DV + jt * 32 + i_loc], acc[jt], 0, 0, 0);
+        }
     }
-    if (i < Nq) {
-        const float inv = 1.0f / den;
-        float *o = out + (((size_t)b * Nq + i) * H + h) * DV;
+
+    // row sums: the two half-wavefronts hold the even / odd keys of the same 32 queries
+    den += __shfl_xor(den, 32);
+    if (lane < 32) den_s[wave * 32 + lane] = den;
+    __syncthreads();
+    const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
 #pragma unroll
-        for (int c = 0; c < DV; c += 4)
-            *reinterpret_cast<float4 *>(o + c) =
-                make_float4(acc[c] * inv, acc[c + 1] * inv, acc[c + 2] * inv, acc[c + 3] * inv);
+    for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * kk + (r & 3);      // accumulator row held in register r
+        const int qo = q_tile0 + row;
+        if (qo < Nq) {
+            const float inv = 1.0f / den_s[wave * 32 + row];
+            float *o = out + (((size_t)b * Nq + qo) * H + h) * DV + i_loc;
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) o[jt * 32] = acc[jt][r] * inv;
+        }
     }
 }
 
@@ -96,24 +144,32 @@ __global__ __launch_bounds__(256) void hamming_scores_kernel(const uint64_t *__r
     scores[idx] = (int16_t)(W * 64 - 2 * dist);
 }
 
+struct Launch {
+    dim3 grid, block;
+    hipStream_t st;
+    const uint64_t *q, *k;
+    const float *v;
+    float *out;
+    int H, Nq, Nk, q_chunks;
+    float c2;
+    bool rowref;
+};
+
 template <int DV, int W>
-void launch_hamming(bool rowref, dim3 grid, hipStream_t st, const uint64_t *q, const uint64_t *k,
-                    const float *v, float *out, int H, int Nq, int Nk, int n_chunks, long n_tasks,
-                    float c2) {
-    if (rowref)
-        hamming_kernel<DV, W, true><<<grid, dim3(256), 0, st>>>(q, k, v, out, H, Nq, Nk, n_chunks, n_tasks, c2);
+void launch_hamming(const Launch &L) {
+    if (L.rowref)
+        hamming_mfma_kernel<DV, W, true><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2);
     else
-        hamming_kernel<DV, W, false><<<grid, dim3(256), 0, st>>>(q, k, v, out, H, Nq, Nk, n_chunks, n_tasks, c2);
+        hamming_mfma_kernel<DV, W, false><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2);
 }
 
 template <int DV>
-int dispatch_w(int W, bool rowref, dim3 grid, hipStream_t st, const uint64_t *q, const uint64_t *k,
-               const float *v, float *out, int H, int Nq, int Nk, int n_chunks, long n_tasks, float c2) {
+int dispatch_w(int W, const Launch &L) {
     switch (W) {
-        case 1: launch_hamming<DV, 1>(rowref, grid, st, q, k, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
-        case 2: launch_hamming<DV, 2>(rowref, grid, st, q, k, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
-        case 4: launch_hamming<DV, 4>(rowref, grid, st, q, k, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
-        case 8: launch_hamming<DV, 8>(rowref, grid, st, q, k, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
+        case 1: launch_hamming<DV, 1>(L); break;
+        case 2: launch_hamming<DV, 2>(L); break;
+        case 4: launch_hamming<DV, 4>(L); break;
+        case 8: launch_hamming<DV, 8>(L); break;
         default:
             return sa::fail(SA_ERR_UNSUPPORTED, "sa_hamming_attention: nbits must be 64, 128, 256 or 512");
     }
@@ -143,19 +199,25 @@ extern "C" int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_c
     hipStream_t st = sa::as_stream(stream);
     const int W = nbits / 64;
     const long BH = (long)B * H;
-    const int n_chunks = (Nq + 63) / 64;
-    const long n_tasks = BH * n_chunks;
-    const long blocks = (n_tasks + 3) / 4;
+    const int q_per_block = kMaxWaves * 32;
+    const int q_chunks = (Nq + q_per_block - 1) / q_per_block;
+    const int waves = Nq >= q_per_block ? kMaxWaves : (Nq + 31) / 32;   // uniform per launch
+    const long blocks = BH * q_chunks;
     SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_hamming_attention: grid too large");
-    const float c2 = -2.0f * scale * 1.4426950408889634f;
+    Launch L;
+    L.grid = dim3((unsigned)blocks);
+    L.block = dim3(q_chunks > 1 ? kMaxWaves * kWave : waves * kWave);
+    L.st = st;
+    L.q = q_codes; L.k = k_codes; L.v = v; L.out = out;
+    L.H = H; L.Nq = Nq; L.Nk = Nk; L.q_chunks = q_chunks;
+    L.c2 = -2.0f * scale * 1.4426950408889634f;
     // exp2 of c2*dist stays a normal float for every possible distance -> no row reference needed
-    const bool rowref = !(scale >= 0.0f && -c2 * (float)nbits <= 100.0f);
-    const dim3 grid((unsigned)blocks);
+    L.rowref = !(scale >= 0.0f && -L.c2 * (float)nbits <= 100.0f);
     int rc;
     switch (dv) {
-        case 32: rc = dispatch_w<32>(W, rowref, grid, st, q_codes, k_codes, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
-        case 64: rc = dispatch_w<64>(W, rowref, grid, st, q_codes, k_codes, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
-        default: rc = dispatch_w<128>(W, rowref, grid, st, q_codes, k_codes, v, out, H, Nq, Nk, n_chunks, n_tasks, c2); break;
+        case 32: rc = dispatch_w<32>(W, L); break;
+        case 64: rc = dispatch_w<64>(W, L); break;
+        default: rc = dispatch_w<128>(W, L); break;
     }
     if (rc != SA_OK) return rc;
     rc = sa::check_launch("sa_hamming_attention");

@@ -32,12 +32,41 @@ def test_binarize_projection_bit_exact(sa, B, N, H, d, nbits):
     x = g.standard_normal((B, N, H, d), dtype=np.float32)
     pr = g.standard_normal((d, nbits), dtype=np.float32)
     ref = oracle.binarize(x, pr, nbits)
-    got = codes_host(sa.sa_binarize(dev(x), dev(pr), nbits))
-    assert got.shape == ref.shape
-    assert np.array_equal(got, ref)
+    for variant in (0, 1, None):      # chain on the VALU, matrix-core pre-pass + exact fallback, default
+        got = codes_host(sa.sa_binarize(dev(x), dev(pr), nbits, variant=variant))
+        assert got.shape == ref.shape
+        assert np.array_equal(got, ref), "variant %s" % variant
 
 
-def test_binarize_near_cancelling_rows_bit_exact(sa):
+@pytest.mark.parametrize("variant", [0, 1])
+def test_binarize_degenerate_rows_bit_exact(sa, variant):
+    """Data on which the matrix-core pre-pass settles nothing: zero rows, rows orthogonal to many hash
+    columns, huge and tiny magnitudes, NaN / Inf.  Every such bit must come from the defining chain."""
+    g = np.random.default_rng(8)
+    d, nbits = 64, 128
+    x = g.standard_normal((1, 300, 2, d), dtype=np.float32)
+    pr = g.standard_normal((d, nbits), dtype=np.float32)
+    pr[:, 5] = 0.0                      # a dead hash column
+    pr[32:, 9] = 0.0
+    x[0, 0:40] = 0.0                    # zero rows
+    x[0, 40:60, :, 32:] = 0.0
+    x[0, 40:60, :, :32] = 1.0
+    x[0, 60:70] *= np.float32(1e30)     # squares overflow
+    x[0, 70:80] *= np.float32(1e-30)    # squares underflow
+    x[0, 80:90] *= np.float32(1e-38)    # denormal products
+    x[0, 90, 0, 3] = np.nan
+    x[0, 91, 1, 7] = np.inf
+    x[0, 92, 0, 0] = -np.inf
+    x[0, 100:140] = np.round(x[0, 100:140] * 2) / 2    # many exact ties at zero are likely
+    pr_i = np.round(pr * 2) / 2
+    for p in (pr, pr_i.astype(np.float32)):
+        ref = oracle.binarize(x, p, nbits)
+        got = codes_host(sa.sa_binarize(dev(x), dev(p), nbits, variant=variant))
+        assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_binarize_near_cancelling_rows_bit_exact(sa, variant):
     """Rows built to make many projections cancel almost exactly: only the defined
     summation order reproduces these signs."""
     g = np.random.default_rng(2)
@@ -52,7 +81,7 @@ def test_binarize_near_cancelling_rows_bit_exact(sa):
             s = x64[0, n, h, : d - 1] @ pr[: d - 1, j].astype(np.float64)
             x[0, n, h, d - 1] = np.float32(-s / np.float64(pr[d - 1, j]))
     ref = oracle.binarize(x, pr, nbits)
-    got = codes_host(sa.sa_binarize(dev(x), dev(pr), nbits))
+    got = codes_host(sa.sa_binarize(dev(x), dev(pr), nbits, variant=variant))
     assert np.array_equal(got, ref)
 
 
