@@ -1,7 +1,9 @@
 // sa_block_forward: one pass of the reparameterised block (Eq. 2 restricted to the
 // attention MatMuls and the MLP): hash Q and K, additive or Hamming attention, then the
-// Shift MLP or the two-expert MoE.  Pure composition of the library's own entry points
-// on one stream; the expert row counts stay on the device (no host round trip).
+// Shift MLP or the two-expert MoE.  Pure composition of the library's own entry points;
+// the expert row counts stay on the device (no host round trip).
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -63,6 +65,50 @@ extern "C" size_t sa_block_workspace_bytes(const sa_block_desc *desc) {
     return L.total;
 }
 
+namespace {
+
+// The two experts are independent once the routing lists exist (the paper's "experts run in
+// parallel", Sec. 4.2), and neither fills the chip on its own at these sizes.  The Mult expert
+// and the routing therefore run on a second stream of the library's own, forked from and joined
+// back into the caller's stream with events, so that from the caller's point of view everything
+// is still ordered on the one stream it passed in.  One side stream and one set of events per
+// device, created on first use at the default priority; concurrent sa_block_forward calls from
+// several host threads serialise on the enqueue.
+struct SideLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, routed = nullptr, attended = nullptr, joined = nullptr;
+    bool ready = false;
+};
+
+std::mutex g_lane_mutex;
+SideLane g_lanes[16];
+
+int side_lane(SideLane **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16)
+        return sa::fail(SA_ERR_HIP, "block: cannot identify the current device");
+    SideLane &l = g_lanes[dev];
+    if (!l.ready) {
+        if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&l.routed, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&l.attended, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&l.joined, hipEventDisableTiming) != hipSuccess)
+            return sa::fail(SA_ERR_HIP, "block: cannot create the side stream");
+        l.ready = true;
+    }
+    *out = &l;
+    return SA_OK;
+}
+
+#define SA_HIP(call)                                                                      \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) return sa::fail(SA_ERR_HIP, "block: %s", hipGetErrorString(e_)); \
+    } while (0)
+
+}  // namespace
+
 extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     sa::clear_error();
     Layout L;
@@ -81,6 +127,27 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     const long T = (long)d->B * d->N;
     const int E = d->H * d->dv;
 
+    hipStream_t main_st = sa::as_stream(stream);
+    const bool moe = d->hid > 0 && d->moe;
+    SideLane *lane = nullptr;
+    std::unique_lock<std::mutex> lock(g_lane_mutex, std::defer_lock);
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
+    int32_t *expert_of = reinterpret_cast<int32_t *>(ws + L.expert_of);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
+    float *gate = reinterpret_cast<float *>(ws + L.gate);
+    if (moe) {
+        // side lane: routing needs nothing but the logits, so it starts right away
+        lock.lock();
+        rc = side_lane(&lane);
+        if (rc != SA_OK) return rc;
+        SA_HIP(hipEventRecord(lane->fork, main_st));
+        SA_HIP(hipStreamWaitEvent(lane->stream, lane->fork, 0));
+        rc = sa_moe_dispatch(d->logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes,
+                             lane->stream);
+        if (rc != SA_OK) return rc;
+        SA_HIP(hipEventRecord(lane->routed, lane->stream));
+    }
+
     rc = sa_binarize(d->q, d->B, d->N, d->H, d->d, d->proj, d->nbits, qc, stream);
     if (rc != SA_OK) return rc;
     rc = sa_binarize(d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, kc, stream);
@@ -94,24 +161,30 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     }
     if (rc != SA_OK || d->hid == 0) return rc;
 
+    if (moe) {
+        // Mult expert on the side lane as soon as the attention output exists
+        SA_HIP(hipEventRecord(lane->attended, main_st));
+        SA_HIP(hipStreamWaitEvent(lane->stream, lane->attended, 0));
+        const sa_rows mult_rows{perm, counts, 0, T};
+        rc = sa_mult_mlp_f16(d->o, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3, ws + L.mult_ws,
+                             L.mult_ws_bytes, lane->stream);
+        if (rc != SA_OK) return rc;
+        SA_HIP(hipEventRecord(lane->joined, lane->stream));
+    }
+
     int8_t *xq = reinterpret_cast<int8_t *>(ws + L.xq);
     rc = sa_quantize_act(d->o, T * E, d->act_inv_scale, xq, stream);
     if (rc != SA_OK) return rc;
-    if (!d->moe) {
+    if (!moe) {
         const sa_rows all{nullptr, nullptr, 0, T};
         return sa_shift_mlp(xq, &all, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, nullptr,
                             d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
     }
-    int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
-    int32_t *expert_of = reinterpret_cast<int32_t *>(ws + L.expert_of);
-    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
-    float *gate = reinterpret_cast<float *>(ws + L.gate);
-    rc = sa_moe_dispatch(d->logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes, stream);
+    SA_HIP(hipStreamWaitEvent(main_st, lane->routed, 0));
+    const sa_rows shift_rows{perm, counts, 1, T};
+    rc = sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
+                      d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
     if (rc != SA_OK) return rc;
-    const sa_rows mult_rows{perm, counts, 0, T}, shift_rows{perm, counts, 1, T};
-    rc = sa_mult_mlp_f16(d->o, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3, ws + L.mult_ws,
-                         L.mult_ws_bytes, stream);
-    if (rc != SA_OK) return rc;
-    return sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
-                        d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
+    SA_HIP(hipStreamWaitEvent(main_st, lane->joined, 0));     // the caller's stream sees both experts done
+    return SA_OK;
 }
