@@ -6,7 +6,7 @@
 // 32x32 MFMA tiles.  K advances 64 bytes per stage through a double-buffered LDS tile that
 // is filled by direct global->LDS loads (no register staging): while stage s is multiplied
 // out of one buffer, the loads of stage s+1 are in flight into the other; one barrier per
-// stage.  A direct load writes 1 KiB of consecutive LDS per wavefront instruction, so LDS
+// stage, and the LDS fragment reads run one half-stage ahead of the MFMAs that consume them.  A direct load writes 1 KiB of consecutive LDS per wavefront instruction, so LDS
 // rows cannot be padded; instead the 16-byte chunks of a row are XOR-swizzled with the row
 // number (the lane chooses which global chunk it fetches), which makes the 16-byte fragment
 // reads of any 16 consecutive rows hit 16 different bank groups.
@@ -15,18 +15,27 @@
 // and one barrier per stage), and the compiler must not serialise the reads of the current
 // buffer behind the loads in flight into the other one.
 //
-// Narrow outputs (int8 / fp16 hidden rows) leave through LDS so that every lane stores 16
-// bytes of one row; 32-bit outputs are stored straight from the accumulators (a 32x32 tile
-// row is 128 contiguous bytes).
+// Outputs leave through LDS, 64 rows per pass, so that every lane stores 16 bytes of one row
+// (a scattered destination row index and its gate are then fetched once per 16 bytes).
 #pragma once
+
+#include <type_traits>
+#include <utility>
 
 #include "common.h"
 #include "gemm_common.h"
 
 namespace sa {
 
-constexpr int kStageBytes = 64;                 // bytes of K per stage and row
-constexpr int kChunksPerRow = kStageBytes / 16; // 16-byte chunks per LDS row
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time.
+template <int... I, class F>
+__device__ inline void static_for_impl(std::integer_sequence<int, I...>, F &&f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ inline void static_for(F &&f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
 
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
@@ -62,29 +71,45 @@ struct GemmArgs {
     int K, N;
 };
 
-// Physical 16-byte chunk of logical chunk c in LDS row r.
+// Physical 16-byte chunk of logical chunk c in LDS row r, for rows of CPR chunks.
+template <int CPR>
 __device__ inline int swizzle(int r, int c) {
-    return c ^ ((r / (16 / kChunksPerRow)) & (kChunksPerRow - 1));
+    return c ^ ((r / (16 / CPR)) & (CPR - 1));
 }
 
-// One wavefront-wide direct load: lane l's 16 bytes at `src` land at LDS byte lds_base + 16 * l.
+// One wavefront-wide direct load: lane l's 16 bytes at `src` land at LDS byte lds_base + 16 * l
+// (lds_base is the same in every lane).
 __device__ inline void load_to_lds_16(const void *src, uint32_t lds_base) {
     asm volatile(
         "s_mov_b32 m0, %0\n\t"
         "s_nop 0\n\t"
         "global_load_lds_dwordx4 %1, off\n\t"
         :
-        : "s"(lds_base), "v"(src)
+        : "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src)
         : "memory");
 }
 
-// A Store type provides
-//   static constexpr int kPackedBytes : 0 = 32-bit output stored per element with
-//       void direct(long m, int n, acc, const int32_t *rows) const
-//     1 or 2 = narrow output [max_rows, N] written through LDS with
-//       uint32_t convert(acc, const uint8_t *lds_table) const,  void *out,  const void *table (256 B or null)
-template <class T, int BM, int BN, class Store>
-__global__ __launch_bounds__(256, 2) void gemm_nt_kernel(GemmArgs g, Store store) {
+// A Store type says how accumulators become output rows:
+//   static constexpr int  kBytes      : bytes per output element (1, 2 or 4)
+//   static constexpr int  kTableBytes : 0, or 256 for a byte table that is copied into LDS
+//   static constexpr bool kScatter    : output row of tile row m is sel.rows[m] (else m)
+//   uint32_t convert(acc, int n, const uint8_t *lds_table) const : the element's bits for column n
+//   void *out : [rows, N] elements;  const void *table;  const float *gate : null, or a factor per
+//       destination row that multiplies fp32 outputs (kScatter && kBytes == 4 only)
+// Wait until at most N of this wavefront's vector-memory loads are still in flight (loads
+// complete in issue order, so the oldest ones are the ones that have landed).
+template <int N>
+__device__ inline void wait_loads_in_flight() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <class T, int BM, int BN, int SB, int NS, int LS, int OCC, class Store>
+__global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store store) {
+    constexpr int kStageBytes = SB;                     // bytes of K per stage and row
+    constexpr int kChunksPerRow = SB / 16;              // 16-byte chunks per LDS row
+    constexpr int KK = SB / 32;                         // 32-byte MFMA steps per stage
+    static_assert(SB == 64 || SB == 128, "stage rows of 64 or 128 bytes");
     constexpr int NP = T::kPlanes;
     constexpr int MI = BM / 64, NJ = BN / 64;           // 32x32 tiles per wavefront
     constexpr int A_BYTES = BM * kStageBytes, B_BYTES = BN * kStageBytes;
@@ -92,9 +117,13 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(GemmArgs g, Store store
     constexpr int ROWS_PER_INSTR = 1024 / kStageBytes;  // LDS rows one wavefront load fills
     constexpr int A_INSTR = BM / ROWS_PER_INSTR / 4;    // loads per wavefront and stage
     constexpr int B_INSTR = BN / ROWS_PER_INSTR / 4;
-    constexpr int ES = Store::kPackedBytes;
-    constexpr int EPI_BYTES = ES ? BM * BN * ES + Store::kTableBytes : 0;
-    constexpr int LDS_BYTES = 2 * STAGE > EPI_BYTES ? 2 * STAGE : EPI_BYTES;
+    constexpr int ES = Store::kBytes;
+    constexpr int SLAB_BYTES = 64 * BN * ES;            // epilogue staging: one 32-row slab per wavefront row
+    constexpr int EPI_BYTES = SLAB_BYTES + Store::kTableBytes;
+    constexpr int LOADS = A_INSTR + NP * B_INSTR;       // direct loads per wavefront and stage
+    constexpr int LDS_BYTES = NS * STAGE > EPI_BYTES ? NS * STAGE : EPI_BYTES;
+    static_assert(NS == 2 || NS == 3, "ring of two or three stages");
+    static_assert(LDS_BYTES * OCC <= 160 * 1024, "OCC workgroups of this tile do not fit the LDS of a CU");
     __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
 
     const int32_t *rows;
@@ -122,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(GemmArgs g, Store store
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i) {
         const int r = (wave * A_INSTR + i) * ROWS_PER_INSTR + lane / kChunksPerRow;
-        const int c = swizzle(r, lane % kChunksPerRow);
+        const int c = swizzle<kChunksPerRow>(r, lane % kChunksPerRow);
         long m = m0 + r;
         m = m < n_rows ? m : n_rows - 1;
         const long src = (g.gather_a && rows) ? (long)rows[m] : m;
@@ -132,22 +161,26 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(GemmArgs g, Store store
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i) {
         const int r = (wave * B_INSTR + i) * ROWS_PER_INSTR + lane / kChunksPerRow;
-        const int c = swizzle(r, lane % kChunksPerRow);
+        const int c = swizzle<kChunksPerRow>(r, lane % kChunksPerRow);
         const int n = min(n0 + r, N - 1);
 #pragma unroll
         for (int p = 0; p < NP; ++p)
             b_src[p][i] = static_cast<const uint8_t *>(g.b[p]) + (size_t)n * row_bytes + c * 16;
     }
 
-    auto issue_stage = [&](int buf, int kbyte) {
+    // Direct load number q (0 .. LOADS-1) of a stage: A rows first, then the B planes.
+    auto issue_load = [&](int q, int buf, int kbyte) {
         const uint32_t base = lds_base + buf * STAGE;
+        if (q < A_INSTR) {
+            load_to_lds_16(a_src[q] + kbyte, base + (wave * A_INSTR + q) * 1024);
+        } else {
+            const int p = (q - A_INSTR) / B_INSTR, i = (q - A_INSTR) % B_INSTR;
+            load_to_lds_16(b_src[p][i] + kbyte, base + A_BYTES + p * B_BYTES + (wave * B_INSTR + i) * 1024);
+        }
+    };
+    auto issue_stage = [&](int buf, int kbyte) {
 #pragma unroll
-        for (int i = 0; i < A_INSTR; ++i) load_to_lds_16(a_src[i] + kbyte, base + (wave * A_INSTR + i) * 1024);
-#pragma unroll
-        for (int p = 0; p < NP; ++p)
-#pragma unroll
-            for (int i = 0; i < B_INSTR; ++i)
-                load_to_lds_16(b_src[p][i] + kbyte, base + A_BYTES + p * B_BYTES + (wave * B_INSTR + i) * 1024);
+        for (int q = 0; q < LOADS; ++q) issue_load(q, buf, kbyte);
     };
 
     typename T::Acc acc[MI][NJ];
@@ -158,121 +191,217 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(GemmArgs g, Store store
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // fragment read offsets (bytes inside a tile) for the two 32-byte halves of a stage
+    // fragment read offsets (bytes inside a tile) for the 32-byte steps of a stage
     const int fr = lane & 31, fg = lane >> 5;
-    int a_rd[MI][2], b_rd[NJ][2];
+    int a_rd[MI][KK], b_rd[NJ][KK];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+    for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int r = wm + i * 32 + fr;
-            a_rd[i][kk] = r * kStageBytes + swizzle(r, 2 * kk + fg) * 16;
+            a_rd[i][kk] = r * kStageBytes + swizzle<kChunksPerRow>(r, 2 * kk + fg) * 16;
         }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             const int r = wn + j * 32 + fr;
-            b_rd[j][kk] = r * kStageBytes + swizzle(r, 2 * kk + fg) * 16;
+            b_rd[j][kk] = r * kStageBytes + swizzle<kChunksPerRow>(r, 2 * kk + fg) * 16;
         }
     }
 
-    const int n_stages = (int)(row_bytes / kStageBytes);
-    issue_stage(0, 0);
-    for (int s = 0; s < n_stages; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's loads of stage s have landed
-        __syncthreads();                         // ... everyone's have, and everyone is done with the other buffer
-        if (s + 1 < n_stages) issue_stage((s + 1) & 1, (s + 1) * kStageBytes);
-        const uint8_t *A = lds + (s & 1) * STAGE;
+    auto read_frags = [&](const uint8_t *A, int kk, uint4 (&af)[MI], uint4 (&bf)[NP][NJ]) {
         const uint8_t *B = A + A_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            uint4 af[MI], bf[NP][NJ];
+        for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const uint4 *>(A + a_rd[i][kk]);
 #pragma unroll
-            for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const uint4 *>(A + a_rd[i][kk]);
+        for (int p = 0; p < NP; ++p)
 #pragma unroll
-            for (int p = 0; p < NP; ++p)
+            for (int j = 0; j < NJ; ++j) bf[p][j] = *reinterpret_cast<const uint4 *>(B + p * B_BYTES + b_rd[j][kk]);
+    };
+    // One 32-byte step of MFMAs.  When phase >= 0, the direct loads [phase * LPS, (phase+1) * LPS)
+    // of the stage at byte kbyte are issued into ring slot `slot`, evenly spaced between the MFMAs:
+    // a wavefront that issues its loads back to back stalls on the full vector-memory queue
+    // (about 1 KiB per 16 cycles and CU) and leaves its matrix core idle meanwhile.
+    constexpr int MFMAS = NP * MI * NJ;
+    constexpr int LPS = (LOADS + LS - 1) / LS;          // loads per step
+    auto multiply = [&](const uint4 (&af)[MI], const uint4 (&bf)[NP][NJ], auto phase_c, bool more, int slot, int kbyte) {
+        constexpr int phase = decltype(phase_c)::value;
+        static_for<MFMAS>([&](auto m_c) {
+            constexpr int m = decltype(m_c)::value;             // MFMAs issued before this one
+            constexpr int p = m / (MI * NJ), i = m / NJ % MI, j = m % NJ;
+            acc[i][j] = T::mma(af[i], bf[p][j], acc[i][j]);
+            // loads [m * LPS / MFMAS, (m + 1) * LPS / MFMAS) of this step's share follow MFMA m
+            if constexpr (phase >= 0) {
+                constexpr int q0 = m * LPS / MFMAS, q1 = (m + 1) * LPS / MFMAS;
+                if constexpr (q1 > q0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<q1 - q0>([&](auto d_c) {
+                        constexpr int q = phase * LPS + q0 + decltype(d_c)::value;
+                        if constexpr (q < LOADS)
+                            if (more) issue_load(q, slot, kbyte);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        });
+    };
+
+    // Software pipeline over a ring of NS stage buffers, all of them loaded ahead.  The LDS
+    // fragment reads of one 32-byte step take about half as long as its MFMAs, so they are issued
+    // one step ahead and run under the matrix cores.  The barrier that hands over stage s+1 sits
+    // before the last step of stage s: by then every fragment of stage s is in registers, so the
+    // slot of stage s is free for stage s+NS, whose loads are spread over that last step and the
+    // first LS-1 steps of stage s+1; the first fragments of stage s+1 are read under the MFMAs
+    // of the last step.
+    static_assert(LS >= 1 && LS <= KK, "loads of a stage are spread over at most one stage of steps");
+    const int n_stages = (int)(row_bytes / kStageBytes);
+    uint4 af[2][MI], bf[2][NP][NJ];
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
-                    bf[p][j] = *reinterpret_cast<const uint4 *>(B + p * B_BYTES + b_rd[j][kk]);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) acc[i][j] = T::mma(af[i], bf[p][j], acc[i][j]);
-        }
+    for (int q = 0; q < NS; ++q)
+        if (q < n_stages) issue_stage(q, q * kStageBytes);
+    // this wavefront's loads of stage 0 have landed (later stages may still be in flight)
+    if (NS == 3 && n_stages > 2)
+        wait_loads_in_flight<2 * LOADS>();
+    else if (n_stages > 1)
+        wait_loads_in_flight<LOADS>();
+    else
+        wait_loads_in_flight<0>();
+    __syncthreads();                             // ... and everyone's
+    read_frags(lds, 0, af[0], bf[0]);
+    int buf = 0, prev = NS - 1;                  // ring slots of stage s and of stage s-1
+    for (int s = 0; s < n_stages; ++s) {
+        const uint8_t *cur = lds + buf * STAGE;
+        const int nxt = buf + 1 == NS ? 0 : buf + 1;
+        static_for<KK>([&](auto kk_c) {
+            constexpr int kk = decltype(kk_c)::value;
+            if constexpr (kk + 1 < KK) {
+                read_frags(cur, kk + 1, af[(kk + 1) & 1], bf[(kk + 1) & 1]);
+            } else if (s + 1 < n_stages) {
+                // stage s+1 has landed (this wavefront's part); with a ring of three, stage s+2 may be in flight
+                if (NS == 3 && s + 2 < n_stages)
+                    wait_loads_in_flight<LOADS>();
+                else
+                    wait_loads_in_flight<0>();
+                __syncthreads();                 // everyone's has, and everyone holds its last fragments of stage s
+                read_frags(lds + nxt * STAGE, 0, af[0], bf[0]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (kk == KK - 1) {
+                // first share of stage s+NS, into the slot this stage has just left
+                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, 0>{}, s + NS < n_stages, buf, (s + NS) * kStageBytes);
+            } else if constexpr (kk + 1 < LS) {
+                // further shares of stage s-1+NS, into the slot of stage s-1
+                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, kk + 1>{}, s >= 1 && s - 1 + NS < n_stages, prev,
+                         (s - 1 + NS) * kStageBytes);
+            } else {
+                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, -1>{}, false, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        prev = buf;
+        buf = nxt;
     }
 
-    if constexpr (ES == 0) {
+    // ---- epilogue.  Every output leaves through LDS so that a lane stores 16 contiguous bytes of
+    //      one row: per pass, each wavefront converts one 32-row slab of its accumulators into a
+    //      64 x BN staging tile, then the workgroup writes the 64 rows out.
+    constexpr int CPR = BN * ES / 16;             // 16-byte chunks per staged row
+    constexpr int PER_THREAD = 64 * CPR / 256;
+    static_assert(PER_THREAD >= 1, "a staged slab has at least one chunk per thread");
+    uint8_t *tile = lds;
+    uint8_t *table = lds + SLAB_BYTES;
+    const size_t out_row_bytes = (size_t)N * ES;
+    const bool whole_chunks = out_row_bytes % 16 == 0;
+    __syncthreads();                              // the last stage has been read
+    if (Store::kTableBytes != 0) table[tid] = static_cast<const uint8_t *>(store.table)[tid];
+    static_for<MI>([&](auto i_c) {
+        constexpr int i = decltype(i_c)::value;
+        __syncthreads();                          // the staging tile is free (and the table is there)
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int j = 0; j < NJ; ++j) {
+            const int nl = wn + j * 32 + (lane & 31);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const int n = n0 + wn + j * 32 + (lane & 31);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const long m = m0 + wm + i * 32 + mfma32_row(r, lane);
-                    if (m < n_rows && n < N) store.direct(m, n, acc[i][j][r], rows);
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int ml = (wave >> 1) * 32 + mfma32_row(r, lane);
+                const uint32_t v = store.convert(acc[i][j][r], min(n0 + nl, N - 1), table);
+                if (ES == 1)
+                    tile[ml * BN + nl] = (uint8_t)v;
+                else if (ES == 2)
+                    reinterpret_cast<uint16_t *>(tile)[ml * BN + nl] = (uint16_t)v;
+                else
+                    reinterpret_cast<uint32_t *>(tile)[ml * BN + nl] = v;
             }
-    } else {
-        // narrow output: convert, lay the BM x BN tile out row-major in LDS, store 16 B per lane
-        uint8_t *tile = lds;
-        uint8_t *table = lds + BM * BN * ES;
-        __syncthreads();                          // the last stage has been read
-        if (Store::kTableBytes != 0) table[tid] = static_cast<const uint8_t *>(store.table)[tid];
+        }
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const int nl = wn + j * 32 + (lane & 31);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int ml = wm + i * 32 + mfma32_row(r, lane);
-                    const uint32_t v = store.convert(acc[i][j][r], table);
-                    if (ES == 1)
-                        tile[ml * BN + nl] = (uint8_t)v;
-                    else
-                        reinterpret_cast<uint16_t *>(tile)[ml * BN + nl] = (uint16_t)v;
-                }
-            }
-        __syncthreads();
-        constexpr int CPR = BN * ES / 16;         // 16-byte chunks per tile row
-        constexpr int PER_THREAD = BM * CPR / 256;
-        const size_t out_row_bytes = (size_t)N * ES;
 #pragma unroll
         for (int q = 0; q < PER_THREAD; ++q) {
             const int c = tid + 256 * q;
             const int ml = c / CPR, cc = c % CPR;
-            const long m = m0 + ml;
+            const long m = m0 + (ml >> 5) * (BM / 2) + i * 32 + (ml & 31);
             const int n = n0 + cc * (16 / ES);
-            if (m < n_rows && n < N)
-                *reinterpret_cast<uint4 *>(static_cast<uint8_t *>(store.out) + (size_t)m * out_row_bytes + (size_t)n * ES) =
-                    *reinterpret_cast<const uint4 *>(tile + (ml * CPR + cc) * 16);
+            if (m < n_rows && n < N) {
+                uint4 v = *reinterpret_cast<const uint4 *>(tile + (ml * CPR + cc) * 16);
+                const long t = (Store::kScatter && rows) ? (long)rows[m] : m;
+                if constexpr (ES == 4 && Store::kScatter) {
+                    if (store.gate) {
+                        const float gt = store.gate[t];
+                        v.x = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.x));
+                        v.y = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.y));
+                        v.z = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.z));
+                        v.w = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.w));
+                    }
+                }
+                uint8_t *dst = static_cast<uint8_t *>(store.out) + (size_t)t * out_row_bytes + (size_t)n * ES;
+                if (ES < 4 || whole_chunks) {
+                    *reinterpret_cast<uint4 *>(dst) = v;
+                } else {                          // 32-bit rows that are not a multiple of 16 bytes
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < N) reinterpret_cast<uint32_t *>(dst)[e] = w[e];
+                }
+            }
         }
-    }
+    });
 }
 
-template <class T, int BM, int BN, class Store>
+template <class T, int BM, int BN, int SB, int NS, int LS, int OCC, class Store>
 int launch_gemm_tile(const GemmArgs &g, const Store &store, hipStream_t st, const char *what) {
     const long row_tiles = (g.sel.max_rows + BM - 1) / BM;
     const long col_tiles = (g.N + BN - 1) / BN;
     const long blocks = (row_tiles + 7) / 8 * 8 * col_tiles;
     SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "%s: too many tiles for one launch", what);
     const dim3 grid((unsigned)blocks);
-    gemm_nt_kernel<T, BM, BN, Store><<<grid, dim3(256), 0, st>>>(g, store);
+    gemm_nt_kernel<T, BM, BN, SB, NS, LS, OCC, Store><<<grid, dim3(256), 0, st>>>(g, store);
     return check_launch(what);
 }
 
-// Tall tiles reuse the B fragments more; small problems need more, smaller workgroups.
-// Narrow outputs need N % 16 == 0 (whole 16-byte chunks per row).
+// Tile choice, from timings of the expert layers of the DeiT-Base block on one MI355X:
+//  * long rows (>= 2 KiB) in whole 128-byte lines: 128-byte stages pay (every request is a
+//    whole cache line); int8 takes the 256 x 128 tile, one workgroup per CU; fp16, whose
+//    steps hold half as many MFMAs, takes 64 x 128 with a ring of three, two per CU;
+//  * short rows leave only a few stages per tile, so prologue and epilogue must hide behind
+//    another resident workgroup: int8 takes 64-byte stages (two or three workgroups per CU),
+//    fp16 128 x 64 tiles with 128-byte stages (two per CU).
+// Narrow (1- and 2-byte) output rows must be whole 16-byte chunks; operand rows must be a
+// multiple of 64 bytes long.
 template <class T, class Store>
 int launch_gemm(const GemmArgs &g, const Store &store, hipStream_t st, const char *what) {
     if (g.sel.max_rows == 0 || g.N == 0) return SA_OK;
-    const long col_tiles = (g.N + 127) / 128;
-    const long blocks256 = ((g.sel.max_rows + 255) / 256) * col_tiles;
-    if (blocks256 >= 512) return launch_gemm_tile<T, 256, 128, Store>(g, store, st, what);
-    return launch_gemm_tile<T, 128, 128, Store>(g, store, st, what);
+    const size_t row_bytes = (size_t)g.K * T::kElemBytes;
+    SA_REQUIRE(row_bytes % 64 == 0 && row_bytes > 0, SA_ERR_SHAPE, "%s: rows of %zu bytes are not a multiple of 64", what, row_bytes);
+    SA_REQUIRE(Store::kBytes == 4 || (size_t)g.N * Store::kBytes % 16 == 0, SA_ERR_SHAPE,
+               "%s: narrow output rows of %d elements are not whole 16-byte chunks", what, g.N);
+    const bool lines = row_bytes % 128 == 0, long_rows = row_bytes >= 2048;
+    const long blocks256 = ((g.sel.max_rows + 255) / 256) * ((g.N + 127) / 128);
+    if constexpr (T::kPlanes == 2) {
+        if (lines && long_rows) return launch_gemm_tile<T, 256, 128, 128, 2, 2, 1, Store>(g, store, st, what);
+        if (blocks256 >= 512) return launch_gemm_tile<T, 256, 128, 64, 2, 1, 2, Store>(g, store, st, what);
+        return launch_gemm_tile<T, 128, 128, 64, 2, 1, 3, Store>(g, store, st, what);
+    } else {
+        if (lines && long_rows) return launch_gemm_tile<T, 64, 128, 128, 3, 2, 2, Store>(g, store, st, what);
+        if (lines) return launch_gemm_tile<T, 128, 64, 128, 2, 2, 2, Store>(g, store, st, what);
+        return launch_gemm_tile<T, 128, 128, 64, 3, 1, 2, Store>(g, store, st, what);
+    }
 }
 
 }  // namespace sa

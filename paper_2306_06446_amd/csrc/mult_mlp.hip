@@ -35,23 +35,18 @@ __global__ __launch_bounds__(256) void gather_half_kernel(const float4 *__restri
 
 template <int MODE>
 struct MultStore {
-    static constexpr int kPackedBytes = (MODE == kEpiGeluHalf) ? 2 : 0;
+    static constexpr int kBytes = (MODE == kEpiGeluHalf) ? 2 : 4;
     static constexpr int kTableBytes = 0;
-    Epilogue e;
-    int N;
-    void *out = nullptr;            // narrow output (fp16 hidden rows)
+    static constexpr bool kScatter = (MODE == kEpiScatterF32);
+    void *out;                      // compact fp32 rows | fp16 hidden rows | scattered fp32 rows
     const void *table = nullptr;
-    __device__ inline void direct(long m, int n, float a, const int32_t *rows) const {
-        if (MODE == kEpiFloat) {
-            e.of[(size_t)m * N + n] = a;
-        } else {
-            const long t = rows ? rows[m] : m;
-            const float g = e.gate ? e.gate[t] : 1.0f;
-            e.yf[(size_t)t * N + n] = g * a;
-        }
-    }
-    __device__ inline uint32_t convert(float a, const uint8_t *) const {
-        return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)gelu_erf(a));
+    const float *gate;
+    explicit MultStore(const Epilogue &epi)
+        : out(MODE == kEpiFloat ? (void *)epi.of : MODE == kEpiGeluHalf ? (void *)epi.hh : (void *)epi.yf),
+          gate(MODE == kEpiScatterF32 ? epi.gate : nullptr) {}
+    __device__ inline uint32_t convert(float a, int, const uint8_t *) const {
+        if (MODE == kEpiGeluHalf) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)gelu_erf(a));
+        return __builtin_bit_cast(uint32_t, a);
     }
 };
 
@@ -108,9 +103,9 @@ extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int h
         g.gather_a = false;
         g.K = E;
         g.N = hid;
-        MultStore<sa::kEpiGeluHalf> s1;
-        s1.out = hbuf;
-        s1.N = hid;
+        sa::Epilogue e1;
+        e1.hh = static_cast<_Float16 *>(hbuf);
+        MultStore<sa::kEpiGeluHalf> s1(e1);
         rc = sa::launch_gemm<sa::F16Traits>(g, s1, st, "sa_mult_mlp_f16(fc1)");
         if (rc != SA_OK) return rc;
     }
@@ -124,17 +119,17 @@ extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int h
     g2.K = hid;
     g2.N = E;
     if (out_or_null) {
-        MultStore<sa::kEpiFloat> s2;
-        s2.e.of = out_or_null;
-        s2.N = E;
+        sa::Epilogue e2;
+        e2.of = out_or_null;
+        MultStore<sa::kEpiFloat> s2(e2);
         rc = sa::launch_gemm<sa::F16Traits>(g2, s2, st, "sa_mult_mlp_f16(fc2)");
         if (rc != SA_OK) return rc;
     }
     if (y_or_null) {
-        MultStore<sa::kEpiScatterF32> s3;
-        s3.e.yf = y_or_null;
-        s3.e.gate = gate_or_null;
-        s3.N = E;
+        sa::Epilogue e3;
+        e3.yf = y_or_null;
+        e3.gate = gate_or_null;
+        MultStore<sa::kEpiScatterF32> s3(e3);
         rc = sa::launch_gemm<sa::F16Traits>(g2, s3, st, "sa_mult_mlp_f16(fc2 scatter)");
         if (rc != SA_OK) return rc;
     }

@@ -157,17 +157,22 @@ __global__ __launch_bounds__(256) void decode_w4_kernel(const uint4 *__restrict_
 
 template <int MODE>
 struct ShiftStore {
-    static constexpr int kPackedBytes = (MODE == kEpiRequantLut) ? 1 : 0;
+    static constexpr int kBytes = (MODE == kEpiRequantLut) ? 1 : 4;
     static constexpr int kTableBytes = (MODE == kEpiRequantLut) ? 256 : 0;
+    static constexpr bool kScatter = (MODE == kEpiScatterI32);
     Epilogue e;
-    int N;
-    void *out;             // narrow output (int8 hidden rows)
+    void *out;             // int32 rows | int8 hidden rows | scattered fp32 rows
     const void *table;     // the 256-entry activation table
-    __device__ inline void direct(long m, int n, int32_t acc, const int32_t *rows) const {
-        epi_store<MODE>(e, m, n, N, acc, rows);
-    }
-    __device__ inline uint32_t convert(int32_t acc, const uint8_t *lds_table) const {
-        return lds_table[(int)requant_code((float)acc * e.rq) + 128];
+    const float *gate;
+    explicit ShiftStore(const Epilogue &epi)
+        : e(epi),
+          out(MODE == kEpiInt32 ? (void *)epi.y : MODE == kEpiRequantLut ? (void *)epi.h : (void *)epi.yf),
+          table(epi.lut),
+          gate(MODE == kEpiScatterI32 ? epi.gate : nullptr) {}
+    __device__ inline uint32_t convert(int32_t acc, int n, const uint8_t *lds_table) const {
+        if (MODE == kEpiInt32) return (uint32_t)(acc + (e.bias ? e.bias[n] : 0));
+        if (MODE == kEpiRequantLut) return lds_table[(int)requant_code((float)acc * e.rq) + 128];
+        return __builtin_bit_cast(uint32_t, e.out_scale * (float)acc);
     }
 };
 
@@ -197,7 +202,7 @@ int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &
         g.gather_a = gather;
         g.K = K;
         g.N = N;
-        ShiftStore<MODE> store{epi, N, epi.h, epi.lut};
+        ShiftStore<MODE> store(epi);
         return launch_gemm<I8Traits>(g, store, st, "shift layer (MFMA)");
     }
     const long gy = (sel.max_rows + kValuRows - 1) / kValuRows;
