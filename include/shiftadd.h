@@ -47,6 +47,8 @@ extern "C" {
 #define SA_VARIANT_VALU 0 /* shift-and-accumulate on the vector ALU                   */
 #define SA_VARIANT_MFMA 1 /* 4-bit weights decoded to int8, int8 matrix cores         */
 #define SA_VARIANT_AUTO 2 /* the faster of the two for the shape                      */
+#define SA_VARIANT_MFMA_PREPARED 3 /* shift layers only: as MFMA, but the weight pointers
+                                      hold planes made by sa_shift_planes_prepare         */
 
 int sa_version(void);
 /* Host string describing the last error returned on this thread ("" if none). */
@@ -108,7 +110,18 @@ int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const
  * falls back to VALU).
  * Both variants are bit-exact.  The MFMA variant decodes the weights to two
  * int8 planes in the workspace (2*N*K bytes) before the matrix-core pass.
+ *
+ * The planes depend on the weights only (s * 2^min(e,6) and s * 64 * [e == 7],
+ * which sum to s * 2^e of Eq. 3), so a caller with fixed weights decodes them
+ * once: sa_shift_planes_prepare writes them to `planes` (device memory of
+ * sa_shift_planes_bytes(K, N) bytes, 16-byte aligned, owned by the caller;
+ * K % 64 == 0).  With variant SA_VARIANT_MFMA_PREPARED the weight arguments of
+ * sa_shift_linear, sa_shift_mlp and sa_block_forward (w4, w1, w2) point at such
+ * planes instead of packed nibbles, and no decode runs.
  */
+size_t sa_shift_planes_bytes(int K, int N);
+int sa_shift_planes_prepare(const uint8_t *w4, int K, int N, void *planes, size_t planes_bytes,
+                            void *stream);
 size_t sa_shift_linear_workspace_bytes(long M, int K, int N, int variant);
 int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t *bias_or_null, int32_t *y,
                     long M, int K, int N, int variant, void *workspace, size_t workspace_bytes,

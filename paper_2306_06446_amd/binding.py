@@ -15,11 +15,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshiftadd.so")
 _lib = None
 
-SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO = 0, 1, 2
+SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO, SA_VARIANT_MFMA_PREPARED = 0, 1, 2, 3
 
 EXPORTS = [
     "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_additive_attention_workspace_bytes",
-    "sa_additive_attention", "sa_hamming_attention", "sa_shift_linear_workspace_bytes", "sa_shift_linear",
+    "sa_additive_attention", "sa_hamming_attention", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
+    "sa_shift_linear_workspace_bytes", "sa_shift_linear",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
@@ -61,7 +62,7 @@ def load_library():
         lib = ctypes.CDLL(LIB_PATH)
         lib.sa_last_error.restype = ctypes.c_char_p
         for name in ("sa_additive_attention_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
-                     "sa_shift_linear_workspace_bytes",
+                     "sa_shift_linear_workspace_bytes", "sa_shift_planes_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
                      "sa_block_workspace_bytes"):
             getattr(lib, name).restype = ctypes.c_size_t
@@ -153,10 +154,27 @@ def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, o
     return (out, scores) if want_scores else out
 
 
+def sa_shift_planes_prepare(w4):
+    """Packed 4-bit weights [N, K/2] -> the two int8 operand planes [2, N, K] of the prepared MFMA variant."""
+    lib = load_library()
+    N, K = w4.shape[0], 2 * w4.shape[1]
+    nbytes = lib.sa_shift_planes_bytes(K, N)
+    if nbytes == 0:
+        raise SAError(-2, "sa_shift_planes_prepare: K must be a multiple of 64")
+    flat = torch.empty(nbytes, dtype=torch.int8, device=w4.device)
+    _check(lib.sa_shift_planes_prepare(_ptr(w4), K, N, _ptr(flat), _z(nbytes), _stream()))
+    return flat[:2 * N * K].view(2, N, K)
+
+
+def _out_width(w, variant):
+    """Rows of a shift weight: packed [N, K/2], or prepared planes [2, N, K]."""
+    return w.shape[1] if variant == SA_VARIANT_MFMA_PREPARED else w.shape[0]
+
+
 def sa_shift_linear(x, w4, bias=None, variant=SA_VARIANT_AUTO, y=None, workspace=None):
     lib = load_library()
     M, K = x.shape
-    N = w4.shape[0]
+    N = _out_width(w4, variant)
     if y is None:
         y = torch.empty((M, N), dtype=torch.int32, device=x.device)
     if workspace is None:
@@ -204,7 +222,7 @@ def sa_shift_mlp(xq, w1, w2, requant_scale, lut, rows=None, counts=None, expert=
                  workspace=None):
     lib = load_library()
     T, E = xq.shape
-    hid = w1.shape[0]
+    hid = _out_width(w1, variant)
     if max_rows is None:
         max_rows = T if rows is None or counts is not None else rows.numel()
     r = _rows(rows, counts, expert, max_rows)

@@ -180,20 +180,32 @@ size_t planes_bytes(int K, int N) { return ((size_t)2 * N * K + 255) / 256 * 256
 
 constexpr int kMfmaK = 64;   // K granularity of the MFMA variant (one LDS stage)
 
-// planes: workspace of planes_bytes(K, N) for the MFMA variant (unused by the VALU variant).
+int decode_planes(const uint8_t *w4, int K, int N, void *planes, hipStream_t st) {
+    int8_t *pa = static_cast<int8_t *>(planes), *pb = pa + (size_t)N * K;
+    const long n_chunks = (long)N * K / 32;
+    decode_w4_kernel<<<dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st>>>(
+        reinterpret_cast<const uint4 *>(w4), n_chunks, reinterpret_cast<uint4 *>(pa), reinterpret_cast<uint4 *>(pb));
+    return check_launch("shift layer (weight decode)");
+}
+
+// planes: workspace of planes_bytes(K, N) for the MFMA variant (unused by the VALU and the
+// prepared variant; for the latter w4 already points at decoded planes).
 template <int MODE>
 int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &sel, bool gather, int K,
                  int N, const Epilogue &epi, void *planes, hipStream_t st) {
     if (sel.max_rows == 0 || N == 0) return SA_OK;
     if (variant == SA_VARIANT_AUTO) variant = (K % kMfmaK == 0) ? SA_VARIANT_MFMA : SA_VARIANT_VALU;
-    if (variant == SA_VARIANT_MFMA) {
+    if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED) {
         SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "shift layer: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
-        int8_t *pa = static_cast<int8_t *>(planes), *pb = pa + (size_t)N * K;
-        const long n_chunks = (long)N * K / 32;
-        decode_w4_kernel<<<dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st>>>(
-            reinterpret_cast<const uint4 *>(w4), n_chunks, reinterpret_cast<uint4 *>(pa), reinterpret_cast<uint4 *>(pb));
-        int rc = check_launch("shift layer (weight decode)");
-        if (rc != SA_OK) return rc;
+        const int8_t *pa, *pb;
+        if (variant == SA_VARIANT_MFMA_PREPARED) {
+            pa = reinterpret_cast<const int8_t *>(w4);      // the caller decoded the weights beforehand
+        } else {
+            int rc = decode_planes(w4, K, N, planes, st);
+            if (rc != SA_OK) return rc;
+            pa = static_cast<const int8_t *>(planes);
+        }
+        pb = pa + (size_t)N * K;
         GemmArgs g;
         g.a = x;
         g.b[0] = pa;
@@ -234,8 +246,26 @@ __global__ __launch_bounds__(256) void requant_lut_kernel(const int32_t *__restr
 
 }  // namespace
 
+extern "C" size_t sa_shift_planes_bytes(int K, int N) {
+    if (K <= 0 || N <= 0 || K % kMfmaK != 0) return 0;
+    return planes_bytes(K, N);
+}
+
+extern "C" int sa_shift_planes_prepare(const uint8_t *w4, int K, int N, void *planes, size_t planes_bytes_given,
+                                       void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(K > 0 && N > 0, SA_ERR_INVALID, "sa_shift_planes_prepare: K and N must be positive");
+    SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_planes_prepare: K (%d) must be a multiple of 64", K);
+    SA_REQUIRE(w4 && planes, SA_ERR_INVALID, "sa_shift_planes_prepare: NULL buffer");
+    SA_REQUIRE(sa::aligned16(w4) && sa::aligned16(planes), SA_ERR_ALIGN,
+               "sa_shift_planes_prepare: pointers must be 16-byte aligned");
+    SA_REQUIRE(planes_bytes_given >= planes_bytes(K, N), SA_ERR_WORKSPACE,
+               "sa_shift_planes_prepare: %zu bytes needed, %zu given", planes_bytes(K, N), planes_bytes_given);
+    return decode_planes(w4, K, N, planes, sa::as_stream(stream));
+}
+
 extern "C" size_t sa_shift_linear_workspace_bytes(long M, int K, int N, int variant) {
-    if (M <= 0 || K <= 0 || N <= 0 || variant == SA_VARIANT_VALU) return 0;
+    if (M <= 0 || K <= 0 || N <= 0 || variant == SA_VARIANT_VALU || variant == SA_VARIANT_MFMA_PREPARED) return 0;
     if (K % kMfmaK != 0) return 0;
     return planes_bytes(K, N);
 }
@@ -245,7 +275,7 @@ extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t
                                size_t workspace_bytes, void *stream) {
     sa::clear_error();
     SA_REQUIRE(M >= 0 && K >= 0 && N >= 0, SA_ERR_INVALID, "sa_shift_linear: negative size");
-    SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_shift_linear: unknown variant %d", variant);
+    SA_REQUIRE(variant >= 0 && variant <= 3, SA_ERR_INVALID, "sa_shift_linear: unknown variant %d", variant);
     SA_REQUIRE(K % 2 == 0, SA_ERR_SHAPE, "sa_shift_linear: K (%d) must be even (two weights per byte)", K);
     SA_REQUIRE(K <= 131072, SA_ERR_SHAPE, "sa_shift_linear: K too large for int32 accumulation");
     SA_REQUIRE(M < (1L << 31), SA_ERR_SHAPE, "sa_shift_linear: M >= 2^31");
@@ -255,8 +285,8 @@ extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t
                    sa::aligned16(workspace),
                SA_ERR_ALIGN, "sa_shift_linear: pointers must be 16-byte aligned");
     SA_REQUIRE(K % 32 == 0, SA_ERR_SHAPE, "sa_shift_linear: K (%d) must be a multiple of 32 (16-byte weight rows)", K);
-    if (variant == SA_VARIANT_MFMA)
-        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
+    if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED)
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear: the MFMA variants need K %% 64 == 0 (K = %d)", K);
     const size_t need = sa_shift_linear_workspace_bytes(M, K, N, variant);
     SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
                "sa_shift_linear: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
@@ -317,7 +347,7 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     int rc = sa::validate_rows(rows, &sel);
     if (rc != SA_OK) return rc;
     SA_REQUIRE(E > 0 && hid > 0, SA_ERR_INVALID, "sa_shift_mlp: E and hid must be positive");
-    SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_shift_mlp: unknown variant %d", variant);
+    SA_REQUIRE(variant >= 0 && variant <= 3, SA_ERR_INVALID, "sa_shift_mlp: unknown variant %d", variant);
     SA_REQUIRE(E % 64 == 0 && hid % 64 == 0, SA_ERR_SHAPE,
                "sa_shift_mlp: E (%d) and hid (%d) must be multiples of 64", E, hid);
     SA_REQUIRE(E <= 131072 && hid <= 131072, SA_ERR_SHAPE, "sa_shift_mlp: width too large");

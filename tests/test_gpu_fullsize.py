@@ -52,7 +52,7 @@ def _mlp_oracle_for_tokens(cfg, o_rows, tokens, logits, p):
 def test_full_size_block_on_sampled_batches(sa, cfg, batches):
     inputs = _block_inputs(cfg)
     q, k, v, pr, scale, p, logits = inputs
-    o, y = run_block(sa, cfg, inputs)
+    o, y = run_block(sa, cfg, inputs, prepared=cfg.E > 0)
     assert np.isfinite(o).all()
     o_ref = _attention_oracle_for_batches(cfg, inputs, batches)
     for b in batches:

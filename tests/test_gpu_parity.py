@@ -184,6 +184,26 @@ def test_shift_linear_extremes_and_bias(sa, variant):
     assert np.array_equal(got, ref)
 
 
+def test_shift_planes_are_the_two_terms_of_the_weight(sa):
+    """Prepared planes: A + B == s * 2^e for every weight, both within int8."""
+    N, K = 70, 128
+    neg, e = wl.shift_weight_raw(3, 6, N, K)
+    planes = host(sa.sa_shift_planes_prepare(dev(wl.pack_w4(neg, e)))).astype(np.int64)
+    w = np.where(neg == 1, -1, 1) * (1 << e.astype(np.int64))
+    assert planes.shape == (2, N, K)
+    assert np.array_equal(planes[0] + planes[1], w)
+    assert np.abs(planes).max() <= 128 and planes.max() <= 127
+
+
+@pytest.mark.parametrize("M,K,N", [(300, 384, 1536), (261, 1536, 384), (129, 192, 768), (1, 64, 1), (64, 3072, 200)])
+def test_shift_linear_on_prepared_planes(sa, M, K, N):
+    w4 = wl.shift_weights(3, 4, N, K)
+    x = wl.int8_activations(3, M, K)
+    planes = sa.sa_shift_planes_prepare(dev(w4))
+    got = host(sa.sa_shift_linear(dev(x), planes, variant=3))
+    assert np.array_equal(got, oracle.shift_linear(x, w4))
+
+
 def test_shift_linear_auto_falls_back_when_k_not_multiple_of_64(sa):
     M, K, N = 40, 96, 33
     w4 = wl.shift_weights(3, 5, N, K)
@@ -267,6 +287,11 @@ def test_shift_mlp_bit_exact_with_row_lists(sa, variant):
     # (c) all rows, no list
     y2c = sa.sa_shift_mlp(d_xq, d_w1, d_w2, p.requant_scale, d_lut, variant=variant)
     assert np.array_equal(host(y2c), oracle.shift_mlp(xq, p.w1, p.w2, p.requant_scale, p.lut))
+    # (d) weights decoded beforehand
+    if variant == 1:
+        y2d = sa.sa_shift_mlp(d_xq, sa.sa_shift_planes_prepare(d_w1), sa.sa_shift_planes_prepare(d_w2),
+                              p.requant_scale, d_lut, rows=dev(rows), variant=3)
+        assert np.array_equal(host(y2d), y2_ref)
 
 
 def test_mult_mlp_matches_oracle(sa):
@@ -316,14 +341,19 @@ def _block_inputs(cfg):
     return q, k, v, pr, scale, p, logits
 
 
-def run_block(sa, cfg, inputs):
+def run_block(sa, cfg, inputs, prepared=False):
+    """prepared: the Shift weights enter as planes decoded beforehand (what bench.py times)."""
     q, k, v, pr, scale, p, logits = inputs
     kw = dict(B=cfg.B, N=cfg.N, H=cfg.H, d=cfg.d, nbits=cfg.nbits, dv=cfg.dv,
               attention=0 if cfg.attention == "linear" else 1, hid=cfg.hid, moe=logits is not None,
               attn_scale=scale, q=dev(q), k=dev(k), v=dev(v), proj=dev(pr))
     if p is not None:
+        w1, w2 = dev(p.w1), dev(p.w2)
+        if prepared:
+            w1, w2 = sa.sa_shift_planes_prepare(w1), sa.sa_shift_planes_prepare(w2)
+            kw.update(shift_variant=3)
         kw.update(act_inv_scale=p.act_inv_scale, requant_scale=p.requant_scale, out_scale=p.out_scale,
-                  w1=dev(p.w1), w2=dev(p.w2), lut=dev(p.lut))
+                  w1=w1, w2=w2, lut=dev(p.lut))
         if logits is not None:
             kw.update(logits=dev(logits), mw1=dev(p.mw1), mw2=dev(p.mw2))
     blk = sa.binding.Block(**kw)
@@ -361,3 +391,6 @@ def test_block_forward_matches_oracle(sa, cfg):
     assert_close(o, o_ref, ATTN_RTOL, ATTN_ATOL, "attention output")
     if y_ref is not None:
         check_block_output(y, y_ref)
+        # the same block on Shift weights decoded beforehand: the same kernels on the same planes
+        o2, y2 = run_block(sa, cfg, inputs, prepared=True)
+        assert np.array_equal(o2, o) and np.array_equal(y2, y)
