@@ -2,20 +2,27 @@
 // replaced by the Hamming similarity S = nbits - 2 * popcount(q xor k) of the
 // codes; V stays fp32, Sec. 4.1).
 //
-// The scores are integer work for the vector ALU (XOR + popcount, then one exp2 per
-// pair); the second MatMul P * V is the dense fp32 contraction of this kernel and
-// runs on the matrix cores (v_mfma_f32_32x32x2_f32).  The two meet in registers:
-// the A operand of that MFMA is one P value per lane - query (lane % 32), key
-// (k0 + lane / 32) - which is exactly the pair whose score the lane has just
-// computed, so P never exists in memory.  A workgroup owns one (batch, head) and up
-// to 256 queries (one 32-query tile per wavefront); key codes and V rows are staged
-// through LDS in chunks of 128 (64 for dv = 128) keys.  Row sums ride along in the lanes and meet in
-// the epilogue.
+// The scores are integer work for the vector ALU (XOR + popcount).  A score takes one of
+// nbits + 1 values, so the softmax numerators p = exp2(-|c2| * t), t = |dist - dist_ref|,
+// come from a table in LDS that is built once per workgroup; each entry holds p in fp32
+// (for the row sum) and p split into two bf16 terms, p ~ ph + pl (each rounded to nearest).
+// The second MatMul P * V is the dense contraction of this kernel and runs on the bf16
+// matrix cores (v_mfma_f32_32x32x16_bf16) as three products with fp32 accumulation,
+//     P * V ~ ph * vh + ph * vl + pl * vh,        v ~ vh + vl likewise,
+// which drops only terms below 2^-17 of each p * v (the output tolerance is 1e-4).  The A
+// operand of one MFMA is 8 numerators per lane - query (lane % 32), keys k0 + 8 * (lane / 32)
+// .. + 7 - exactly the pairs whose distances the lane has just computed, so P never exists
+// in memory.  A workgroup owns one (batch, head) and up to 256 queries (one 32-query tile per
+// wavefront); key codes and V rows are staged through LDS in chunks of 128 keys, V
+// transposed and split into its two bf16 planes, so that a B operand (8 consecutive keys of
+// one column) is one 16-byte read.  Row sums ride along in the lanes and meet in the epilogue.
 //
 // softmax(scale*S)_j = exp2(c2 * (dist_j - dist_ref)) / sum, c2 = -2*scale*log2(e),
 // dist_ref = the distance of the largest score.  When scale >= 0 and the exponent
 // range cannot underflow, dist_ref = 0 (no first pass); otherwise a first pass over
 // the key codes finds it per query.
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -23,8 +30,12 @@ namespace {
 using sa::kWave;
 
 constexpr int kMaxWaves = 8;       // 32-query tiles per workgroup
+constexpr int kKeyChunk = 128;     // keys staged in LDS at a time
+constexpr int kVtStride = kKeyChunk + 8;   // bf16 elements per transposed V row: 272 bytes, so that the
+                                           // 16-byte reads of 16 consecutive columns hit 16 bank groups
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 template <int W>
 __device__ inline int distance(const uint64_t (&q)[W], const uint64_t *k) {
@@ -34,14 +45,33 @@ __device__ inline int distance(const uint64_t (&q)[W], const uint64_t *k) {
     return dist;
 }
 
+// Round-to-nearest-even bf16 of a finite float, as the upper 16 bits.
+__device__ inline uint32_t bf16_bits(float f) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+// f ~ hi + lo, two bf16 terms; returns (hi << 16) | lo.
+__device__ inline uint32_t split_bf16(float f) {
+    const uint32_t hi = bf16_bits(f);
+    const float rest = f - __builtin_bit_cast(float, hi << 16);
+    return (hi << 16) | bf16_bits(rest);
+}
+
+struct TableEntry {
+    uint32_t hl;      // bf16 terms of p: (hi << 16) | lo
+    float p;
+};
+
 template <int DV, int W, bool ROWREF>
 __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
     const uint64_t *__restrict__ q_codes, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
     float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2) {
     constexpr int JT = DV / 32;
-    constexpr int kKeyChunk = DV > 64 ? 64 : 128;     // keys staged in LDS at a time (<= 40 KB)
+    constexpr int NBITS = W * 64;
     __shared__ __attribute__((aligned(16))) uint64_t kc_s[kKeyChunk * W];
-    __shared__ __attribute__((aligned(16))) float v_s[kKeyChunk * DV];
+    __shared__ __attribute__((aligned(16))) uint16_t vth_s[DV * kVtStride];   // V^T, upper bf16 term
+    __shared__ __attribute__((aligned(16))) uint16_t vtl_s[DV * kVtStride];   // V^T, lower bf16 term
+    __shared__ __attribute__((aligned(8))) TableEntry tab_s[NBITS + 1];
     __shared__ float den_s[kMaxWaves * 32];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -50,7 +80,7 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
     const long bh = blockIdx.x / q_chunks;
     const int chunk = blockIdx.x % q_chunks;
     const int b = (int)(bh / H), h = (int)(bh % H);
-    const int i_loc = lane & 31, kk = lane >> 5;
+    const int i_loc = lane & 31, kg = lane >> 5;
     const int qi = chunk * (kMaxWaves * 32) + wave * 32 + i_loc;      // this lane's query
     const int qi_ld = min(qi, Nq - 1);
 
@@ -58,6 +88,14 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
 #pragma unroll
     for (int w = 0; w < W; ++w) q[w] = q_codes[((size_t)bh * Nq + qi_ld) * W + w];
     const uint64_t *kc_g = k_codes + (size_t)bh * Nk * W;
+
+    // numerators by t = |dist - dist_ref|: the exponent is c2 * (dist - dist_ref) = -|c2| * t
+    const float c2n = c2 <= 0.0f ? c2 : -c2;
+    for (int t = tid; t <= NBITS; t += n_threads) {
+        const float pt = __builtin_amdgcn_exp2f(c2n * (float)t);
+        tab_s[t].hl = split_bf16(pt);
+        tab_s[t].p = pt;
+    }
 
     int dref = 0;
     if (ROWREF) {
@@ -84,38 +122,77 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
         for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
     float den = 0.0f;
 
+    // One step: 16 keys from k0 (8 per half-wavefront).  MASK: keys from n on do not count.
+    auto step = [&](int k0, int n, auto mask_c) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        const int kb = k0 + 8 * kg;                       // this lane's first key
+        uint32_t hl[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int t = distance<W>(q, kc_s + (kb + e) * W);
+            if (ROWREF) {
+                t = (c2 <= 0.0f) ? t - dref : dref - t;
+                if (MASK) t = min(max(t, 0), NBITS);       // a padding key may lie beyond the reference
+            }
+            const TableEntry te = tab_s[t];
+            hl[e] = te.hl;
+            den += (!MASK || kb + e < n) ? te.p : 0.0f;
+        }
+        // A operands: element e of the lane is key kb + e
+        uint32_t ah[4], al[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            ah[e2] = __builtin_amdgcn_perm(hl[2 * e2 + 1], hl[2 * e2], 0x07060302u);   // upper halves
+            al[e2] = __builtin_amdgcn_perm(hl[2 * e2 + 1], hl[2 * e2], 0x05040100u);   // lower halves
+        }
+        const v8bf ph = __builtin_bit_cast(v8bf, make_uint4(ah[0], ah[1], ah[2], ah[3]));
+        const v8bf pl = __builtin_bit_cast(v8bf, make_uint4(al[0], al[1], al[2], al[3]));
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) {
+            const int off = (jt * 32 + i_loc) * kVtStride + kb;
+            const v8bf vh = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vth_s + off));
+            const v8bf vl = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vtl_s + off));
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vh, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vl, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, vh, acc[jt], 0, 0, 0);
+        }
+    };
+
     for (int j0 = 0; j0 < Nk; j0 += kKeyChunk) {
         const int n = min(kKeyChunk, Nk - j0);
-        const int n_pad = (n + 1) & ~1;
-        __syncthreads();                           // the previous chunk has been consumed
+        const int n_pad = (n + 15) & ~15;
+        __syncthreads();                           // the previous chunk has been consumed (and the table is there)
         for (int t = tid; t < n_pad * W; t += n_threads) kc_s[t] = (t < n * W) ? kc_g[(size_t)j0 * W + t] : 0ull;
-        for (int t = tid; t < n_pad * (DV / 4); t += n_threads) {
-            const int j = t / (DV / 4), c4 = t % (DV / 4);
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);   // rows past the last key must be finite: 0 * v
-            if (j < n) val = *reinterpret_cast<const float4 *>(v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c4 * 4);
-            *reinterpret_cast<float4 *>(v_s + j * DV + c4 * 4) = val;
+        // V: one task = two consecutive keys of one column -> one dword into each transposed plane
+        // (consecutive threads take consecutive columns: coalesced reads).  Keys past the last one
+        // are zero in both planes, so their numerators add nothing.
+        for (int t = tid; t < (n_pad / 2) * DV; t += n_threads) {
+            const int c = t % DV, j = 2 * (t / DV);
+            const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c;
+            const float v0 = (j < n) ? vp[0] : 0.0f;
+            const float v1 = (j + 1 < n) ? vp[(size_t)H * DV] : 0.0f;
+            const uint32_t s0 = split_bf16(v0), s1 = split_bf16(v1);
+            const int off = c * kVtStride + j;                 // even: 4-byte aligned
+            *reinterpret_cast<uint32_t *>(vth_s + off) = __builtin_amdgcn_perm(s1, s0, 0x07060302u);
+            *reinterpret_cast<uint32_t *>(vtl_s + off) = __builtin_amdgcn_perm(s1, s0, 0x05040100u);
         }
         __syncthreads();
-        for (int k0 = 0; k0 < n_pad; k0 += 2) {
-            const int j = k0 + kk;                 // lanes 0..31 take key k0, lanes 32..63 key k0 + 1
-            const int dist = distance<W>(q, kc_s + j * W);
-            float p = __builtin_amdgcn_exp2f(c2 * (float)(dist - dref));
-            p = (j < n) ? p : 0.0f;
-            den += p;
-#pragma unroll
-            for (int jt = 0; jt < JT; ++jt)
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(p, v_s[j * DV + jt * 32 + i_loc], acc[jt], 0, 0, 0);
+        for (int k0 = 0; k0 < n_pad; k0 += 16) {
+            if (k0 + 16 <= n)
+                step(k0, n, std::false_type{});
+            else
+                step(k0, n, std::true_type{});
         }
     }
 
-    // row sums: the two half-wavefronts hold the even / odd keys of the same 32 queries
+    // row sums: the two half-wavefronts hold different keys of the same 32 queries
     den += __shfl_xor(den, 32);
     if (lane < 32) den_s[wave * 32 + lane] = den;
     __syncthreads();
     const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * kk + (r & 3);      // accumulator row held in register r
+        const int row = 8 * (r >> 2) + 4 * kg + (r & 3);      // accumulator row held in register r
         const int qo = q_tile0 + row;
         if (qo < Nq) {
             const float inv = 1.0f / den_s[wave * 32 + row];

@@ -363,17 +363,19 @@ def run_block(sa, cfg, inputs, prepared=False):
 
 
 def check_block_output(y, y_ref):
-    """End-to-end MLP output.  The fp32 attention output feeds an int8 quantiser (step 1/inv_scale):
-    a value within float error (~1e-5 at N = 16384) of a rounding boundary flips one int8 code by one
-    step.  One flipped code shifts every fc1 accumulator of that token by 2^e, flips a few dozen
-    hidden codes and moves that token's outputs by ~1e-2 of the output rms.  With E = 256..768
-    elements per token up to ~15 % of the tokens carry such a flip, so the test asks: at least 97 %
-    of the outputs agree to float accuracy, and none is further than 5e-2 rms away.  Stage-level
-    tests on shared inputs carry the bit-exact claims."""
+    """End-to-end MLP output.  The fp32 attention output feeds an int8 quantiser whose step is
+    1/inv_scale, about 1/32 of the rms of its input.  The attention output carries a relative
+    error of a few 1e-6 (bf16 three-product P*V of the Hamming kernel; ~1e-5 absolute at N = 16384
+    for the linear kernel), so an element lands on the other side of a rounding boundary with
+    probability ~1e-4, and a token of E = 256..768 elements carries at least one flipped code with
+    probability up to ~10 %.  One flipped code shifts every fc1 accumulator of that token by 2^e,
+    flips a few dozen hidden codes and moves that token's outputs by ~1e-2 of the output rms.  So
+    the test asks: at least 90 % of the outputs agree to float accuracy, and none is further than
+    5e-2 rms away.  Stage-level tests on shared inputs carry the bit-exact claims."""
     rms = float(np.sqrt(np.mean(np.square(y_ref))))
     err = np.abs(y.astype(np.float64) - y_ref)
     tight = err <= 2e-3 * np.abs(y_ref) + 1e-3 * rms
-    assert tight.mean() > 0.97, "only %.4f of the block outputs agree tightly" % tight.mean()
+    assert tight.mean() > 0.90, "only %.4f of the block outputs agree tightly" % tight.mean()
     assert err.max() <= 5e-2 * rms, "worst block output error %.3g (rms %.3g)" % (err.max(), rms)
 
 
