@@ -31,6 +31,7 @@ using sa::kWave;
 
 constexpr int kMaxWaves = 8;       // 32-query tiles per workgroup
 constexpr int kKeyChunk = 128;     // keys staged in LDS at a time
+constexpr int kStageBatch = 4;     // V staging tasks whose loads a thread keeps in flight together
 constexpr int kVtStride = kKeyChunk + 8;   // bf16 elements per transposed V row: 272 bytes, so that the
                                            // 16-byte reads of 16 consecutive columns hit 16 bank groups
 
@@ -163,26 +164,41 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
         const int n_pad = (n + 15) & ~15;
         __syncthreads();                           // the previous chunk has been consumed (and the table is there)
         for (int t = tid; t < n_pad * W; t += n_threads) kc_s[t] = (t < n * W) ? kc_g[(size_t)j0 * W + t] : 0ull;
-        // V: one task = two consecutive keys of one column -> one dword into each transposed plane
-        // (consecutive threads take consecutive columns: coalesced reads).  Keys past the last one
-        // are zero in both planes, so their numerators add nothing.
-        for (int t = tid; t < (n_pad / 2) * DV; t += n_threads) {
-            const int c = t % DV, j = 2 * (t / DV);
-            const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c;
-            const float v0 = (j < n) ? vp[0] : 0.0f;
-            const float v1 = (j + 1 < n) ? vp[(size_t)H * DV] : 0.0f;
-            const uint32_t s0 = split_bf16(v0), s1 = split_bf16(v1);
-            const int off = c * kVtStride + j;                 // even: 4-byte aligned
-            *reinterpret_cast<uint32_t *>(vth_s + off) = __builtin_amdgcn_perm(s1, s0, 0x07060302u);
-            *reinterpret_cast<uint32_t *>(vtl_s + off) = __builtin_amdgcn_perm(s1, s0, 0x05040100u);
+        // V: one task = two consecutive keys x four columns -> four dwords into each transposed plane
+        // (consecutive threads take consecutive float4s of a row: coalesced reads).  The loads of
+        // kStageBatch tasks are issued together, so a chunk costs a few memory round trips, not one
+        // per task.  Keys past the last one are zero in both planes: their numerators add nothing.
+        const int n_tasks = (n_pad / 2) * (DV / 4);
+        for (int base = 0; base < n_tasks; base += n_threads * kStageBatch) {
+            float4 v0[kStageBatch], v1[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int t = base + u * n_threads + tid;
+                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
+                v0[u] = v1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c4 * 4;
+                if (t < n_tasks && j < n) v0[u] = *reinterpret_cast<const float4 *>(vp);
+                if (t < n_tasks && j + 1 < n) v1[u] = *reinterpret_cast<const float4 *>(vp + (size_t)H * DV);
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int t = base + u * n_threads + tid;
+                if (t >= n_tasks) continue;
+                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
+                const float a0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, a1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t s0 = split_bf16(a0[c]), s1 = split_bf16(a1[c]);
+                    const int off = (c4 * 4 + c) * kVtStride + j;      // even: 4-byte aligned
+                    *reinterpret_cast<uint32_t *>(vth_s + off) = __builtin_amdgcn_perm(s1, s0, 0x07060302u);
+                    *reinterpret_cast<uint32_t *>(vtl_s + off) = __builtin_amdgcn_perm(s1, s0, 0x05040100u);
+                }
+            }
         }
         __syncthreads();
-        for (int k0 = 0; k0 < n_pad; k0 += 16) {
-            if (k0 + 16 <= n)
-                step(k0, n, std::false_type{});
-            else
-                step(k0, n, std::true_type{});
-        }
+        const int n_full = n & ~15;                // whole steps first, then at most one masked step
+        for (int k0 = 0; k0 < n_full; k0 += 16) step(k0, n, std::false_type{});
+        if (n_full < n) step(n_full, n, std::true_type{});
     }
 
     // row sums: the two half-wavefronts hold different keys of the same 32 queries
