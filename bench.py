@@ -26,6 +26,7 @@ PEAK_TFLOPS = {                  # dense peaks of MI355X
     "alu_int": 39.3,             # 32-bit integer vector ops: 256 CU x 64 lanes x 2.4 GHz
     "mfma_i8": 5000.0,
     "mfma_f16": 2500.0,
+    "mfma_f32": 157.3,           # an fp32 contraction is priced at the fp32 matrix peak, however it is run
 }
 
 
@@ -43,6 +44,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy first: a kernel of known traffic for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     return ap.parse_args()
 
 
@@ -65,7 +69,8 @@ def kernel_table(cfg, p, counts):
         tab.append(dict(name="qkv", bytes=code_b + kv_b + v_b, ops=adds, compute="alu_fp32"))
     else:
         pairs = B * H * N * N
-        tab.append(dict(name="hamming", bytes=2 * code_b + 2 * v_b, ops=2 * pairs * cfg.dv, compute="alu_fp32"))
+        # P * V is the dense fp32 contraction of this kernel (it runs as three bf16 matrix-core products)
+        tab.append(dict(name="hamming", bytes=2 * code_b + 2 * v_b, ops=2 * pairs * cfg.dv, compute="mfma_f32"))
     if cfg.E:
         tab.append(dict(name="quantize", bytes=T * E * 5, ops=2 * T * E, compute="alu_fp32"))
         t_shift, t_mult = (counts[1], counts[0]) if counts is not None else (T, 0)
@@ -140,6 +145,14 @@ def main():
             if moe:
                 kw.update(logits=dev(logits), mw1=shared["mw1"], mw2=shared["mw2"])
         blocks.append((sa.Block(**kw), kw))
+
+    if args.calibrate_copy:
+        src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                     # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: W warm-up steps, then exactly K steps
     for i in range(args.warmup):

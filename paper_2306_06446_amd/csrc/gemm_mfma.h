@@ -69,6 +69,7 @@ struct GemmArgs {
     RowSel sel;             // which rows of A / of the scattered output
     bool gather_a;          // A rows are sel.rows[m] (else compact m)
     int K, N;
+    int col_groups = 1;     // 1, 2, 4 or 8: set by the launcher
 };
 
 // Physical 16-byte chunk of logical chunk c in LDS row r, for rows of CPR chunks.
@@ -130,13 +131,19 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
     long n_rows;
     resolve_rows(g.sel, rows, n_rows);
     // Workgroups are handed to the 8 XCDs round-robin by their linear id, and each XCD has its own
-    // L2.  All column tiles of one row tile are therefore given ids with the same id % 8: the row
-    // tile of A is fetched into one L2 only, and the (small) B planes stay resident in every L2.
+    // 4 MiB L2.  The 8 XCDs form a (8 / col_groups) x col_groups grid over the output: an XCD owns
+    // every (8 / col_groups)-th row tile and every col_groups-th column tile, and walks them row
+    // tile by row tile.  Its share of the B planes (chosen by the host to fit the L2) stays
+    // resident, and each row tile of A is fetched by col_groups L2s only.
     const int col_tiles = (g.N + BN - 1) / BN;
+    const int cg = g.col_groups, rg = 8 / cg;
+    const int cols_per_group = (col_tiles + cg - 1) / cg;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const long m0 = ((long)(slot / col_tiles) * 8 + xcd) * BM;
-    if (m0 >= n_rows) return;
-    const int n0 = (slot % col_tiles) * BN;
+    const long row_tile = (long)(slot / cols_per_group) * rg + xcd / cg;
+    const int col_tile = (slot % cols_per_group) * cg + xcd % cg;
+    const long m0 = row_tile * BM;
+    if (m0 >= n_rows || col_tile >= col_tiles) return;
+    const int n0 = col_tile * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
@@ -368,10 +375,17 @@ template <class T, int BM, int BN, int SB, int NS, int LS, int OCC, class Store>
 int launch_gemm_tile(const GemmArgs &g, const Store &store, hipStream_t st, const char *what) {
     const long row_tiles = (g.sel.max_rows + BM - 1) / BM;
     const long col_tiles = (g.N + BN - 1) / BN;
-    const long blocks = (row_tiles + 7) / 8 * 8 * col_tiles;
+    // the fewest column groups whose share of the B planes leaves room in a 4 MiB L2
+    const size_t b_bytes = (size_t)T::kPlanes * g.N * g.K * T::kElemBytes;
+    int cg = 1;
+    while (cg < 8 && b_bytes / cg > (size_t)(5 << 19)) cg *= 2;     // 2.5 MiB
+    const int rg = 8 / cg;
+    const long blocks = 8 * ((row_tiles + rg - 1) / rg) * ((col_tiles + cg - 1) / cg);
     SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "%s: too many tiles for one launch", what);
     const dim3 grid((unsigned)blocks);
-    gemm_nt_kernel<T, BM, BN, SB, NS, LS, OCC, Store><<<grid, dim3(256), 0, st>>>(g, store);
+    GemmArgs ga = g;
+    ga.col_groups = cg;
+    gemm_nt_kernel<T, BM, BN, SB, NS, LS, OCC, Store><<<grid, dim3(256), 0, st>>>(ga, store);
     return check_launch(what);
 }
 
