@@ -69,14 +69,19 @@ def kernel_table(cfg, p, counts):
         tab.append(dict(name="qkv", bytes=code_b + kv_b + v_b, ops=adds, compute="alu_fp32"))
     else:
         pairs = B * H * N * N
-        # P * V is the dense fp32 contraction of this kernel (it runs as three bf16 matrix-core products)
-        tab.append(dict(name="hamming", bytes=2 * code_b + 2 * v_b, ops=2 * pairs * cfg.dv, compute="mfma_f32"))
+        # P * V is the dense fp32 contraction of this kernel (it runs as three bf16 matrix-core products);
+        # with an MLP behind it the kernel also writes its output as int8 codes (and fp16 for a Mult expert)
+        extra = T * E * (1 + (2 if counts is not None else 0)) if cfg.E else 0
+        tab.append(dict(name="hamming", bytes=2 * code_b + 2 * v_b + extra, ops=2 * pairs * cfg.dv,
+                        compute="mfma_f32"))
     if cfg.E:
-        tab.append(dict(name="quantize", bytes=T * E * 5, ops=2 * T * E, compute="alu_fp32"))
+        if cfg.attention == "linear":
+            tab.append(dict(name="quantize", bytes=T * E * (5 + (2 if counts is not None else 0)), ops=2 * T * E,
+                            compute="alu_fp32"))
         t_shift, t_mult = (counts[1], counts[0]) if counts is not None else (T, 0)
         if counts is not None:
             tab.append(dict(name="dispatch", bytes=T * (8 + 12), ops=4 * T, compute="alu_fp32"))
-            tab.append(dict(name="mult_fc1", bytes=t_mult * E * 4 + E * cfg.hid * 2 + t_mult * cfg.hid * 2,
+            tab.append(dict(name="mult_fc1", bytes=t_mult * E * 2 + E * cfg.hid * 2 + t_mult * cfg.hid * 2,
                             ops=2 * t_mult * E * cfg.hid, compute="mfma_f16"))
             tab.append(dict(name="mult_fc2", bytes=t_mult * cfg.hid * 2 + E * cfg.hid * 2 + t_mult * E * 4,
                             ops=2 * t_mult * E * cfg.hid, compute="mfma_f16"))
@@ -254,14 +259,24 @@ def make_stages(sa, torch, cfg, kw, p, moe, variant):
                                                      kv=kv, workspace=ws)
         st["qkv"] = lambda: sa.sa_additive_attention(qc, None, None, kw["attn_scale"], cfg.nbits, phases=2,
                                                      kv=kv, out=o, workspace=ws)
-    else:
-        st["hamming"] = lambda: sa.sa_hamming_attention(qc, kc, kw["v"], kw["attn_scale"], cfg.nbits, out=o)
+    x = o.view(T, E) if E else None
+    xq = torch.empty((T, E), dtype=torch.int8, device=d) if E else None
+    xh = torch.empty((T, E), dtype=torch.float16, device=d) if (E and moe) else None
+    if cfg.attention != "linear":
+        if E:       # as in the block: the kernel also leaves the forms the MLP reads
+            st["hamming"] = lambda: sa.sa_hamming_attention_fused(qc, kc, kw["v"], kw["attn_scale"], cfg.nbits,
+                                                                  p.act_inv_scale, out=o, xq=xq, xh=xh,
+                                                                  want_xh=False)
+        else:
+            st["hamming"] = lambda: sa.sa_hamming_attention(qc, kc, kw["v"], kw["attn_scale"], cfg.nbits, out=o)
     if not E:
         return st
-    x = o.view(T, E)
-    xq = torch.empty((T, E), dtype=torch.int8, device=d)
     y = torch.empty((T, E), dtype=torch.float32, device=d)
-    st["quantize"] = lambda: sa.sa_quantize_act(x, p.act_inv_scale, q=xq)
+    if cfg.attention == "linear":
+        if moe:
+            st["quantize"] = lambda: sa.sa_quantize_act_half(x, p.act_inv_scale, q=xq, xh=xh)
+        else:
+            st["quantize"] = lambda: sa.sa_quantize_act(x, p.act_inv_scale, q=xq)
     sws = torch.empty(max(16, lib.sa_shift_mlp_workspace_bytes(sa._l(T), E, cfg.hid)), dtype=torch.uint8, device=d)
     rows = dict()
     if moe:
@@ -271,10 +286,10 @@ def make_stages(sa, torch, cfg, kw, p, moe, variant):
         st["dispatch"] = lambda: sa.sa_moe_dispatch(kw["logits"], out=outs, workspace=dws)
         mws = torch.empty(max(16, lib.sa_mult_mlp_workspace_bytes(sa._l(T), E, cfg.hid)), dtype=torch.uint8, device=d)
         mrows = dict(rows=outs[0], counts=outs[2], expert=0, max_rows=T, gate=outs[3])
-        st["mult_fc1"] = lambda: sa.sa_mult_mlp_f16(x, kw["mw1"], kw["mw2"], want_out=False, y=y, stages=1,
-                                                    workspace=mws, **mrows)
-        st["mult_fc2"] = lambda: sa.sa_mult_mlp_f16(x, kw["mw1"], kw["mw2"], want_out=False, y=y, stages=2,
-                                                    workspace=mws, **mrows)
+        st["mult_fc1"] = lambda: sa.sa_mult_mlp_f16_half(xh, kw["mw1"], kw["mw2"], want_out=False, y=y, stages=1,
+                                                         workspace=mws, **mrows)
+        st["mult_fc2"] = lambda: sa.sa_mult_mlp_f16_half(xh, kw["mw1"], kw["mw2"], want_out=False, y=y, stages=2,
+                                                         workspace=mws, **mrows)
         rows = dict(rows=outs[0], counts=outs[2], expert=1, max_rows=T, gate=outs[3])
     for name, stage in (("shift_fc1", 1), ("shift_fc2", 2)):
         st[name] = (lambda stage=stage: sa.sa_shift_mlp(xq, kw["w1"], kw["w2"], p.requant_scale, kw["lut"],

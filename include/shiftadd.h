@@ -101,6 +101,14 @@ int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_codes, cons
 int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
                          float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
                          float scale, int16_t *scores_or_null, void *stream);
+/* The same, with the attention output also written in the two forms the MLP of the block
+ * reads (Eq. 2 feeds the attention output to the MLP): xq_or_null int8 [B*Nq, H*dv], the
+ * codes sa_quantize_act(out, act_inv_scale) would give, and xh_or_null fp16 [B*Nq, H*dv],
+ * out rounded to nearest.  Either may be NULL. */
+int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
+                               float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
+                               float scale, int16_t *scores_or_null, int8_t *xq_or_null,
+                               void *xh_or_null, float act_inv_scale, void *stream);
 
 /*
  * Shift layer (Eq. 3, O_Shift = sum X * s * 2^P) on int8 activations with
@@ -148,6 +156,10 @@ int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *
  * NaN -> 0.  One fp32 multiply and one round-to-nearest-even; bit-exact.
  */
 int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *stream);
+/* The same pass also leaves x rounded to fp16 in xh_or_null ([n], 16-byte aligned) when it
+ * is not NULL: the input form of the Mult expert (Sec. 4.2), so x is read once for both. */
+int sa_quantize_act_half(const float *x, long n, float inv_scale, int8_t *q, void *xh_or_null,
+                         void *stream);
 
 /*
  * Between the two shift linears of the Shift expert:
@@ -203,6 +215,13 @@ int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const v
                     const void *w2_f16, float *out_or_null, float *y_or_null,
                     const float *gate_or_null, int stages, void *workspace,
                     size_t workspace_bytes, void *stream);
+/* The same expert on rows that already exist in fp16: xh_all is [T, E] fp16 (all tokens, as
+ * sa_quantize_act_half or sa_hamming_attention_fused leave them) and the first layer picks
+ * the rows of `rows` itself, so no gathered copy is made. */
+int sa_mult_mlp_f16_half(const void *xh_all, const sa_rows *rows, int E, int hid,
+                         const void *w1_f16, const void *w2_f16, float *out_or_null,
+                         float *y_or_null, const float *gate_or_null, int stages,
+                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* Plain row movement (Sec. 4.2, y = sum_i G(x) * E_i(x) with one non-zero term):
  *   gather : dst[i, :] = src[rows[i], :]                 (row_bytes % 16 == 0)

@@ -19,11 +19,11 @@ SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO, SA_VARIANT_MFMA_PREPARED = 0,
 
 EXPORTS = [
     "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_additive_attention_workspace_bytes",
-    "sa_additive_attention", "sa_hamming_attention", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
+    "sa_additive_attention", "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear",
-    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_requant_lut",
+    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
-    "sa_mult_mlp_f16", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
+    "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
     "sa_block_forward",
 ]
 
@@ -154,6 +154,25 @@ def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, o
     return (out, scores) if want_scores else out
 
 
+def sa_hamming_attention_fused(q_codes, k_codes, v, scale, nbits, act_inv_scale, out=None, xq=None, xh=None,
+                               want_xq=True, want_xh=True):
+    """Hamming attention that also leaves its output as int8 codes (xq) and in fp16 (xh), both [B*Nq, H*dv]."""
+    B, H, Nq, W = q_codes.shape
+    Nk = k_codes.shape[2]
+    dv = v.shape[3]
+    dev = v.device
+    if out is None:
+        out = torch.empty((B, Nq, H, dv), dtype=torch.float32, device=dev)
+    if xq is None and want_xq:
+        xq = torch.empty((B * Nq, H * dv), dtype=torch.int8, device=dev)
+    if xh is None and want_xh:
+        xh = torch.empty((B * Nq, H * dv), dtype=torch.float16, device=dev)
+    _check(load_library().sa_hamming_attention_fused(_ptr(q_codes), _ptr(k_codes), _ptr(v), _ptr(out), B, H, Nq, Nk,
+                                                     nbits, dv, _f(scale), _ptr(None), _ptr(xq), _ptr(xh),
+                                                     _f(act_inv_scale), _stream()))
+    return out, xq, xh
+
+
 def sa_shift_planes_prepare(w4):
     """Packed 4-bit weights [N, K/2] -> the two int8 operand planes [2, N, K] of the prepared MFMA variant."""
     lib = load_library()
@@ -210,6 +229,15 @@ def sa_quantize_act(x, inv_scale, q=None):
     return q
 
 
+def sa_quantize_act_half(x, inv_scale, q=None, xh=None):
+    if q is None:
+        q = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    if xh is None:
+        xh = torch.empty(x.shape, dtype=torch.float16, device=x.device)
+    _check(load_library().sa_quantize_act_half(_ptr(x), _l(x.numel()), _f(inv_scale), _ptr(q), _ptr(xh), _stream()))
+    return q, xh
+
+
 def sa_requant_lut(y, s, lut, h=None):
     if h is None:
         h = torch.empty(y.shape, dtype=torch.int8, device=y.device)
@@ -250,6 +278,24 @@ def sa_mult_mlp_f16(x, w1, w2, rows=None, counts=None, expert=0, max_rows=None, 
         ws = _workspace(lib.sa_mult_mlp_workspace_bytes(_l(max_rows), E, hid), x.device)
     _check(lib.sa_mult_mlp_f16(_ptr(x), ctypes.byref(r), E, hid, _ptr(w1), _ptr(w2), _ptr(out), _ptr(y),
                                _ptr(gate), stages, _ptr(ws), _z(ws.numel()), _stream()))
+    return out
+
+
+def sa_mult_mlp_f16_half(xh_all, w1, w2, rows=None, counts=None, expert=0, max_rows=None, want_out=True,
+                         y=None, gate=None, stages=3, workspace=None):
+    """The Mult expert on fp16 rows of all tokens [T, E]; `rows` are picked inside the first layer."""
+    lib = load_library()
+    T, E = xh_all.shape
+    hid = w1.shape[0]
+    if max_rows is None:
+        max_rows = T if rows is None or counts is not None else rows.numel()
+    r = _rows(rows, counts, expert, max_rows)
+    out = torch.empty((max_rows, E), dtype=torch.float32, device=xh_all.device) if want_out else None
+    ws = workspace
+    if ws is None:
+        ws = _workspace(lib.sa_mult_mlp_workspace_bytes(_l(max_rows), E, hid), xh_all.device)
+    _check(lib.sa_mult_mlp_f16_half(_ptr(xh_all), ctypes.byref(r), E, hid, _ptr(w1), _ptr(w2), _ptr(out), _ptr(y),
+                                    _ptr(gate), stages, _ptr(ws), _z(ws.numel()), _stream()))
     return out
 
 

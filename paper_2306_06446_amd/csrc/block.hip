@@ -9,7 +9,7 @@
 namespace {
 
 struct Layout {
-    size_t qc, kc, kv, attn_ws, xq, perm, expert_of, counts, gate, disp_ws, shift_ws, mult_ws, total;
+    size_t qc, kc, kv, attn_ws, xq, xh, perm, expert_of, counts, gate, disp_ws, shift_ws, mult_ws, total;
     size_t attn_ws_bytes, disp_ws_bytes, shift_ws_bytes, mult_ws_bytes;
 };
 
@@ -35,7 +35,7 @@ int plan(const sa_block_desc *d, Layout *L) {
         L->attn_ws_bytes = sa_additive_attention_workspace_bytes(d->B, d->H, d->N, d->nbits, d->dv);
     }
     L->attn_ws = off; off += up(L->attn_ws_bytes);
-    L->xq = off;
+    L->xq = L->xh = off;
     L->disp_ws_bytes = L->shift_ws_bytes = L->mult_ws_bytes = 0;
     L->perm = L->expert_of = L->counts = L->gate = L->disp_ws = L->shift_ws = L->mult_ws = off;
     if (d->hid > 0) {
@@ -43,6 +43,7 @@ int plan(const sa_block_desc *d, Layout *L) {
         L->shift_ws_bytes = sa_shift_mlp_workspace_bytes((long)T, (int)E, d->hid);
         L->shift_ws = off; off += up(L->shift_ws_bytes);
         if (d->moe) {
+            L->xh = off; off += up(T * E * 2);          // fp16 copy of the attention output for the Mult expert
             L->perm = off; off += up(T * 4);
             L->expert_of = off; off += up(T * 4);
             L->counts = off; off += 256;
@@ -152,29 +153,33 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     if (rc != SA_OK) return rc;
     rc = sa_binarize(d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, kc, stream);
     if (rc != SA_OK) return rc;
+    // The attention output leaves in three forms: fp32 (the block's output o), the int8 codes the
+    // Shift layers read, and (with a Mult expert) the fp16 rounding its first layer reads.  The
+    // Hamming kernel writes all three from its accumulators; the linear path adds one pass over o.
+    int8_t *xq = reinterpret_cast<int8_t *>(ws + L.xq);
+    void *xh = moe ? static_cast<void *>(ws + L.xh) : nullptr;
+    const bool mlp = d->hid > 0;
     if (d->attention == 0) {
         rc = sa_additive_attention(qc, kc, d->v, d->o, d->B, d->H, d->N, d->N, d->nbits, d->dv, d->attn_scale,
                                    reinterpret_cast<float *>(ws + L.kv), 3, ws + L.attn_ws, L.attn_ws_bytes, stream);
+        if (rc == SA_OK && mlp) rc = sa_quantize_act_half(d->o, T * E, d->act_inv_scale, xq, xh, stream);
     } else {
-        rc = sa_hamming_attention(qc, kc, d->v, d->o, d->B, d->H, d->N, d->N, d->nbits, d->dv, d->attn_scale,
-                                  nullptr, stream);
+        rc = sa_hamming_attention_fused(qc, kc, d->v, d->o, d->B, d->H, d->N, d->N, d->nbits, d->dv, d->attn_scale,
+                                         nullptr, mlp ? xq : nullptr, xh, d->act_inv_scale, stream);
     }
-    if (rc != SA_OK || d->hid == 0) return rc;
+    if (rc != SA_OK || !mlp) return rc;
 
     if (moe) {
         // Mult expert on the side lane as soon as the attention output exists
         SA_HIP(hipEventRecord(lane->attended, main_st));
         SA_HIP(hipStreamWaitEvent(lane->stream, lane->attended, 0));
         const sa_rows mult_rows{perm, counts, 0, T};
-        rc = sa_mult_mlp_f16(d->o, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3, ws + L.mult_ws,
-                             L.mult_ws_bytes, lane->stream);
+        rc = sa_mult_mlp_f16_half(xh, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3, ws + L.mult_ws,
+                                  L.mult_ws_bytes, lane->stream);
         if (rc != SA_OK) return rc;
         SA_HIP(hipEventRecord(lane->joined, lane->stream));
     }
 
-    int8_t *xq = reinterpret_cast<int8_t *>(ws + L.xq);
-    rc = sa_quantize_act(d->o, T * E, d->act_inv_scale, xq, stream);
-    if (rc != SA_OK) return rc;
     if (!moe) {
         const sa_rows all{nullptr, nullptr, 0, T};
         return sa_shift_mlp(xq, &all, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, nullptr,

@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "gemm_common.h"
 
 namespace {
 
@@ -58,6 +59,31 @@ __device__ inline uint32_t split_bf16(float f) {
     return (hi << 16) | bf16_bits(rest);
 }
 
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+
+// x[j] of lane q (q = lane % 4) <-> x[q] of lane j, inside each group of four lanes: two butterfly
+// stages, lane bit b against register-index bit b.
+__device__ inline void transpose_in_quad(float (&x)[4], int q4) {
+    constexpr int kXor1 = 0xB1, kXor2 = 0x4E;           // DPP quad_perm [1,0,3,2] and [2,3,0,1]
+    const bool odd = q4 & 1, upper = q4 & 2;
+#pragma unroll
+    for (int p = 0; p < 4; p += 2) {                     // pairs (0,1) and (2,3)
+        const float send = odd ? x[p] : x[p + 1];
+        const float recv = __builtin_bit_cast(
+            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), kXor1, 0xF, 0xF, false));
+        x[p] = odd ? recv : x[p];
+        x[p + 1] = odd ? x[p + 1] : recv;
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {                        // pairs (0,2) and (1,3)
+        const float send = upper ? x[p] : x[p + 2];
+        const float recv = __builtin_bit_cast(
+            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), kXor2, 0xF, 0xF, false));
+        x[p] = upper ? recv : x[p];
+        x[p + 2] = upper ? x[p + 2] : recv;
+    }
+}
+
 struct TableEntry {
     uint32_t hl;      // bf16 terms of p: (hi << 16) | lo
     float p;
@@ -66,7 +92,8 @@ struct TableEntry {
 template <int DV, int W, bool ROWREF>
 __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
     const uint64_t *__restrict__ q_codes, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
-    float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2) {
+    float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2, int8_t *__restrict__ xq,
+    _Float16 *__restrict__ xh, float act_inv_scale) {
     constexpr int JT = DV / 32;
     constexpr int NBITS = W * 64;
     __shared__ __attribute__((aligned(16))) uint64_t kc_s[kKeyChunk * W];
@@ -205,16 +232,38 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
     den += __shfl_xor(den, 32);
     if (lane < 32) den_s[wave * 32 + lane] = den;
     __syncthreads();
+    // A lane holds one column of four consecutive rows per register quartet; after a 4 x 4
+    // transpose inside each quad of lanes it holds four consecutive columns of one row, and every
+    // output form leaves in whole 16- / 8- / 4-byte pieces of a row.
     const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
+    const int q4 = lane & 3;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * kg + (r & 3);      // accumulator row held in register r
+    for (int g = 0; g < 4; ++g) {
+        const int row = 8 * g + 4 * kg + q4;                  // the row this lane holds after the transpose
         const int qo = q_tile0 + row;
-        if (qo < Nq) {
-            const float inv = 1.0f / den_s[wave * 32 + row];
-            float *o = out + (((size_t)b * Nq + qo) * H + h) * DV + i_loc;
+        const float inv = 1.0f / den_s[wave * 32 + row];
+        const size_t at = (((size_t)b * Nq + min(qo, Nq - 1)) * H + h) * DV + (i_loc & ~3);
 #pragma unroll
-            for (int jt = 0; jt < JT; ++jt) o[jt * 32] = acc[jt][r] * inv;
+        for (int jt = 0; jt < JT; ++jt) {
+            float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
+            transpose_in_quad(x, q4);
+            if (qo < Nq) {
+                const float4 val = make_float4(x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv);
+                *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
+                // what the MLP reads: the int8 codes of the activation quantiser, and the fp16 rounding
+                if (xq) {
+                    const uint32_t c0 = (uint8_t)sa::requant_code(val.x * act_inv_scale);
+                    const uint32_t c1 = (uint8_t)sa::requant_code(val.y * act_inv_scale);
+                    const uint32_t c2b = (uint8_t)sa::requant_code(val.z * act_inv_scale);
+                    const uint32_t c3 = (uint8_t)sa::requant_code(val.w * act_inv_scale);
+                    *reinterpret_cast<uint32_t *>(xq + at + jt * 32) = c0 | (c1 << 8) | (c2b << 16) | (c3 << 24);
+                }
+                if (xh) {
+                    v4h hv;
+                    hv[0] = (_Float16)val.x; hv[1] = (_Float16)val.y; hv[2] = (_Float16)val.z; hv[3] = (_Float16)val.w;
+                    *reinterpret_cast<v4h *>(xh + at + jt * 32) = hv;
+                }
+            }
         }
     }
 }
@@ -246,14 +295,19 @@ struct Launch {
     int H, Nq, Nk, q_chunks;
     float c2;
     bool rowref;
+    int8_t *xq;
+    _Float16 *xh;
+    float act_inv_scale;
 };
 
 template <int DV, int W>
 void launch_hamming(const Launch &L) {
     if (L.rowref)
-        hamming_mfma_kernel<DV, W, true><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2);
+        hamming_mfma_kernel<DV, W, true><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2,
+                                                                       L.xq, L.xh, L.act_inv_scale);
     else
-        hamming_mfma_kernel<DV, W, false><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2);
+        hamming_mfma_kernel<DV, W, false><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2,
+                                                                       L.xq, L.xh, L.act_inv_scale);
 }
 
 template <int DV>
@@ -275,6 +329,15 @@ extern "C" int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_c
                                     float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
                                     float scale, int16_t *scores_or_null, void *stream) {
     sa::clear_error();
+    return sa_hamming_attention_fused(q_codes, k_codes, v, out, B, H, Nq, Nk, nbits, dv, scale, scores_or_null,
+                                      nullptr, nullptr, 0.0f, stream);
+}
+
+extern "C" int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
+                                          float *out, int B, int H, int Nq, int Nk, int nbits, int dv, float scale,
+                                          int16_t *scores_or_null, int8_t *xq_or_null, void *xh_or_null,
+                                          float act_inv_scale, void *stream) {
+    sa::clear_error();
     SA_REQUIRE(B >= 0 && H >= 0 && Nq >= 0 && Nk >= 0 && nbits > 0 && dv > 0, SA_ERR_INVALID,
                "sa_hamming_attention: negative size");
     SA_REQUIRE(nbits % 64 == 0, SA_ERR_SHAPE, "sa_hamming_attention: nbits %d is not a multiple of 64", nbits);
@@ -286,8 +349,8 @@ extern "C" int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_c
     if ((long)B * H == 0 || Nq == 0) return SA_OK;
     SA_REQUIRE(Nk > 0, SA_ERR_SHAPE, "sa_hamming_attention: softmax over zero keys is undefined");
     SA_REQUIRE(q_codes && k_codes && v && out, SA_ERR_INVALID, "sa_hamming_attention: NULL buffer");
-    SA_REQUIRE(sa::aligned16(q_codes) && sa::aligned16(k_codes) && sa::aligned16(v) &&
-                   sa::aligned16(out) && sa::aligned16(scores_or_null),
+    SA_REQUIRE(sa::aligned16(q_codes) && sa::aligned16(k_codes) && sa::aligned16(v) && sa::aligned16(out) &&
+                   sa::aligned16(scores_or_null) && sa::aligned16(xq_or_null) && sa::aligned16(xh_or_null),
                SA_ERR_ALIGN, "sa_hamming_attention: pointers must be 16-byte aligned");
     hipStream_t st = sa::as_stream(stream);
     const int W = nbits / 64;
@@ -303,6 +366,9 @@ extern "C" int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_c
     L.st = st;
     L.q = q_codes; L.k = k_codes; L.v = v; L.out = out;
     L.H = H; L.Nq = Nq; L.Nk = Nk; L.q_chunks = q_chunks;
+    L.xq = xq_or_null;
+    L.xh = static_cast<_Float16 *>(xh_or_null);
+    L.act_inv_scale = act_inv_scale;
     L.c2 = -2.0f * scale * 1.4426950408889634f;
     // exp2 of c2*dist stays a normal float for every possible distance -> no row reference needed
     L.rowref = !(scale >= 0.0f && -L.c2 * (float)nbits <= 100.0f);

@@ -60,51 +60,40 @@ extern "C" size_t sa_mult_mlp_workspace_bytes(long max_rows, int E, int hid) {
     return up256((size_t)max_rows * hid * 2) + up256((size_t)max_rows * E * 2);
 }
 
-extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const void *w1_f16,
-                               const void *w2_f16, float *out_or_null, float *y_or_null,
-                               const float *gate_or_null, int stages, void *workspace,
-                               size_t workspace_bytes, void *stream) {
-    sa::clear_error();
-    sa::RowSel sel;
-    int rc = sa::validate_rows(rows, &sel);
-    if (rc != SA_OK) return rc;
-    SA_REQUIRE(E > 0 && hid > 0, SA_ERR_INVALID, "sa_mult_mlp_f16: E and hid must be positive");
-    SA_REQUIRE(E % 32 == 0 && hid % 32 == 0, SA_ERR_SHAPE,
-               "sa_mult_mlp_f16: E (%d) and hid (%d) must be multiples of 32", E, hid);
-    if (sel.max_rows == 0) return SA_OK;
-    SA_REQUIRE(x && w1_f16 && w2_f16, SA_ERR_INVALID, "sa_mult_mlp_f16: NULL buffer");
-    SA_REQUIRE(stages >= 1 && stages <= 3, SA_ERR_INVALID, "sa_mult_mlp_f16: stages must be 1, 2 or 3");
-    SA_REQUIRE(!(stages & 2) || out_or_null || y_or_null, SA_ERR_INVALID, "sa_mult_mlp_f16: no output requested");
-    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w1_f16) && sa::aligned16(w2_f16) && sa::aligned16(out_or_null) &&
-                   sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) && sa::aligned16(workspace) &&
-                   sa::aligned4(sel.rows),
-               SA_ERR_ALIGN, "sa_mult_mlp_f16: pointers must be 16-byte aligned");
-    const size_t need = sa_mult_mlp_workspace_bytes(sel.max_rows, E, hid);
-    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
-               "sa_mult_mlp_f16: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-    hipStream_t st = sa::as_stream(stream);
+namespace {
+
+// Both layers.  Either x (fp32, gathered and rounded to fp16 by a small kernel first) or
+// xh_all (fp16 rows of every token, picked by `sel` inside the GEMM) is given.
+int mult_mlp_impl(const float *x, const _Float16 *xh_all, const sa::RowSel &sel, int E, int hid, const void *w1_f16,
+                  const void *w2_f16, float *out_or_null, float *y_or_null, const float *gate_or_null, int stages,
+                  void *workspace, hipStream_t st) {
+    int rc;
     _Float16 *hbuf = static_cast<_Float16 *>(workspace);
     _Float16 *xh = reinterpret_cast<_Float16 *>(static_cast<uint8_t *>(workspace) +
                                                  up256((size_t)sel.max_rows * hid * 2));
-
     if (stages & 1) {
-        const long total = sel.max_rows * (E / 4);
-        const long blocks = (total + 255) / 256;
-        SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_mult_mlp_f16: too many rows");
-        gather_half_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(reinterpret_cast<const float4 *>(x), E / 4,
-                                                                         sel, reinterpret_cast<v4h *>(xh));
-        rc = sa::check_launch("sa_mult_mlp_f16(gather)");
-        if (rc != SA_OK) return rc;
         sa::GemmArgs g;
-        g.a = xh;
+        if (xh_all) {
+            g.a = xh_all;
+            g.gather_a = true;
+        } else {
+            const long total = sel.max_rows * (E / 4);
+            const long blocks = (total + 255) / 256;
+            SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_mult_mlp_f16: too many rows");
+            gather_half_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(reinterpret_cast<const float4 *>(x),
+                                                                             E / 4, sel, reinterpret_cast<v4h *>(xh));
+            rc = sa::check_launch("sa_mult_mlp_f16(gather)");
+            if (rc != SA_OK) return rc;
+            g.a = xh;
+            g.gather_a = false;
+        }
         g.b[0] = w1_f16;
         g.b[1] = nullptr;
         g.sel = sel;
-        g.gather_a = false;
         g.K = E;
         g.N = hid;
         sa::Epilogue e1;
-        e1.hh = static_cast<_Float16 *>(hbuf);
+        e1.hh = hbuf;
         MultStore<sa::kEpiGeluHalf> s1(e1);
         rc = sa::launch_gemm<sa::F16Traits>(g, s1, st, "sa_mult_mlp_f16(fc1)");
         if (rc != SA_OK) return rc;
@@ -134,4 +123,54 @@ extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int h
         if (rc != SA_OK) return rc;
     }
     return SA_OK;
+}
+
+int check_mult_args(const void *x, const sa_rows *rows, sa::RowSel *sel, int E, int hid, const void *w1_f16,
+                    const void *w2_f16, float *out_or_null, float *y_or_null, const float *gate_or_null, int stages,
+                    void *workspace, size_t workspace_bytes) {
+    int rc = sa::validate_rows(rows, sel);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(E > 0 && hid > 0, SA_ERR_INVALID, "sa_mult_mlp_f16: E and hid must be positive");
+    SA_REQUIRE(E % 32 == 0 && hid % 32 == 0, SA_ERR_SHAPE,
+               "sa_mult_mlp_f16: E (%d) and hid (%d) must be multiples of 32", E, hid);
+    if (sel->max_rows == 0) return SA_OK;
+    SA_REQUIRE(x && w1_f16 && w2_f16, SA_ERR_INVALID, "sa_mult_mlp_f16: NULL buffer");
+    SA_REQUIRE(stages >= 1 && stages <= 3, SA_ERR_INVALID, "sa_mult_mlp_f16: stages must be 1, 2 or 3");
+    SA_REQUIRE(!(stages & 2) || out_or_null || y_or_null, SA_ERR_INVALID, "sa_mult_mlp_f16: no output requested");
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w1_f16) && sa::aligned16(w2_f16) && sa::aligned16(out_or_null) &&
+                   sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) && sa::aligned16(workspace) &&
+                   sa::aligned4(sel->rows),
+               SA_ERR_ALIGN, "sa_mult_mlp_f16: pointers must be 16-byte aligned");
+    const size_t need = sa_mult_mlp_workspace_bytes(sel->max_rows, E, hid);
+    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
+               "sa_mult_mlp_f16: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    return SA_OK;
+}
+
+}  // namespace
+
+extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const void *w1_f16,
+                               const void *w2_f16, float *out_or_null, float *y_or_null,
+                               const float *gate_or_null, int stages, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    sa::clear_error();
+    sa::RowSel sel;
+    int rc = check_mult_args(x, rows, &sel, E, hid, w1_f16, w2_f16, out_or_null, y_or_null, gate_or_null, stages,
+                             workspace, workspace_bytes);
+    if (rc != SA_OK || sel.max_rows == 0) return rc;
+    return mult_mlp_impl(x, nullptr, sel, E, hid, w1_f16, w2_f16, out_or_null, y_or_null, gate_or_null, stages,
+                         workspace, sa::as_stream(stream));
+}
+
+extern "C" int sa_mult_mlp_f16_half(const void *xh_all, const sa_rows *rows, int E, int hid, const void *w1_f16,
+                                    const void *w2_f16, float *out_or_null, float *y_or_null,
+                                    const float *gate_or_null, int stages, void *workspace,
+                                    size_t workspace_bytes, void *stream) {
+    sa::clear_error();
+    sa::RowSel sel;
+    int rc = check_mult_args(xh_all, rows, &sel, E, hid, w1_f16, w2_f16, out_or_null, y_or_null, gate_or_null,
+                             stages, workspace, workspace_bytes);
+    if (rc != SA_OK || sel.max_rows == 0) return rc;
+    return mult_mlp_impl(nullptr, static_cast<const _Float16 *>(xh_all), sel, E, hid, w1_f16, w2_f16, out_or_null,
+                         y_or_null, gate_or_null, stages, workspace, sa::as_stream(stream));
 }

@@ -224,16 +224,28 @@ int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &
     return check_launch("shift layer (VALU)");
 }
 
+typedef _Float16 v4h_t __attribute__((ext_vector_type(4)));
+
+// q = int8 codes of x * inv_scale; xh (optional) = x rounded to fp16.  Four elements per thread.
 __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__ x, long n,
-                                                       float inv_scale, int8_t *__restrict__ q) {
+                                                       float inv_scale, int8_t *__restrict__ q,
+                                                       _Float16 *__restrict__ xh) {
     const long i4 = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i4 + 3 < n) {
         const float4 v = *reinterpret_cast<const float4 *>(x + i4);
         const uint32_t b0 = (uint8_t)requant_code(v.x * inv_scale), b1 = (uint8_t)requant_code(v.y * inv_scale);
         const uint32_t b2 = (uint8_t)requant_code(v.z * inv_scale), b3 = (uint8_t)requant_code(v.w * inv_scale);
         *reinterpret_cast<uint32_t *>(q + i4) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+        if (xh) {
+            v4h_t h;
+            h[0] = (_Float16)v.x; h[1] = (_Float16)v.y; h[2] = (_Float16)v.z; h[3] = (_Float16)v.w;
+            *reinterpret_cast<v4h_t *>(xh + i4) = h;
+        }
     } else {
-        for (long i = i4; i < n; ++i) q[i] = requant_code(x[i] * inv_scale);
+        for (long i = i4; i < n; ++i) {
+            q[i] = requant_code(x[i] * inv_scale);
+            if (xh) xh[i] = (_Float16)x[i];
+        }
     }
 }
 
@@ -307,13 +319,21 @@ extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t
 
 extern "C" int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *stream) {
     sa::clear_error();
+    return sa_quantize_act_half(x, n, inv_scale, q, nullptr, stream);
+}
+
+extern "C" int sa_quantize_act_half(const float *x, long n, float inv_scale, int8_t *q, void *xh_or_null,
+                                    void *stream) {
+    sa::clear_error();
     SA_REQUIRE(n >= 0, SA_ERR_INVALID, "sa_quantize_act: n < 0");
     if (n == 0) return SA_OK;
     SA_REQUIRE(x && q, SA_ERR_INVALID, "sa_quantize_act: NULL buffer");
-    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(q), SA_ERR_ALIGN, "sa_quantize_act: pointers must be 16-byte aligned");
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(q) && sa::aligned16(xh_or_null), SA_ERR_ALIGN,
+               "sa_quantize_act: pointers must be 16-byte aligned");
     const long blocks = ((n + 3) / 4 + 255) / 256;
     SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_quantize_act: n too large");
-    quantize_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(x, n, inv_scale, q);
+    quantize_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(
+        x, n, inv_scale, q, static_cast<_Float16 *>(xh_or_null));
     return sa::check_launch("sa_quantize_act");
 }
 

@@ -213,6 +213,46 @@ def test_shift_linear_auto_falls_back_when_k_not_multiple_of_64(sa):
 
 # -------------------------------------------------------- quantisation glue ----
 
+def test_fused_attention_outputs_are_the_quantiser_and_the_half_rounding_of_out(sa):
+    """The int8 and fp16 forms the Hamming kernel writes beside its fp32 output.  Inside the library
+    they must be bit for bit what its quantiser and a half rounding give on that fp32 output; against
+    the oracle (which runs on its own attention output) the codes may differ by one step where a value
+    sits on a rounding boundary."""
+    cfg = wl.scaled_down(wl.C4, B=2)
+    q, k, v = wl.qkv(cfg)
+    pr, scale = wl.proj(cfg), wl.attention_scale(cfg)
+    p = wl.mlp_params(cfg)
+    qc, kc = sa.sa_binarize(dev(q), dev(pr), cfg.nbits), sa.sa_binarize(dev(k), dev(pr), cfg.nbits)
+    out, xq, xh = sa.sa_hamming_attention_fused(qc, kc, dev(v), scale, cfg.nbits, p.act_inv_scale)
+    plain = sa.sa_hamming_attention(qc, kc, dev(v), scale, cfg.nbits)
+    assert torch.equal(out, plain)
+    # same kernel arithmetic on the same fp32 values: the library's own quantiser must agree exactly
+    assert torch.equal(xq, sa.sa_quantize_act(out.view(cfg.T, cfg.E), p.act_inv_scale))
+    assert torch.equal(xh, out.view(cfg.T, cfg.E).to(torch.float16))
+    # and against the oracle end to end: codes differ by at most one step, and rarely
+    o_ref = oracle.hamming_attention(oracle.binarize(q, pr, cfg.nbits), oracle.binarize(k, pr, cfg.nbits), v,
+                                     cfg.nbits, scale)
+    xq_ref = oracle.quantize_act(o_ref.reshape(cfg.T, cfg.E).astype(np.float32), p.act_inv_scale)
+    diff = np.abs(host(xq).astype(np.int32) - xq_ref.astype(np.int32))
+    assert diff.max() <= 1 and (diff != 0).mean() < 1e-3
+
+
+def test_quantize_act_half_and_mult_expert_on_half_rows(sa):
+    cfg = wl.scaled_down(wl.C1, B=2, N=150)
+    p = wl.mlp_params(cfg)
+    T, E = cfg.T, cfg.E
+    x = wl.float_activations(1, T, E)
+    xq, xh = sa.sa_quantize_act_half(dev(x), p.act_inv_scale)
+    assert np.array_equal(host(xq), oracle.quantize_act(x, p.act_inv_scale))
+    assert np.array_equal(host(xh).astype(np.float64), oracle.round_to_half(x.astype(np.float64)))
+    logits = wl.router_logits(cfg)
+    perm_r, _, cnt_r, _ = oracle.moe_dispatch(logits)
+    rows = perm_r[: cnt_r[0]]
+    ref = oracle.mult_mlp(x, rows, p.mw1, p.mw2)
+    out = sa.sa_mult_mlp_f16_half(xh, dev(p.mw1), dev(p.mw2), rows=dev(rows))
+    assert_close(host(out), ref, 2e-3, 1e-3, "Mult expert on fp16 rows")
+
+
 def test_quantize_act_bit_exact(sa):
     g = np.random.default_rng(21)
     x = (g.standard_normal(100003) * 3).astype(np.float32)
