@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--kernels-only", action="store_true",
+                    help="skip the block steps and run only the per-kernel timing pass (for a rocprofv3 trace whose "
+                         "per-kernel averages cover exactly the launches the live timings cover)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device copy first: a kernel of known traffic for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings")
@@ -160,15 +163,16 @@ def main():
         del src, dst
 
     # ---- the timed region: W warm-up steps, then exactly K steps
-    for i in range(args.warmup):
+    n_warm, n_steps = (0, 1) if args.kernels_only else (args.warmup, args.steps)
+    for i in range(n_warm):
         blocks[i % n_sets][0].forward()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(n_steps):
         blocks[i % n_sets][0].forward()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / n_steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
 
     # ---- per-kernel durations, HIP events on the launch stream, same buffers, same rotation

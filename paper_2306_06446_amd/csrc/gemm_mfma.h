@@ -375,7 +375,9 @@ template <class T, int BM, int BN, int SB, int NS, int LS, int OCC, class Store>
 int launch_gemm_tile(const GemmArgs &g, const Store &store, hipStream_t st, const char *what) {
     const long row_tiles = (g.sel.max_rows + BM - 1) / BM;
     const long col_tiles = (g.N + BN - 1) / BN;
-    // the fewest column groups whose share of the B planes leaves room in a 4 MiB L2
+    // The fewest column groups whose share of the B planes stays resident in a 4 MiB L2 next to
+    // the A rows streaming through it.  (Fewer groups fetch fewer bytes when A is the larger operand,
+    // but a B share that is evicted between row tiles costs more time than the extra A traffic.)
     const size_t b_bytes = (size_t)T::kPlanes * g.N * g.K * T::kElemBytes;
     int cg = 1;
     while (cg < 8 && b_bytes / cg > (size_t)(5 << 19)) cg *= 2;     // 2.5 MiB
