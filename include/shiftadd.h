@@ -84,7 +84,11 @@ int sa_binarize_ex(const float *x, int B, int N, int H, int d, const float *proj
  *   q_codes [B,H,Nq,W], k_codes [B,H,Nk,W], v [B,Nk,H,dv], out [B,Nq,H,dv],
  *   kv [B,H,nbits,dv] fp32.  dv in {32, 64, 128}.
  * Sums are fp32, in a fixed order (results are reproducible run to run).
+ * Both phases run on the matrix cores (the +-1 operand against the three exact bf16 term
+ * planes of the fp32 operand: the same sums); adding SA_ADDITIVE_VALU to `phases` runs the
+ * sign-select-and-accumulate kernels on the vector ALU instead.
  */
+#define SA_ADDITIVE_VALU 4
 size_t sa_additive_attention_workspace_bytes(int B, int H, int Nk, int nbits, int dv);
 int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
                           float *out, int B, int H, int Nq, int Nk, int nbits, int dv,

@@ -156,9 +156,15 @@ bool dv_ok(int dv) { return dv == 32 || dv == 64 || dv == 128; }
 
 extern "C" size_t sa_additive_attention_workspace_bytes(int B, int H, int Nk, int nbits, int dv) {
     if (B <= 0 || H <= 0 || Nk <= 0 || nbits <= 0 || dv <= 0 || nbits % 64) return 0;
+    // room for whichever variant runs: partial sums [splits][B*H][nbits][dv]
     const KtvPlan p = plan_ktv(B, H, Nk, nbits);
-    if (p.splits <= 1) return 0;
-    return (size_t)p.splits * B * H * nbits * dv * sizeof(float);
+    int splits = p.splits;
+    if (sa::additive_mfma_ktv_supported(nbits, dv)) {
+        const sa::AdditiveMfmaPlan m = sa::plan_additive_mfma(B, H, Nk, nbits);
+        if (m.splits > splits) splits = m.splits;
+    }
+    if (splits <= 1) return 0;
+    return (size_t)splits * B * H * nbits * dv * sizeof(float);
 }
 
 extern "C" int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_codes,
@@ -166,7 +172,9 @@ extern "C" int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_
                                      int nbits, int dv, float scale, float *kv, int phases,
                                      void *workspace, size_t workspace_bytes, void *stream) {
     sa::clear_error();
-    SA_REQUIRE(phases >= 1 && phases <= 3, SA_ERR_INVALID, "sa_additive_attention: phases must be 1, 2 or 3");
+    SA_REQUIRE(phases >= 1 && phases <= 7 && (phases & 3) != 0, SA_ERR_INVALID,
+               "sa_additive_attention: phases must be 1, 2 or 3, optionally + 4");
+    const bool valu = (phases & SA_ADDITIVE_VALU) != 0;
     SA_REQUIRE(B >= 0 && H >= 0 && Nq >= 0 && Nk >= 0 && nbits > 0 && dv > 0, SA_ERR_INVALID,
                "sa_additive_attention: negative size");
     SA_REQUIRE(nbits % 64 == 0 && nbits <= 4096, SA_ERR_SHAPE,
@@ -190,6 +198,26 @@ extern "C" int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_
         } else {
             SA_REQUIRE(k_codes != nullptr && v != nullptr, SA_ERR_INVALID,
                        "sa_additive_attention: phase 1 needs k_codes and v");
+            if (!valu && sa::additive_mfma_ktv_supported(nbits, dv)) {
+                const sa::AdditiveMfmaPlan m = sa::plan_additive_mfma(B, H, Nk, nbits);
+                float *dst = kv;
+                if (m.splits > 1) {
+                    const size_t need = (size_t)m.splits * kv_elems * sizeof(float);
+                    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
+                               "sa_additive_attention: workspace of %zu bytes needed, %zu given", need,
+                               workspace_bytes);
+                    dst = static_cast<float *>(workspace);
+                }
+                int rc = sa::launch_ktv_mfma(k_codes, v, dst, B, H, Nk, nbits, dv, m, st);
+                if (rc != SA_OK) return rc;
+                if (m.splits > 1) {
+                    const long n4 = (long)(kv_elems / 4);
+                    ktv_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(
+                        reinterpret_cast<const float4 *>(dst), reinterpret_cast<float4 *>(kv), n4, m.splits);
+                    rc = sa::check_launch("sa_additive_attention(reduce)");
+                    if (rc != SA_OK) return rc;
+                }
+            } else {
             const KtvPlan p = plan_ktv(B, H, Nk, nbits);
             float *dst = kv;
             if (p.splits > 1) {
@@ -216,11 +244,14 @@ extern "C" int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_
                 rc = sa::check_launch("sa_additive_attention(reduce)");
                 if (rc != SA_OK) return rc;
             }
+            }
         }
     }
     if ((phases & 2) && Nq > 0) {
         SA_REQUIRE(q_codes != nullptr && out != nullptr, SA_ERR_INVALID,
                    "sa_additive_attention: phase 2 needs q_codes and out");
+        if (!valu && sa::additive_mfma_qkv_supported(nbits, dv))
+            return sa::launch_qkv_mfma(q_codes, kv, out, B, H, Nq, nbits, dv, scale, st);
         const int n_chunks = (Nq + 63) / 64;
         const long n_tasks = BH * n_chunks;
         const long blocks = (n_tasks + 3) / 4;

@@ -53,6 +53,21 @@ bool binarize_mfma_supported(int d, int nbits);
 int launch_binarize_mfma(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int d,
                          int nbits, hipStream_t st);
 
+// Additive attention on the matrix cores (additive_mfma.hip).
+struct AdditiveMfmaPlan {
+    int groups;             // groups of up to 4 code words
+    int wb, ph;             // words per workgroup, token phases per word
+    int splits;             // token ranges (partial K^T V each)
+    int tokens_per_block;
+};
+bool additive_mfma_ktv_supported(int nbits, int dv);
+bool additive_mfma_qkv_supported(int nbits, int dv);
+AdditiveMfmaPlan plan_additive_mfma(int B, int H, int Nk, int nbits);
+int launch_ktv_mfma(const uint64_t *k_codes, const float *v, float *dst, int B, int H, int Nk, int nbits, int dv,
+                    const AdditiveMfmaPlan &p, hipStream_t st);
+int launch_qkv_mfma(const uint64_t *q_codes, const float *kv, float *out, int B, int H, int Nq, int nbits, int dv,
+                    float scale, hipStream_t st);
+
 }  // namespace sa
 
 #define SA_REQUIRE(cond, code, ...) \

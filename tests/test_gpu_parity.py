@@ -96,28 +96,51 @@ def test_binarize_sign_mode_bit_exact(sa):
 
 # -------------------------------------------------------- additive attention ----
 
+@pytest.mark.parametrize("valu", [0, 4], ids=["mfma", "valu"])
 @pytest.mark.parametrize("B,H,Nq,Nk,nbits,dv", [
     (1, 3, 197, 197, 64, 64),     # c1
     (2, 1, 777, 777, 64, 32),     # c2 widths
     (1, 2, 1500, 1500, 256, 64),  # c5 widths, several splits
     (2, 2, 65, 300, 128, 128),    # Nq != Nk, dv = 128
     (1, 1, 1, 1, 64, 32),         # degenerate
+    (1, 2, 130, 257, 192, 32),    # three code words: K^T V on the matrix cores, Q(K^T V) on the vector ALU
+    (1, 1, 40, 500, 384, 64),     # six code words: two word groups, the second half empty
+    (1, 1, 90, 129, 256, 128),    # K^T V planes too large for the LDS: Q(K^T V) on the vector ALU
 ])
-def test_additive_attention_matches_oracle(sa, B, H, Nq, Nk, nbits, dv):
+def test_additive_attention_matches_oracle(sa, B, H, Nq, Nk, nbits, dv, valu):
     q = wl.random_codes(1, (B, H, Nq), nbits)
     k = wl.random_codes(2, (B, H, Nk), nbits)
     v = np.random.default_rng([4, B, H, Nk, dv]).standard_normal((B, Nk, H, dv), dtype=np.float32)
     scale = float(np.float32(1.0 / math.sqrt(Nk * nbits)))
     o_ref, kv_ref = oracle.additive_attention(q, k, v, nbits, scale)
-    out, kv = sa.sa_additive_attention(dev(q), dev(k), dev(v), scale, nbits)
+    out, kv = sa.sa_additive_attention(dev(q), dev(k), dev(v), scale, nbits, phases=3 + valu)
     rtol, atol = kv_tolerance(kv_ref)
     assert_close(host(kv), kv_ref, rtol, atol, "K^T V")
     assert_close(host(out), o_ref, ATTN_RTOL, ATTN_ATOL, "Q(K^T V)")
     # phases run separately give the same bits as the fused call
-    _, kv1 = sa.sa_additive_attention(None, dev(k), dev(v), scale, nbits, phases=1)
+    _, kv1 = sa.sa_additive_attention(None, dev(k), dev(v), scale, nbits, phases=1 + valu)
     assert torch.equal(kv1, kv)
-    out2, _ = sa.sa_additive_attention(dev(q), None, None, scale, nbits, phases=2, kv=kv1)
+    out2, _ = sa.sa_additive_attention(dev(q), None, None, scale, nbits, phases=2 + valu, kv=kv1)
     assert torch.equal(out2, out)
+
+
+def test_additive_attention_wide_range_values(sa):
+    """V with magnitudes across 2^-40 .. 2^40 and exact powers of two: the three-term bf16 split must
+    carry every fp32 value exactly, so tiny addends are not lost next to large ones of other rows."""
+    B, H, N, nbits, dv = 1, 1, 160, 64, 32
+    g = np.random.default_rng(11)
+    q = wl.random_codes(3, (B, H, N), nbits)
+    k = wl.random_codes(4, (B, H, N), nbits)
+    v = (g.standard_normal((B, N, H, dv)) * np.exp2(g.integers(-40, 41, size=(B, N, H, 1)))).astype(np.float32)
+    v[0, :8, 0, :] = np.exp2(np.arange(8, dtype=np.float32))[:, None]
+    o_ref, kv_ref = oracle.additive_attention(q, k, v, nbits, 1.0)
+    out, kv = sa.sa_additive_attention(dev(q), dev(k), dev(v), 1.0, nbits)
+    rtol, atol = kv_tolerance(kv_ref)
+    assert_close(host(kv), kv_ref, rtol, atol, "K^T V, wide range")
+    # a single token: K^T V is +-V exactly, whatever the magnitudes
+    _, kv1 = sa.sa_additive_attention(None, dev(k[:, :, :1]), dev(v[:, :1]), 1.0, nbits, phases=1)
+    bits = ((k[0, 0, 0, 0] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(np.float64) * 2 - 1
+    assert np.array_equal(host(kv1)[0, 0].astype(np.float64), bits[:, None] * v[0, 0, 0].astype(np.float64)[None, :])
 
 
 def test_additive_attention_is_reproducible(sa):
