@@ -26,7 +26,10 @@ PEAK_TFLOPS = {                  # dense peaks of MI355X
     "alu_int": 39.3,             # 32-bit integer vector ops: 256 CU x 64 lanes x 2.4 GHz
     "mfma_i8": 5000.0,
     "mfma_f16": 2500.0,
-    "mfma_f32": 157.3,           # an fp32 contraction is priced at the fp32 matrix peak, however it is run
+    # an fp32 contraction with one exactly-representable (+-1 or two-term) operand runs as three bf16
+    # matrix-core products of the fp32 operand's exact bf16 terms: its algorithmic flops are priced at
+    # the bf16 peak / 3 (above the fp32 matrix peak of 157.3, which such a kernel can beat)
+    "mfma_bf16x3": 2500.0 / 3,
 }
 
 
@@ -62,21 +65,21 @@ def kernel_table(cfg, p, counts):
     bin_bytes = rows * cfg.d * 4 + cfg.d * cfg.nbits * 4 + rows * cfg.nbits // 8
     bin_flop = 2 * rows * cfg.nbits * cfg.d
     for name in ("binarize_q", "binarize_k"):
-        tab.append(dict(name=name, bytes=bin_bytes, ops=bin_flop, compute="alu_fp32"))
+        tab.append(dict(name=name, bytes=bin_bytes, ops=bin_flop, compute="mfma_bf16x3" if cfg.d in (32, 64, 128) else "alu_fp32"))
     code_b = rows * cfg.nbits // 8
     v_b = rows * cfg.dv * 4
     if cfg.attention == "linear":
         kv_b = B * H * cfg.nbits * cfg.dv * 4
-        adds = rows * cfg.nbits * cfg.dv          # one accumulate per (token, bit, column)
-        tab.append(dict(name="ktv", bytes=code_b + v_b + kv_b, ops=adds, compute="alu_fp32"))
-        tab.append(dict(name="qkv", bytes=code_b + kv_b + v_b, ops=adds, compute="alu_fp32"))
+        flops = 2 * rows * cfg.nbits * cfg.dv     # one sign-selected accumulate per (token, bit, column)
+        tab.append(dict(name="ktv", bytes=code_b + v_b + kv_b, ops=flops, compute="mfma_bf16x3"))
+        tab.append(dict(name="qkv", bytes=code_b + kv_b + v_b, ops=flops, compute="mfma_bf16x3"))
     else:
         pairs = B * H * N * N
         # P * V is the dense fp32 contraction of this kernel (it runs as three bf16 matrix-core products);
         # with an MLP behind it the kernel also writes its output as int8 codes (and fp16 for a Mult expert)
         extra = T * E * (1 + (2 if counts is not None else 0)) if cfg.E else 0
         tab.append(dict(name="hamming", bytes=2 * code_b + 2 * v_b + extra, ops=2 * pairs * cfg.dv,
-                        compute="mfma_f32"))
+                        compute="mfma_bf16x3"))
     if cfg.E:
         if cfg.attention == "linear":
             tab.append(dict(name="quantize", bytes=T * E * (5 + (2 if counts is not None else 0)), ops=2 * T * E,

@@ -28,8 +28,8 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kListCap = 192;                 // unsettled bits parked per wavefront
-constexpr float kKeepFactor = 6.26e-8f;       // (2^-12)^2 * 1.05
-constexpr float kKeepFloor = 1e-37f;          // |z~| below ~3e-19: the relative error model does not hold
+constexpr float kKeepFactor = 6.26e-8f;       // (2^-12)^2 * 1.05: keep = sqrt(kKeepFactor * |x|^2)
+constexpr float kKeepFloor = 1e-37f;          // keep >= ~3e-19: below that the relative error model does not hold
 
 struct RowMap {
     int N, H, W;
@@ -130,14 +130,18 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
         float n2 = 0.0f;
 #pragma unroll
         for (int t = 0; t < TPC; ++t) n2 += cn2_s[t][c];
-        const float inv = 1.0f / __builtin_sqrtf(n2);      // 0 or Inf for a dead / overflowing column: all parked
+        // a dead, overflowing or non-finite column gets an all-zero r^: z~ = 0 fails the margin test, so
+        // every bit of that column is parked and settled by the defining chain
+        const float inv_raw = 1.0f / __builtin_sqrtf(n2);
+        const bool usable = inv_raw > 0.0f && inv_raw < __builtin_inff();
+        const float inv = usable ? inv_raw : 0.0f;
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) {
             v8bf vh, vl;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 __bf16 hi, lo;
-                split_bf16(rv[st * 8 + e] * inv, hi, lo);
+                split_bf16(usable ? rv[st * 8 + e] * inv : 0.0f, hi, lo);
                 vh[e] = hi;
                 vl[e] = lo;
             }
@@ -177,7 +181,9 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
 #pragma unroll
         for (int k = 0; k < HALF; ++k) nx2 += xv[k] * xv[k];
         nx2 += __shfl_xor(nx2, 32);                                // |x_row|^2, row = r0 + i_loc
-        const float thr = __builtin_fmaxf(kKeepFactor * nx2, kKeepFloor);
+        // keep sign(z~) where |z~| > keep = 2^-12 |x| (floored); a non-finite |x|^2 keeps nothing
+        const float keep = nx2 < __builtin_inff() ? __builtin_sqrtf(__builtin_fmaxf(kKeepFactor * nx2, kKeepFloor))
+                                                  : __builtin_inff();
 
         // z~^T: accumulator (jt, r) of lane (i_loc, g) = hash bit jt*32 + 8*(r/4) + 4*g + r%4 of row i_loc
         v16f acc[JT];
@@ -208,22 +214,34 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        // provisional bits (sign of z~; -0 and NaN are parked anyway) and the unsettled ones,
-        // one mask bit per accumulator register, per 32-bit group
+        // provisional bits (sign of z~; -0 is parked anyway) and the unsettled ones, one mask bit per
+        // accumulator register, per 32-bit group.  Signs: 16 funnel shifts collect the sign bits, then
+        // the four nibbles move to their byte.  Margin: the smallest |z~| of the 16 decides for all of
+        // them at once (99.7 % of the groups); only a group with a doubtful element is tested one by one.
         const bool row_ok = (r0 + i_loc) < rows;
         uint32_t bits[JT], park[JT];
         uint32_t any_park = 0;
 #pragma unroll
         for (int jt = 0; jt < JT; ++jt) {
-            uint32_t neg = 0, pk = 0;
+            uint32_t neg = 0;                                                 // bit r = sign of register r
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float z = acc[jt][r];
-                const int pos = 8 * (r >> 2) + (r & 3);                       // + 4 * g, applied below
-                neg |= (__builtin_bit_cast(uint32_t, z) >> 31) << pos;
-                pk |= (uint32_t)(!(z * z > thr)) << pos;
+            for (int q = 0; q < 16; ++q) {
+                const float z = acc[jt][15 - q];
+                neg = __builtin_amdgcn_alignbit(neg, __builtin_bit_cast(uint32_t, z), 31);
             }
-            bits[jt] = (~neg & 0x0f0f0f0fu) << (4 * g);
+            const uint32_t pos_bits = ~neg;
+            const uint32_t spread = (pos_bits & 0xFu) | ((pos_bits & 0xF0u) << 4) | ((pos_bits & 0xF00u) << 8) |
+                                    ((pos_bits & 0xF000u) << 12);             // register r -> bit 8*(r/4) + r%4
+            bits[jt] = spread << (4 * g);
+            float smallest = __builtin_fabsf(acc[jt][0]);
+#pragma unroll
+            for (int r = 1; r < 16; ++r) smallest = __builtin_fminf(smallest, __builtin_fabsf(acc[jt][r]));
+            uint32_t pk = 0;
+            if (__builtin_amdgcn_ballot_w64(!(smallest > keep)) != 0) {        // wave-uniform
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    pk |= (uint32_t)(!(__builtin_fabsf(acc[jt][r]) > keep)) << (8 * (r >> 2) + (r & 3));
+            }
             park[jt] = row_ok ? (pk << (4 * g)) : 0u;
             any_park |= park[jt];
         }
