@@ -329,7 +329,7 @@ def cpu_baseline(cfg, sample_batch):
     import oracle
     from paper_2306_06446_amd import workloads as wl
 
-    default = {1: 1, 2: 2, 4: 8, 5: 1}[cfg.cfg_id]
+    default = {1: 1, 2: 8, 4: 32, 5: 2}[cfg.cfg_id]      # a few seconds of wall time on 16 cores
     sb = sample_batch or default
     n = cfg.N if cfg.cfg_id != 5 else 2048
     small = wl.scaled_down(cfg, B=sb, N=n)
