@@ -36,6 +36,24 @@ __device__ inline int8_t requant_code(float t) {
     return (t != t) ? (int8_t)0 : (int8_t)t;
 }
 
+// The same code for an int32 accumulator and a finite scale, as the table index code + 128 (1..255),
+// in five vector operations: clamp first (a finite product never is NaN), then add 1.5 * 2^23 + 128,
+// which rounds to nearest even at unit spacing and leaves the index in the low byte of the sum.
+// The host passes a finite scale (requant_scale_finite): the results are those of requant_code.
+__device__ inline uint32_t requant_index(int32_t acc, float rq_finite) {
+    const float t = __builtin_amdgcn_fmed3f((float)acc * rq_finite, -127.0f, 127.0f);
+    return __builtin_bit_cast(uint32_t, t + 12583040.0f) & 0xFFu;
+}
+
+// NaN -> 0 (every product is NaN -> code 0, as 0 * acc), +-Inf -> +-FLT_MAX (same clamped codes; 0 * acc = 0 -> code 0,
+// where Inf * 0 = NaN -> code 0 as well).
+inline float requant_scale_finite(float s) {
+    if (s != s) return 0.0f;
+    if (s > 3.402823466e38f) return 3.402823466e38f;
+    if (s < -3.402823466e38f) return -3.402823466e38f;
+    return s;
+}
+
 // Row of the 32x32 accumulator tile that register r of lane `lane` holds; the column is lane % 32.
 __device__ inline int mfma32_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 

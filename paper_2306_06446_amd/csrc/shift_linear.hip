@@ -155,6 +155,11 @@ __global__ __launch_bounds__(256) void decode_w4_kernel(const uint4 *__restrict_
     plane_b[2 * i + 1] = make_uint4(ob[4], ob[5], ob[6], ob[7]);
 }
 
+inline Epilogue with_finite_scale(Epilogue e) {
+    e.rq = requant_scale_finite(e.rq);
+    return e;
+}
+
 template <int MODE>
 struct ShiftStore {
     static constexpr int kBytes = (MODE == kEpiRequantLut) ? 1 : 4;
@@ -164,14 +169,14 @@ struct ShiftStore {
     void *out;             // int32 rows | int8 hidden rows | scattered fp32 rows
     const void *table;     // the 256-entry activation table
     const float *gate;
-    explicit ShiftStore(const Epilogue &epi)
-        : e(epi),
+    explicit ShiftStore(const Epilogue &epi)     // epi.rq is made finite here: convert() relies on it
+        : e(with_finite_scale(epi)),
           out(MODE == kEpiInt32 ? (void *)epi.y : MODE == kEpiRequantLut ? (void *)epi.h : (void *)epi.yf),
           table(epi.lut),
           gate(MODE == kEpiScatterI32 ? epi.gate : nullptr) {}
     __device__ inline uint32_t convert(int32_t acc, int n, const uint8_t *lds_table) const {
         if (MODE == kEpiInt32) return (uint32_t)(acc + (e.bias ? e.bias[n] : 0));
-        if (MODE == kEpiRequantLut) return lds_table[(int)requant_code((float)acc * e.rq) + 128];
+        if (MODE == kEpiRequantLut) return lds_table[requant_index(acc, e.rq)];
         return __builtin_bit_cast(uint32_t, e.out_scale * (float)acc);
     }
 };

@@ -357,6 +357,20 @@ def test_shift_mlp_bit_exact_with_row_lists(sa, variant):
         assert np.array_equal(host(y2d), y2_ref)
 
 
+@pytest.mark.parametrize("scale", [0.5, 1.0, -0.25, 1e-9, 1e30, float("inf"), float("-inf"), float("nan"), 0.0])
+def test_shift_mlp_requant_scale_edge_cases(sa, scale):
+    """The fused requantisation between the two Shift layers: ties (scale 0.5 on odd sums), saturation,
+    sign flip, and the non-finite scales (NaN -> code 0 everywhere; Inf saturates, and 0 * Inf -> code 0)."""
+    cfg = wl.scaled_down(wl.C1, B=1, N=70)
+    p = wl.mlp_params(cfg)
+    xq = wl.int8_activations(1, cfg.T, cfg.E, extra=9)
+    xq[0, :] = 0                                              # an all-zero row: 0 * Inf
+    ref = oracle.shift_mlp(xq, p.w1, p.w2, scale, p.lut)
+    for variant in (0, 1):
+        got = sa.sa_shift_mlp(dev(xq), dev(p.w1), dev(p.w2), scale, dev(p.lut), variant=variant)
+        assert np.array_equal(host(got), ref), "variant %d" % variant
+
+
 def test_mult_mlp_matches_oracle(sa):
     cfg = wl.scaled_down(wl.C1, B=2, N=150)
     p = wl.mlp_params(cfg)
