@@ -11,7 +11,7 @@
 //   K^T V   : M = code bits (one 64-bit word = two 32-bit tiles per wavefront), N = dv columns,
 //             K = tokens, 16 per MFMA.  The A operand is built in registers from the code words
 //             (one bit-field extract per element); V is staged through LDS transposed into its
-//             three bf16 planes, 128 tokens per chunk.  Token ranges are split over workgroups;
+//             three bf16 planes, 64 tokens per chunk, double-buffered.  Token ranges are split over workgroups;
 //             partial sums meet in a second pass in ascending order (no float atomics).
 //   Q(K^T V): M = tokens (TM 32-token tiles per wavefront), N = dv columns, K = code bits.  The
 //             A operand of a step is the 8 bf16 signs of one code byte, read from a 256-entry
@@ -24,26 +24,27 @@ namespace {
 
 using sa::kWave;
 
-constexpr int kChunk = 128;                // tokens staged at a time (K^T V)
-constexpr int kChunkStride = kChunk + 8;   // bf16 elements per transposed row: 272 bytes, conflict-free b128 reads
 constexpr int kStageBatch = 4;             // staging tasks whose loads a thread keeps in flight together
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
-// Round-to-nearest-even bf16 of a finite float, as the upper 16 bits.
-__device__ inline uint32_t bf16_bits(float f) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
-// f = t0 + t1 + t2 exactly (three bf16 terms, each the rounding of what is left).
-__device__ inline void split3(float f, uint32_t (&t)[3]) {
-    t[0] = bf16_bits(f);
-    const float r1 = f - __builtin_bit_cast(float, t[0] << 16);
-    t[1] = bf16_bits(r1);
-    const float r2 = r1 - __builtin_bit_cast(float, t[1] << 16);
-    t[2] = bf16_bits(r2);
+// (a, b) = sum of three bf16 term pairs, exactly: each term is the round-to-nearest bf16 of what the
+// previous terms left.  t[p] holds term p of a in its lower and of b in its upper half (one
+// v_cvt_pk_bf16_f32 per term pair).
+__device__ inline void split3_pair(float a, float b, uint32_t (&t)[3]) {
+    v2f r = {a, b};
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        t[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2bf));
+        if (p < 2) {
+            r[0] -= __builtin_bit_cast(float, t[p] << 16);
+            r[1] -= __builtin_bit_cast(float, t[p] & 0xFFFF0000u);
+        }
+    }
 }
 
 // Rows r0, r0+1 (pairs) x columns of an fp32 matrix [n_rows, DV] with row stride `row_stride` floats
@@ -73,13 +74,12 @@ __device__ inline void stage_transposed(const float *__restrict__ src, size_t ro
             const float a0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, a1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                uint32_t s0[3], s1[3];
-                split3(a0[c], s0);
-                split3(a1[c], s1);
+                uint32_t t[3];
+                split3_pair(a0[c], a1[c], t);
                 const int off = (c4 * 4 + c) * stride + j;             // even: 4-byte aligned
-                *reinterpret_cast<uint32_t *>(plane0 + off) = s0[0] | (s1[0] << 16);
-                *reinterpret_cast<uint32_t *>(plane1 + off) = s0[1] | (s1[1] << 16);
-                *reinterpret_cast<uint32_t *>(plane2 + off) = s0[2] | (s1[2] << 16);
+                *reinterpret_cast<uint32_t *>(plane0 + off) = t[0];
+                *reinterpret_cast<uint32_t *>(plane1 + off) = t[1];
+                *reinterpret_cast<uint32_t *>(plane2 + off) = t[2];
             }
         }
     }
@@ -97,13 +97,71 @@ __device__ inline uint32_t sign_pair(uint32_t lo, uint32_t hi, int pos) {
 // ------------------------------------------------------------------------------ K^T V ----
 // Workgroup: one (b, h), one group of up to 4 code words, one token range.  WB words per group
 // (1, 2, 3 or 4), PH token phases (wavefronts that share a word take alternate 16-token steps).
+// Tokens pass in chunks of 64 through two LDS buffers: the rows of chunk c+1 are loaded into
+// registers before chunk c is multiplied and written (split into their planes) after it.
+constexpr int kTok = 64;                   // tokens per chunk
+constexpr int kTokStride = kTok + 8;       // bf16 elements per transposed row: 144 bytes, conflict-free b128 reads
+
+template <int DV>
+struct KtvChunk {
+    static constexpr int U = (kTok / 2 * (DV / 4) + 191) / 192;      // staging tasks per thread (>= 192 threads)
+    float4 v0[U], v1[U];
+    uint64_t code;
+};
+
+template <int DV>
+__device__ inline void ktv_load(KtvChunk<DV> &c, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
+                                long bh, int b, int h, int H, int Nk, int W, int w0, int wb, int WB, long j0, int n,
+                                int tid, int n_threads) {
+    // one code word per thread: kTok * WB <= 256 of them, zero past the last token / word
+    const int j = tid / WB, wq = tid % WB;
+    c.code = (tid < kTok * WB && j < n && wq < wb) ? k_codes[((size_t)bh * Nk + j0 + j) * W + w0 + wq] : 0ull;
+    constexpr int n_tasks = kTok / 2 * (DV / 4);
+    const float *src = v + (((size_t)b * Nk + j0) * H + h) * DV;
+    const size_t row_stride = (size_t)H * DV;
+#pragma unroll
+    for (int u = 0; u < KtvChunk<DV>::U; ++u) {
+        const int t = u * n_threads + tid;
+        const int c4 = t % (DV / 4), jr = 2 * (t / (DV / 4));
+        c.v0[u] = c.v1[u] = make_float4(0.f, 0.f, 0.f, 0.f);     // rows past the last token add nothing
+        const float *p = src + (size_t)jr * row_stride + c4 * 4;
+        if (t < n_tasks && jr < n) c.v0[u] = *reinterpret_cast<const float4 *>(p);
+        if (t < n_tasks && jr + 1 < n) c.v1[u] = *reinterpret_cast<const float4 *>(p + row_stride);
+    }
+}
+
+template <int DV>
+__device__ inline void ktv_store(const KtvChunk<DV> &c, uint64_t *kc, uint16_t *plane0, uint16_t *plane1, uint16_t *plane2,
+                                 int WB, int tid, int n_threads) {
+    if (tid < kTok * WB) kc[tid] = c.code;
+    constexpr int n_tasks = kTok / 2 * (DV / 4);
+#pragma unroll
+    for (int u = 0; u < KtvChunk<DV>::U; ++u) {
+        const int t = u * n_threads + tid;
+        if (t >= n_tasks) continue;
+        const int c4 = t % (DV / 4), jr = 2 * (t / (DV / 4));
+        const float a0[4] = {c.v0[u].x, c.v0[u].y, c.v0[u].z, c.v0[u].w}, a1[4] = {c.v1[u].x, c.v1[u].y, c.v1[u].z, c.v1[u].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t t3[3];
+            split3_pair(a0[q], a1[q], t3);
+            const int off = (c4 * 4 + q) * kTokStride + jr;          // even: 4-byte aligned
+            *reinterpret_cast<uint32_t *>(plane0 + off) = t3[0];
+            *reinterpret_cast<uint32_t *>(plane1 + off) = t3[1];
+            *reinterpret_cast<uint32_t *>(plane2 + off) = t3[2];
+        }
+    }
+}
+
 template <int DV>
 __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
                                                        float *__restrict__ dst, int H, int Nk, int W, int WB, int PH,
                                                        int splits, int tokens_per_block) {
     constexpr int JT = DV / 32;
-    __shared__ __attribute__((aligned(16))) uint64_t kc_s[kChunk * 4];
-    __shared__ __attribute__((aligned(16))) uint16_t vt_s[3][DV * kChunkStride];
+    constexpr int PLANE = DV * kTokStride;
+    __shared__ __attribute__((aligned(16))) uint64_t kc_s[2][kTok * 4];
+    __shared__ __attribute__((aligned(16))) uint16_t vt_s[2][3 * PLANE];
+    static_assert(sizeof(vt_s) >= 4 * 2 * JT * 16 * 64 * 4 / 2, "the phase reduction reuses the V planes");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -131,25 +189,28 @@ __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restric
 
     const long first = (long)split * tokens_per_block;
     const long last = min((long)Nk, first + tokens_per_block);
-    for (long j0 = first; j0 < last; j0 += kChunk) {
-        const int n = (int)min((long)kChunk, last - j0);
+    KtvChunk<DV> regs;
+    if (first < last)
+        ktv_load<DV>(regs, k_codes, v, bh, b, h, H, Nk, W, w0, wb, WB, first, (int)min((long)kTok, last - first), tid,
+                     n_threads);
+    int buf = 0;
+    for (long j0 = first; j0 < last; j0 += kTok, buf ^= 1) {
+        const int n = (int)min((long)kTok, last - j0);
         const int n_pad = (n + 15) & ~15;
-        __syncthreads();                           // the previous chunk has been consumed
-        for (int t = tid; t < n_pad * WB; t += n_threads) {
-            const int j = t / WB, wq = t % WB;
-            kc_s[t] = (j < n && wq < wb) ? k_codes[((size_t)bh * Nk + j0 + j) * W + w0 + wq] : 0ull;
-        }
-        // rows past the last token are zero in every plane: whatever sign they meet adds nothing
-        stage_transposed<DV>(v + (((size_t)b * Nk + j0) * H + h) * DV, (size_t)H * DV, n, n_pad, vt_s[0], vt_s[1],
-                             vt_s[2], kChunkStride, tid, n_threads);
-        __syncthreads();
+        uint16_t *pl = vt_s[buf];
+        ktv_store<DV>(regs, kc_s[buf], pl, pl + PLANE, pl + 2 * PLANE, WB, tid, n_threads);
+        __syncthreads();                           // this chunk is staged; the other buffer has been consumed
+        if (j0 + kTok < last)
+            ktv_load<DV>(regs, k_codes, v, bh, b, h, H, Nk, W, w0, wb, WB, j0 + kTok,
+                         (int)min((long)kTok, last - j0 - kTok), tid, n_threads);
         if (!active) continue;
+        const uint64_t *kc = kc_s[buf];
         for (int k0 = 16 * phase; k0 < n_pad; k0 += 16 * PH) {
             const int kb = k0 + 8 * kg;            // this lane's first token of the step
             uint32_t lo[8], hi[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint64_t wd = kc_s[(kb + e) * WB + wl];
+                const uint64_t wd = kc[(kb + e) * WB + wl];
                 lo[e] = (uint32_t)wd;
                 hi[e] = (uint32_t)(wd >> 32);
             }
@@ -164,10 +225,10 @@ __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restric
             const v8bf s1 = __builtin_bit_cast(v8bf, make_uint4(a1[0], a1[1], a1[2], a1[3]));
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
-                const int off = (jt * 32 + m) * kChunkStride + kb;
+                const int off = (jt * 32 + m) * kTokStride + kb;
 #pragma unroll
                 for (int p = 0; p < 3; ++p) {
-                    const v8bf vp = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vt_s[p] + off));
+                    const v8bf vp = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(pl + p * PLANE + off));
                     acc[0][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s0, vp, acc[0][jt], 0, 0, 0);
                     acc[1][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(s1, vp, acc[1][jt], 0, 0, 0);
                 }
@@ -177,7 +238,7 @@ __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restric
 
     // token phases of one word meet in LDS, ascending phase order
     if (PH > 1) {
-        float *red = reinterpret_cast<float *>(&vt_s[0][0]);     // 2 * JT * 16 * 64 floats per word <= 32 KiB
+        float *red = reinterpret_cast<float *>(&vt_s[0][0]);     // 2 * JT * 16 * 64 floats per word
         for (int ph = 1; ph < PH; ++ph) {
             __syncthreads();
             if (active && phase == ph) {
@@ -215,9 +276,11 @@ __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restric
 }
 
 // --------------------------------------------------------------------------- Q (K^T V) ----
-// Workgroup: one (b, h) and a range of token tiles; 4 wavefronts, TM 32-token tiles each per pass.
+// Workgroup: one (b, h) and a range of token tiles; kQkvWaves wavefronts, TM 32-token tiles each per pass.
+constexpr int kQkvWaves = 8;
+
 template <int DV, int W, int TM>
-__global__ __launch_bounds__(256) void qkv_mfma_kernel(const uint64_t *__restrict__ q_codes, const float *__restrict__ kv,
+__global__ __launch_bounds__(kQkvWaves * 64) void qkv_mfma_kernel(const uint64_t *__restrict__ q_codes, const float *__restrict__ kv,
                                                        float *__restrict__ out, int H, int Nq, int blocks_per_bh,
                                                        int tiles_per_block, float scale) {
     constexpr int JT = DV / 32;
@@ -234,20 +297,20 @@ __global__ __launch_bounds__(256) void qkv_mfma_kernel(const uint64_t *__restric
     const int m = lane & 31, kg = lane >> 5;
 
     // byte -> its 8 bits as bf16 signs, element e = bit e
-    {
+    if (tid < 256) {
         uint32_t d[4];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) d[e2] = sign_pair((uint32_t)tid, (uint32_t)tid >> 1, 2 * e2);
         sign_s[tid] = make_uint4(d[0], d[1], d[2], d[3]);
     }
     stage_transposed<DV>(kv + (size_t)bh * NBITS * DV, (size_t)DV, NBITS, NBITS, kvt_s[0], kvt_s[1], kvt_s[2], STRIDE, tid,
-                         256);
+                         kQkvWaves * 64);
     __syncthreads();
 
     const int n_tiles = (Nq + 31) / 32;
     const int tile_begin = part * tiles_per_block;
     const int tile_end = min(n_tiles, tile_begin + tiles_per_block);
-    for (int tile0 = tile_begin + wave * TM; tile0 < tile_end; tile0 += 4 * TM) {
+    for (int tile0 = tile_begin + wave * TM; tile0 < tile_end; tile0 += kQkvWaves * TM) {
         uint32_t code[TM][2 * W];
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
@@ -288,6 +351,8 @@ __global__ __launch_bounds__(256) void qkv_mfma_kernel(const uint64_t *__restric
                         acc[tm][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], kp, acc[tm][jt], 0, 0, 0);
                 }
             }
+            // keep the steps apart: hoisting every operand read of the tile to the top costs hundreds of registers
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
@@ -307,16 +372,16 @@ __global__ __launch_bounds__(256) void qkv_mfma_kernel(const uint64_t *__restric
 
 template <int DV, int W>
 void launch_qkv_w(const uint64_t *q_codes, const float *kv, float *out, long BH, int H, int Nq, float scale, hipStream_t st) {
-    constexpr int TM = 2;
+    constexpr int TM = DV == 128 ? 1 : 2;       // accumulators: TM * DV / 32 tiles of 16 registers
     const int n_tiles = (Nq + 31) / 32;
-    // enough workgroups to fill the chip, but each stages all of K^T V once: several passes of its 4 wavefronts
+    // enough workgroups to fill the chip, but each stages all of K^T V once: several passes of its wavefronts
     long per_bh = (1024 + BH - 1) / BH;
     const int passes = (size_t)W * 64 * DV * 4 >= 32768 ? 4 : 1;      // a small K^T V is cheap to stage again
-    const long max_per_bh = (n_tiles + 4 * TM * passes - 1) / (4 * TM * passes);
+    const long max_per_bh = (n_tiles + kQkvWaves * TM * passes - 1) / (kQkvWaves * TM * passes);
     if (per_bh > max_per_bh) per_bh = max_per_bh;
     if (per_bh < 1) per_bh = 1;
     const int tiles_per_block = (int)((n_tiles + per_bh - 1) / per_bh);
-    qkv_mfma_kernel<DV, W, TM><<<dim3((unsigned)(BH * per_bh)), dim3(256), 0, st>>>(q_codes, kv, out, H, Nq, (int)per_bh,
+    qkv_mfma_kernel<DV, W, TM><<<dim3((unsigned)(BH * per_bh)), dim3(kQkvWaves * 64), 0, st>>>(q_codes, kv, out, H, Nq, (int)per_bh,
                                                                                      tiles_per_block, scale);
 }
 
@@ -357,13 +422,13 @@ AdditiveMfmaPlan plan_additive_mfma(int B, int H, int Nk, int nbits) {
     p.wb = W < 4 ? W : 4;
     p.ph = p.wb == 1 ? 4 : (p.wb == 2 ? 2 : 1);
     const long base = (long)B * H * p.groups;
-    long splits = (1024 + base - 1) / base;
-    const long chunks = ((long)Nk + kChunk - 1) / kChunk;
+    long splits = (768 + base - 1) / base;
+    const long chunks = ((long)Nk + kTok - 1) / kTok;
     if (splits > chunks) splits = chunks;
     if (splits < 1) splits = 1;
     if (splits > 256) splits = 256;
     const long chunks_per_block = (chunks + splits - 1) / splits;
-    p.tokens_per_block = (int)(chunks_per_block * kChunk);
+    p.tokens_per_block = (int)(chunks_per_block * kTok);
     p.splits = (int)((chunks + chunks_per_block - 1) / chunks_per_block);
     return p;
 }
