@@ -64,8 +64,9 @@ def kernel_table(cfg, p, counts):
     tab = []
     bin_bytes = rows * cfg.d * 4 + cfg.d * cfg.nbits * 4 + rows * cfg.nbits // 8
     bin_flop = 2 * rows * cfg.nbits * cfg.d
-    for name in ("binarize_q", "binarize_k"):
-        tab.append(dict(name=name, bytes=bin_bytes, ops=bin_flop, compute="mfma_bf16x3" if cfg.d in (32, 64, 128) else "alu_fp32"))
+    # Q and K are hashed by one launch
+    tab.append(dict(name="binarize_qk", bytes=2 * bin_bytes - cfg.d * cfg.nbits * 4, ops=2 * bin_flop,
+                    compute="mfma_bf16x3" if cfg.d in (32, 64, 128) else "alu_fp32"))
     code_b = rows * cfg.nbits // 8
     v_b = rows * cfg.dv * 4
     if cfg.attention == "linear":
@@ -256,8 +257,7 @@ def make_stages(sa, torch, cfg, kw, p, moe, variant):
     kc = torch.empty_like(qc)
     o = torch.empty((cfg.B, cfg.N, cfg.H, cfg.dv), dtype=torch.float32, device=d)
     lib = sa.load_library()
-    st = {"binarize_q": lambda: sa.sa_binarize(kw["q"], kw["proj"], cfg.nbits, codes=qc),
-          "binarize_k": lambda: sa.sa_binarize(kw["k"], kw["proj"], cfg.nbits, codes=kc)}
+    st = {"binarize_qk": lambda: sa.sa_binarize_pair(kw["q"], kw["k"], kw["proj"], cfg.nbits, q_codes=qc, k_codes=kc)}
     if cfg.attention == "linear":
         kv = torch.empty((cfg.B, cfg.H, cfg.nbits, cfg.dv), dtype=torch.float32, device=d)
         ws = torch.empty(max(16, lib.sa_additive_attention_workspace_bytes(cfg.B, cfg.H, cfg.N, cfg.nbits, cfg.dv)),

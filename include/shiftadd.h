@@ -74,6 +74,10 @@ int sa_binarize(const float *x, int B, int N, int H, int d, const float *proj, i
  *   SA_VARIANT_AUTO  what sa_binarize uses                                          */
 int sa_binarize_ex(const float *x, int B, int N, int H, int d, const float *proj, int nbits,
                    uint64_t *codes, int variant, void *stream);
+/* Q and K of one block: two tensors of the same shape through the same hash, in one launch
+ * where the matrix-core kernel takes the shape (otherwise the same as two sa_binarize calls). */
+int sa_binarize_pair(const float *q, const float *k, int B, int N, int H, int d, const float *proj,
+                     int nbits, uint64_t *q_codes, uint64_t *k_codes, void *stream);
 
 /*
  * Linear attention with both MatMuls as Add layers (Eq. 3, O_Add; Sec. 4.1,

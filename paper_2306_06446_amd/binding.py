@@ -18,7 +18,7 @@ _lib = None
 SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO, SA_VARIANT_MFMA_PREPARED = 0, 1, 2, 3
 
 EXPORTS = [
-    "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_additive_attention_workspace_bytes",
+    "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_binarize_pair", "sa_additive_attention_workspace_bytes",
     "sa_additive_attention", "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
@@ -121,6 +121,18 @@ def sa_binarize(x, proj, nbits, codes=None, variant=None):
     else:
         _check(lib.sa_binarize_ex(_ptr(x), B, N, H, d, _ptr(proj), nbits, _ptr(codes), variant, _stream()))
     return codes
+
+
+def sa_binarize_pair(q, k, proj, nbits, q_codes=None, k_codes=None):
+    """Q and K of one block through the same hash, one launch where the matrix-core kernel takes the shape."""
+    B, N, H, d = q.shape
+    if q_codes is None:
+        q_codes = torch.empty((B, H, N, nbits // 64), dtype=torch.int64, device=q.device)
+    if k_codes is None:
+        k_codes = torch.empty((B, H, N, nbits // 64), dtype=torch.int64, device=q.device)
+    _check(load_library().sa_binarize_pair(_ptr(q), _ptr(k), B, N, H, d, _ptr(proj), nbits, _ptr(q_codes),
+                                           _ptr(k_codes), _stream()))
+    return q_codes, k_codes
 
 
 def sa_additive_attention(q_codes, k_codes, v, scale, nbits, phases=3, kv=None, out=None,

@@ -71,6 +71,20 @@ extern "C" int sa_binarize(const float *x, int B, int N, int H, int d, const flo
     return sa_binarize_ex(x, B, N, H, d, proj, nbits, codes, SA_VARIANT_AUTO, stream);
 }
 
+extern "C" int sa_binarize_pair(const float *q, const float *k, int B, int N, int H, int d, const float *proj,
+                                int nbits, uint64_t *q_codes, uint64_t *k_codes, void *stream) {
+    sa::clear_error();
+    const long rows = (long)B * N * H;
+    // one launch when the matrix-core kernel takes the shape; otherwise simply one call per tensor
+    if (proj != nullptr && B > 0 && N > 0 && H > 0 && rows < (1L << 31) && sa::binarize_mfma_supported(d, nbits) &&
+        nbits <= 4096 && q && k && q_codes && k_codes && sa::aligned16(q) && sa::aligned16(k) && sa::aligned16(proj) &&
+        sa::aligned16(q_codes) && sa::aligned16(k_codes))
+        return sa::launch_binarize_mfma(q, k, proj, q_codes, k_codes, rows, N, H, d, nbits, sa::as_stream(stream));
+    const int rc = sa_binarize_ex(q, B, N, H, d, proj, nbits, q_codes, SA_VARIANT_AUTO, stream);
+    if (rc != SA_OK) return rc;
+    return sa_binarize_ex(k, B, N, H, d, proj, nbits, k_codes, SA_VARIANT_AUTO, stream);
+}
+
 extern "C" int sa_binarize_ex(const float *x, int B, int N, int H, int d, const float *proj,
                               int nbits, uint64_t *codes, int variant, void *stream) {
     sa::clear_error();
@@ -98,7 +112,7 @@ extern "C" int sa_binarize_ex(const float *x, int B, int N, int H, int d, const 
         return sa::check_launch("sa_binarize(sign)");
     }
     if (variant != SA_VARIANT_VALU && sa::binarize_mfma_supported(d, nbits))
-        return sa::launch_binarize_mfma(x, proj, codes, rows, N, H, d, nbits, st);
+        return sa::launch_binarize_mfma(x, nullptr, proj, codes, nullptr, rows, N, H, d, nbits, st);
     SA_REQUIRE(variant != SA_VARIANT_MFMA, SA_ERR_UNSUPPORTED,
                "sa_binarize: the matrix-core variant needs d in {32, 64, 128} (got %d)", d);
     const int n_chunks = (N + 63) / 64;

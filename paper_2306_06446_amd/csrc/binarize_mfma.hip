@@ -48,12 +48,21 @@ __device__ inline void split_bf16(float f, __bf16 &hi, __bf16 &lo) {
 
 // Re-runs the defining chain for one parked (row, bit) entry and flips the stored bit where the
 // pre-pass had it wrong.
+// Up to two tensors of the same shape are hashed by one launch (Q and K of a block).
+struct Tensors {
+    const float *x0, *x1;
+    uint64_t *codes0, *codes1;
+};
+
 template <int D>
-__device__ inline void settle_entry(uint64_t e, const float *__restrict__ x, const float *__restrict__ proj,
-                                    uint64_t *codes, const RowMap &map, int nbits) {
+__device__ inline void settle_entry(uint64_t e, const Tensors &ts, const float *__restrict__ proj, const RowMap &map,
+                                    int nbits) {
     const long row = (long)(e & 0xffffffffu);
     const int col = (int)((e >> 32) & 0xffffu);
     const bool prov = (e >> 48) & 1u;
+    const bool second = (e >> 49) & 1u;
+    const float *x = second ? ts.x1 : ts.x0;
+    uint64_t *codes = second ? ts.codes1 : ts.codes0;
     const float *xr = x + (size_t)row * D;
     const float *pc = proj + col;
     float acc = 0.0f;
@@ -79,20 +88,18 @@ __device__ inline void settle_entry(uint64_t e, const float *__restrict__ x, con
 // One wavefront's list, worked off 64 entries at a time.  Kept out of line: inside the tile loop it is
 // the rare path (degenerate data) and must not cost the loop its registers.
 template <int D>
-__device__ __attribute__((noinline)) void work_off_list(const uint64_t *list, int cnt, const float *__restrict__ x,
-                                                        const float *__restrict__ proj, uint64_t *codes,
-                                                        RowMap map, int nbits) {
+__device__ __attribute__((noinline)) void work_off_list(const uint64_t *list, int cnt, Tensors ts,
+                                                        const float *__restrict__ proj, RowMap map, int nbits) {
     const int lane = threadIdx.x & 63;
     __builtin_amdgcn_s_waitcnt(0x0F70);      // the words these bits live in have been stored
     for (int t0 = 0; t0 < cnt; t0 += 64)
-        if (t0 + lane < cnt) settle_entry<D>(list[t0 + lane], x, proj, codes, map, nbits);
+        if (t0 + lane < cnt) settle_entry<D>(list[t0 + lane], ts, proj, map, nbits);
 }
 
 // D: head dim; G: hash columns handled by one workgroup (blockIdx.y selects the group).
 template <int D, int G>
-__global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__restrict__ x,
-                                                               const float *__restrict__ proj, uint64_t *codes,
-                                                               long rows, RowMap map, int nbits, long n_tiles) {
+__global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const float *__restrict__ proj, long rows,
+                                                               RowMap map, int nbits, long n_tiles, long n_total) {
     constexpr int S = D / 16;      // MFMA steps along k
     constexpr int JT = G / 32;     // 32-bit groups of hash columns
     constexpr int HALF = D / 2;    // k values one lane owns (the other half-wavefront owns the rest)
@@ -156,9 +163,11 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
     uint64_t *list = list_s[wave];
 
     // the next tile's rows are in flight while the current tile is multiplied and packed
+    // tiles 0 .. n_tiles-1 belong to the first tensor, the next n_tiles to the second
     auto load_tile = [&](long tile, float (&dst)[HALF]) {
-        const long row_ld = min(tile * 32 + i_loc, rows - 1);
-        const float *xr = x + (size_t)row_ld * D + g * HALF;
+        const bool second = tile >= n_tiles;
+        const long row_ld = min((second ? tile - n_tiles : tile) * 32 + i_loc, rows - 1);
+        const float *xr = (second ? ts.x1 : ts.x0) + (size_t)row_ld * D + g * HALF;
 #pragma unroll
         for (int q = 0; q < HALF / 4; ++q) {
             const float4 t4 = *reinterpret_cast<const float4 *>(xr + 4 * q);
@@ -169,14 +178,16 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
     float xn[HALF];
     {
         const long first = (long)blockIdx.x * 4 + wave;
-        if (first < n_tiles) load_tile(first, xn);
+        if (first < n_total) load_tile(first, xn);
     }
-    for (long tile = (long)blockIdx.x * 4 + wave; tile < n_tiles; tile += tile_step) {
-        const long r0 = tile * 32;
+    for (long tile = (long)blockIdx.x * 4 + wave; tile < n_total; tile += tile_step) {
+        const bool second = tile >= n_tiles;
+        const long r0 = (second ? tile - n_tiles : tile) * 32;
+        uint64_t *codes = second ? ts.codes1 : ts.codes0;
         float xv[HALF];
 #pragma unroll
         for (int k = 0; k < HALF; ++k) xv[k] = xn[k];
-        if (tile + tile_step < n_tiles) load_tile(tile + tile_step, xn);
+        if (tile + tile_step < n_total) load_tile(tile + tile_step, xn);
         float nx2 = 0.0f;
 #pragma unroll
         for (int k = 0; k < HALF; ++k) nx2 += xv[k] * xv[k];
@@ -270,7 +281,7 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
             const int pos = parked ? __builtin_ctz(mine) : 0;
             const uint64_t pm = __ballot(parked);
             if (cnt + 64 > kListCap) {
-                work_off_list<D>(list, cnt, x, proj, codes, map, nbits);
+                work_off_list<D>(list, cnt, ts, proj, map, nbits);
                 cnt = 0;
             }
             if (parked) {
@@ -280,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
 #pragma unroll
                 for (int t = 0; t < JT; ++t) b = (t == jt) ? bits[t] : b;
                 list[slot] = (uint64_t)(uint32_t)(r0 + i_loc) | ((uint64_t)(c0 + jt * 32 + pos) << 32) |
-                             ((uint64_t)((b >> pos) & 1u) << 48);
+                             ((uint64_t)((b >> pos) & 1u) << 48) | ((uint64_t)second << 49);
                 const uint32_t cleared = mine & (mine - 1u);
 #pragma unroll
                 for (int t = 0; t < JT; ++t) park[t] = (t == jt) ? cleared : park[t];
@@ -304,7 +315,7 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(const float *__re
             if (t < n3) {
                 const int w = (t >= n0) + (t >= n1) + (t >= n2);
                 const int base = w == 0 ? 0 : (w == 1 ? n0 : (w == 2 ? n1 : n2));
-                settle_entry<D>(list_s[w][t - base], x, proj, codes, map, nbits);
+                settle_entry<D>(list_s[w][t - base], ts, proj, map, nbits);
             }
         }
     }
@@ -317,31 +328,34 @@ bool binarize_mfma_supported(int d, int nbits) {
 }
 
 template <int D, int G>
-int launch_one(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int nbits,
-               hipStream_t st) {
+int launch_one(const Tensors &ts, int count, const float *proj, long rows, int N, int H, int nbits, hipStream_t st) {
     const long n_tiles = (rows + 31) / 32;
+    const long n_total = n_tiles * count;
     // about two workgroups of 4 wavefronts per CU (what the registers allow), every wavefront the
     // same number of tiles
-    const long tiles_per_wave = (n_tiles + 4 * 512 - 1) / (4 * 512);
-    const long blocks = (n_tiles + 4 * tiles_per_wave - 1) / (4 * tiles_per_wave);
+    const long tiles_per_wave = (n_total + 4 * 512 - 1) / (4 * 512);
+    const long blocks = (n_total + 4 * tiles_per_wave - 1) / (4 * tiles_per_wave);
     const dim3 grid((unsigned)blocks, (unsigned)(nbits / G));
     RowMap map{N, H, nbits / 64};
-    binarize_mfma_kernel<D, G><<<grid, dim3(256), 0, st>>>(x, proj, codes, rows, map, nbits, n_tiles);
+    binarize_mfma_kernel<D, G><<<grid, dim3(256), 0, st>>>(ts, proj, rows, map, nbits, n_tiles, n_total);
     return check_launch("sa_binarize(mfma)");
 }
 
-int launch_binarize_mfma(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int d,
-                         int nbits, hipStream_t st) {
+// x1 / codes1 may be null: one tensor.
+int launch_binarize_mfma(const float *x0, const float *x1, const float *proj, uint64_t *codes0, uint64_t *codes1,
+                         long rows, int N, int H, int d, int nbits, hipStream_t st) {
+    const Tensors ts{x0, x1, codes0, codes1};
+    const int count = x1 ? 2 : 1;
     const bool g128 = (nbits % 128 == 0);
     switch (d) {
         case 32:
-            return g128 ? launch_one<32, 128>(x, proj, codes, rows, N, H, nbits, st)
-                        : launch_one<32, 64>(x, proj, codes, rows, N, H, nbits, st);
+            return g128 ? launch_one<32, 128>(ts, count, proj, rows, N, H, nbits, st)
+                        : launch_one<32, 64>(ts, count, proj, rows, N, H, nbits, st);
         case 64:
-            return g128 ? launch_one<64, 128>(x, proj, codes, rows, N, H, nbits, st)
-                        : launch_one<64, 64>(x, proj, codes, rows, N, H, nbits, st);
+            return g128 ? launch_one<64, 128>(ts, count, proj, rows, N, H, nbits, st)
+                        : launch_one<64, 64>(ts, count, proj, rows, N, H, nbits, st);
         default:
-            return launch_one<128, 64>(x, proj, codes, rows, N, H, nbits, st);
+            return launch_one<128, 64>(ts, count, proj, rows, N, H, nbits, st);
     }
 }
 

@@ -149,9 +149,7 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
         SA_HIP(hipEventRecord(lane->routed, lane->stream));
     }
 
-    rc = sa_binarize(d->q, d->B, d->N, d->H, d->d, d->proj, d->nbits, qc, stream);
-    if (rc != SA_OK) return rc;
-    rc = sa_binarize(d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, kc, stream);
+    rc = sa_binarize_pair(d->q, d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, qc, kc, stream);
     if (rc != SA_OK) return rc;
     // The attention output leaves in three forms: fp32 (the block's output o), the int8 codes the
     // Shift layers read, and (with a Mult expert) the fp16 rounding its first layer reads.  The

@@ -50,8 +50,8 @@ int validate_rows(const sa_rows *rows, RowSel *out);
 
 // Hash pre-pass on the matrix cores with exact fallback (binarize_mfma.hip).
 bool binarize_mfma_supported(int d, int nbits);
-int launch_binarize_mfma(const float *x, const float *proj, uint64_t *codes, long rows, int N, int H, int d,
-                         int nbits, hipStream_t st);
+int launch_binarize_mfma(const float *x0, const float *x1_or_null, const float *proj, uint64_t *codes0,
+                         uint64_t *codes1_or_null, long rows, int N, int H, int d, int nbits, hipStream_t st);
 
 // Additive attention on the matrix cores (additive_mfma.hip).
 struct AdditiveMfmaPlan {

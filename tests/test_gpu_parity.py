@@ -94,6 +94,28 @@ def test_binarize_sign_mode_bit_exact(sa):
     assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("B,N,H,d,nbits", [(2, 197, 12, 64, 128), (1, 300, 4, 64, 256), (2, 130, 1, 32, 64)])
+def test_binarize_pair_bit_exact(sa, B, N, H, d, nbits):
+    """Two tensors in one launch."""
+    g = np.random.default_rng([12, B, N, H, d, nbits])
+    q = g.standard_normal((B, N, H, d), dtype=np.float32)
+    k = g.standard_normal((B, N, H, d), dtype=np.float32)
+    k[0, 0, 0, :] = 0.0                                     # a parked row in the second tensor
+    pr = g.standard_normal((d, nbits), dtype=np.float32)
+    qc, kc = sa.sa_binarize_pair(dev(q), dev(k), dev(pr), nbits)
+    assert np.array_equal(codes_host(qc), oracle.binarize(q, pr, nbits))
+    assert np.array_equal(codes_host(kc), oracle.binarize(k, pr, nbits))
+
+
+def test_binarize_pair_without_projection_is_two_sign_hashes(sa):
+    g = np.random.default_rng(13)
+    q = g.standard_normal((2, 70, 3, 64), dtype=np.float32)
+    k = g.standard_normal((2, 70, 3, 64), dtype=np.float32)
+    qc, kc = sa.sa_binarize_pair(dev(q), dev(k), None, 64)
+    assert np.array_equal(codes_host(qc), oracle.binarize(q, None, 64))
+    assert np.array_equal(codes_host(kc), oracle.binarize(k, None, 64))
+
+
 # -------------------------------------------------------- additive attention ----
 
 @pytest.mark.parametrize("valu", [0, 4], ids=["mfma", "valu"])
