@@ -97,20 +97,21 @@ __device__ __attribute__((noinline)) void work_off_list(const uint64_t *list, in
 }
 
 // D: head dim; G: hash columns handled by one workgroup (blockIdx.y selects the group).
-template <int D, int G>
+template <int D, int G, int CG>
 __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const float *__restrict__ proj, long rows,
                                                                RowMap map, int nbits, long n_tiles, long n_total) {
     constexpr int S = D / 16;      // MFMA steps along k
     constexpr int JT = G / 32;     // 32-bit groups of hash columns
     constexpr int HALF = D / 2;    // k values one lane owns (the other half-wavefront owns the rest)
-    __shared__ __attribute__((aligned(16))) uint4 bfr_s[S * JT * 2 * 64];
+    constexpr int FRAGS = S * JT * 2 * 64;      // fragments of one group of G columns
+    __shared__ __attribute__((aligned(16))) uint4 bfr_s[CG * FRAGS];
     __shared__ uint64_t list_s[4][kListCap];
     __shared__ int cnt_s[4];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i_loc = lane & 31, g = lane >> 5;
-    const int c0 = blockIdx.y * G;
+    const int c_first = blockIdx.y * (G * CG);  // this workgroup hashes CG groups of G columns from here
 
     // ---- hash matrix -> normalised bf16 fragments in LDS: fragment (s, jt, hi/lo), lane L holds
     //      r^[k = (L/32)*HALF + s*8 + e][c0 + jt*32 + L%32], e = 0..7.
@@ -121,7 +122,9 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
     constexpr int STEPS = KPT / 8;         // fragments (per hi / lo) per thread
     static_assert(KPT % 8 == 0 && HALF % KPT == 0, "a thread's k slice must lie inside one half");
     __shared__ float cn2_s[TPC][G];
-    {
+#pragma unroll 1
+    for (int cg = 0; cg < CG; ++cg) {
+        const int c0 = c_first + cg * G;
         const int c = tid % G, qs = tid / G;
         const int k_first = qs * KPT;
         const int fg = k_first / HALF, s_first = (k_first % HALF) / 8;
@@ -132,6 +135,7 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
         float s2 = 0.0f;
 #pragma unroll
         for (int k = 0; k < KPT; ++k) s2 += rv[k] * rv[k];
+        __syncthreads();                         // the previous group's sums have been read
         cn2_s[qs][c] = s2;
         __syncthreads();
         float n2 = 0.0f;
@@ -153,8 +157,8 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
                 vl[e] = lo;
             }
             const int s = s_first + st;
-            bfr_s[((s * JT + jt) * 2 + 0) * 64 + L] = __builtin_bit_cast(uint4, vh);
-            bfr_s[((s * JT + jt) * 2 + 1) * 64 + L] = __builtin_bit_cast(uint4, vl);
+            bfr_s[cg * FRAGS + ((s * JT + jt) * 2 + 0) * 64 + L] = __builtin_bit_cast(uint4, vh);
+            bfr_s[cg * FRAGS + ((s * JT + jt) * 2 + 1) * 64 + L] = __builtin_bit_cast(uint4, vl);
         }
     }
     __syncthreads();
@@ -196,6 +200,23 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
         const float keep = nx2 < __builtin_inff() ? __builtin_sqrtf(__builtin_fmaxf(kKeepFactor * nx2, kKeepFloor))
                                                   : __builtin_inff();
 
+        // the two bf16 terms of the row, once for all column groups
+        v8bf xh[S], xl[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                __bf16 hi, lo;
+                split_bf16(xv[s * 8 + e], hi, lo);
+                xh[s][e] = hi;
+                xl[s][e] = lo;
+            }
+        const bool row_ok = (r0 + i_loc) < rows;
+
+#pragma unroll 1
+        for (int cg = 0; cg < CG; ++cg) {
+        const int c0 = c_first + cg * G;
+        const uint4 *frag = bfr_s + cg * FRAGS;
         // z~^T: accumulator (jt, r) of lane (i_loc, g) = hash bit jt*32 + 8*(r/4) + 4*g + r%4 of row i_loc
         v16f acc[JT];
 #pragma unroll
@@ -204,21 +225,13 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
             for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            v8bf xh, xl;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                __bf16 hi, lo;
-                split_bf16(xv[s * 8 + e], hi, lo);
-                xh[e] = hi;
-                xl[e] = lo;
-            }
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
-                const v8bf rh = __builtin_bit_cast(v8bf, bfr_s[((s * JT + jt) * 2 + 0) * 64 + lane]);
-                const v8bf rl = __builtin_bit_cast(v8bf, bfr_s[((s * JT + jt) * 2 + 1) * 64 + lane]);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xh, acc[jt], 0, 0, 0);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl, xh, acc[jt], 0, 0, 0);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xl, acc[jt], 0, 0, 0);
+                const v8bf rh = __builtin_bit_cast(v8bf, frag[((s * JT + jt) * 2 + 0) * 64 + lane]);
+                const v8bf rl = __builtin_bit_cast(v8bf, frag[((s * JT + jt) * 2 + 1) * 64 + lane]);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xh[s], acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl, xh[s], acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xl[s], acc[jt], 0, 0, 0);
             }
             // keep the steps apart: hoisting every fragment read of the tile to the top costs
             // 128 registers and one wavefront of occupancy
@@ -229,7 +242,6 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
         // accumulator register, per 32-bit group.  Signs: 16 funnel shifts collect the sign bits, then
         // the four nibbles move to their byte.  Margin: the smallest |z~| of the 16 decides for all of
         // them at once (99.7 % of the groups); only a group with a doubtful element is tested one by one.
-        const bool row_ok = (r0 + i_loc) < rows;
         uint32_t bits[JT], park[JT];
         uint32_t any_park = 0;
 #pragma unroll
@@ -301,6 +313,7 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
             }
             cnt += __builtin_popcountll(pm);
         }
+        }   // column groups
     }
 
     // The four wavefronts' leftovers are worked off together by wavefront 0: the cost of a pass is
@@ -327,7 +340,7 @@ bool binarize_mfma_supported(int d, int nbits) {
     return (d == 32 || d == 64 || d == 128) && nbits % 64 == 0;
 }
 
-template <int D, int G>
+template <int D, int G, int CG>
 int launch_one(const Tensors &ts, int count, const float *proj, long rows, int N, int H, int nbits, hipStream_t st) {
     const long n_tiles = (rows + 31) / 32;
     const long n_total = n_tiles * count;
@@ -335,27 +348,32 @@ int launch_one(const Tensors &ts, int count, const float *proj, long rows, int N
     // same number of tiles
     const long tiles_per_wave = (n_total + 4 * 512 - 1) / (4 * 512);
     const long blocks = (n_total + 4 * tiles_per_wave - 1) / (4 * tiles_per_wave);
-    const dim3 grid((unsigned)blocks, (unsigned)(nbits / G));
+    const dim3 grid((unsigned)blocks, (unsigned)(nbits / (G * CG)));
     RowMap map{N, H, nbits / 64};
-    binarize_mfma_kernel<D, G><<<grid, dim3(256), 0, st>>>(ts, proj, rows, map, nbits, n_tiles, n_total);
+    binarize_mfma_kernel<D, G, CG><<<grid, dim3(256), 0, st>>>(ts, proj, rows, map, nbits, n_tiles, n_total);
     return check_launch("sa_binarize(mfma)");
 }
 
-// x1 / codes1 may be null: one tensor.
+// x1 / codes1 may be null: one tensor.  Column groups: 128 columns per pass of the matrix cores (64
+// for d = 128 or when nbits is not a multiple of 128); when nbits is a multiple of 256 a workgroup
+// takes two groups per row tile, so the rows are read and split once for both.
 int launch_binarize_mfma(const float *x0, const float *x1, const float *proj, uint64_t *codes0, uint64_t *codes1,
                          long rows, int N, int H, int d, int nbits, hipStream_t st) {
     const Tensors ts{x0, x1, codes0, codes1};
     const int count = x1 ? 2 : 1;
-    const bool g128 = (nbits % 128 == 0);
+    const bool g128 = (nbits % 128 == 0), two = (nbits % 256 == 0);
     switch (d) {
         case 32:
-            return g128 ? launch_one<32, 128>(ts, count, proj, rows, N, H, nbits, st)
-                        : launch_one<32, 64>(ts, count, proj, rows, N, H, nbits, st);
+            return two    ? launch_one<32, 128, 2>(ts, count, proj, rows, N, H, nbits, st)
+                   : g128 ? launch_one<32, 128, 1>(ts, count, proj, rows, N, H, nbits, st)
+                          : launch_one<32, 64, 1>(ts, count, proj, rows, N, H, nbits, st);
         case 64:
-            return g128 ? launch_one<64, 128>(ts, count, proj, rows, N, H, nbits, st)
-                        : launch_one<64, 64>(ts, count, proj, rows, N, H, nbits, st);
+            return two    ? launch_one<64, 128, 2>(ts, count, proj, rows, N, H, nbits, st)
+                   : g128 ? launch_one<64, 128, 1>(ts, count, proj, rows, N, H, nbits, st)
+                          : launch_one<64, 64, 1>(ts, count, proj, rows, N, H, nbits, st);
         default:
-            return launch_one<128, 64>(ts, count, proj, rows, N, H, nbits, st);
+            return g128 ? launch_one<128, 64, 2>(ts, count, proj, rows, N, H, nbits, st)
+                        : launch_one<128, 64, 1>(ts, count, proj, rows, N, H, nbits, st);
     }
 }
 
