@@ -112,11 +112,15 @@ int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const
 /* The same, with the attention output also written in the two forms the MLP of the block
  * reads (Eq. 2 feeds the attention output to the MLP): xq_or_null int8 [B*Nq, H*dv], the
  * codes sa_quantize_act(out, act_inv_scale) would give, and xh_or_null fp16 [B*Nq, H*dv],
- * out rounded to nearest.  Either may be NULL. */
+ * out rounded to nearest.  Either may be NULL.
+ * variant: SA_VARIANT_VALU computes the scores by XOR + popcount on the vector ALU;
+ * SA_VARIANT_MFMA as the dot product of the +-1 sign vectors on the matrix cores (the same
+ * integers, nbits <= 256); SA_VARIANT_AUTO (what sa_hamming_attention uses) takes the
+ * faster one, which at the measured shapes is the popcount. */
 int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
                                float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
                                float scale, int16_t *scores_or_null, int8_t *xq_or_null,
-                               void *xh_or_null, float act_inv_scale, void *stream);
+                               void *xh_or_null, float act_inv_scale, int variant, void *stream);
 
 /*
  * Shift layer (Eq. 3, O_Shift = sum X * s * 2^P) on int8 activations with

@@ -167,7 +167,7 @@ def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, o
 
 
 def sa_hamming_attention_fused(q_codes, k_codes, v, scale, nbits, act_inv_scale, out=None, xq=None, xh=None,
-                               want_xq=True, want_xh=True):
+                               want_xq=True, want_xh=True, variant=SA_VARIANT_AUTO):
     """Hamming attention that also leaves its output as int8 codes (xq) and in fp16 (xh), both [B*Nq, H*dv]."""
     B, H, Nq, W = q_codes.shape
     Nk = k_codes.shape[2]
@@ -181,7 +181,7 @@ def sa_hamming_attention_fused(q_codes, k_codes, v, scale, nbits, act_inv_scale,
         xh = torch.empty((B * Nq, H * dv), dtype=torch.float16, device=dev)
     _check(load_library().sa_hamming_attention_fused(_ptr(q_codes), _ptr(k_codes), _ptr(v), _ptr(out), B, H, Nq, Nk,
                                                      nbits, dv, _f(scale), _ptr(None), _ptr(xq), _ptr(xh),
-                                                     _f(act_inv_scale), _stream()))
+                                                     _f(act_inv_scale), variant, _stream()))
     return out, xq, xh
 
 

@@ -163,7 +163,7 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
         if (rc == SA_OK && mlp) rc = sa_quantize_act_half(d->o, T * E, d->act_inv_scale, xq, xh, stream);
     } else {
         rc = sa_hamming_attention_fused(qc, kc, d->v, d->o, d->B, d->H, d->N, d->N, d->nbits, d->dv, d->attn_scale,
-                                         nullptr, mlp ? xq : nullptr, xh, d->act_inv_scale, stream);
+                                         nullptr, mlp ? xq : nullptr, xh, d->act_inv_scale, SA_VARIANT_AUTO, stream);
     }
     if (rc != SA_OK || !mlp) return rc;
 

@@ -84,10 +84,70 @@ __device__ inline void transpose_in_quad(float (&x)[4], int q4) {
     }
 }
 
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+
+// The two bf16 terms of a pair of values, as the dwords the transposed planes store: upper terms
+// (a in the lower half, b in the upper half) and lower terms.  One v_cvt_pk_bf16_f32 per plane.
+__device__ inline void split_bf16_pair(float a, float b, uint32_t &upper, uint32_t &lower) {
+    v2f r = {a, b};
+    upper = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2bf));
+    r[0] -= __builtin_bit_cast(float, upper << 16);
+    r[1] -= __builtin_bit_cast(float, upper & 0xFFFF0000u);
+    lower = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2bf));
+}
+
 struct TableEntry {
     uint32_t hl;      // bf16 terms of p: (hi << 16) | lo
     float p;
 };
+
+// Row sums meet, then every output form leaves in whole 16- / 8- / 4-byte pieces of a row.
+template <int DV>
+__device__ inline void write_outputs(v16f (&acc)[DV / 32], float den, float *den_s, float *__restrict__ out,
+                                     int8_t *__restrict__ xq, _Float16 *__restrict__ xh, float act_inv_scale, int b,
+                                     int h, int H, int Nq, int chunk, int wave, int lane) {
+    constexpr int JT = DV / 32;
+    const int i_loc = lane & 31, kg = lane >> 5;
+    // row sums: the two half-wavefronts hold different keys of the same 32 queries
+    den += __shfl_xor(den, 32);
+    if (lane < 32) den_s[wave * 32 + lane] = den;
+    __syncthreads();
+    // A lane holds one column of four consecutive rows per register quartet; after a 4 x 4
+    // transpose inside each quad of lanes it holds four consecutive columns of one row, and every
+    // output form leaves in whole 16- / 8- / 4-byte pieces of a row.
+    const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
+    const int q4 = lane & 3;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int row = 8 * g + 4 * kg + q4;                  // the row this lane holds after the transpose
+        const int qo = q_tile0 + row;
+        const float inv = 1.0f / den_s[wave * 32 + row];
+        const size_t at = (((size_t)b * Nq + min(qo, Nq - 1)) * H + h) * DV + (i_loc & ~3);
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) {
+            float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
+            transpose_in_quad(x, q4);
+            if (qo < Nq) {
+                const float4 val = make_float4(x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv);
+                *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
+                // what the MLP reads: the int8 codes of the activation quantiser, and the fp16 rounding
+                if (xq) {
+                    const uint32_t c0 = (uint8_t)sa::requant_code(val.x * act_inv_scale);
+                    const uint32_t c1 = (uint8_t)sa::requant_code(val.y * act_inv_scale);
+                    const uint32_t c2b = (uint8_t)sa::requant_code(val.z * act_inv_scale);
+                    const uint32_t c3 = (uint8_t)sa::requant_code(val.w * act_inv_scale);
+                    *reinterpret_cast<uint32_t *>(xq + at + jt * 32) = c0 | (c1 << 8) | (c2b << 16) | (c3 << 24);
+                }
+                if (xh) {
+                    v4h hv;
+                    hv[0] = (_Float16)val.x; hv[1] = (_Float16)val.y; hv[2] = (_Float16)val.z; hv[3] = (_Float16)val.w;
+                    *reinterpret_cast<v4h *>(xh + at + jt * 32) = hv;
+                }
+            }
+        }
+    }
+}
 
 template <int DV, int W, bool ROWREF>
 __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
@@ -215,10 +275,11 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
                 const float a0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, a1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const uint32_t s0 = split_bf16(a0[c]), s1 = split_bf16(a1[c]);
+                    uint32_t up, lo;
+                    split_bf16_pair(a0[c], a1[c], up, lo);
                     const int off = (c4 * 4 + c) * kVtStride + j;      // even: 4-byte aligned
-                    *reinterpret_cast<uint32_t *>(vth_s + off) = __builtin_amdgcn_perm(s1, s0, 0x07060302u);
-                    *reinterpret_cast<uint32_t *>(vtl_s + off) = __builtin_amdgcn_perm(s1, s0, 0x05040100u);
+                    *reinterpret_cast<uint32_t *>(vth_s + off) = up;
+                    *reinterpret_cast<uint32_t *>(vtl_s + off) = lo;
                 }
             }
         }
@@ -228,44 +289,206 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
         if (n_full < n) step(n_full, n, std::true_type{});
     }
 
-    // row sums: the two half-wavefronts hold different keys of the same 32 queries
-    den += __shfl_xor(den, 32);
-    if (lane < 32) den_s[wave * 32 + lane] = den;
-    __syncthreads();
-    // A lane holds one column of four consecutive rows per register quartet; after a 4 x 4
-    // transpose inside each quad of lanes it holds four consecutive columns of one row, and every
-    // output form leaves in whole 16- / 8- / 4-byte pieces of a row.
-    const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
-    const int q4 = lane & 3;
+    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane);
+}
+
+// ---- the same attention with the scores on the matrix cores as well ------------------------------
+// For +-1 codes the Hamming similarity nbits - 2 popcount(q xor k) IS the dot product of the two
+// sign vectors, an exact small integer in fp32: v_mfma_f32_32x32x16_bf16 on the codes expanded to
+// +-1.0 gives a 32-key x 32-query tile of scores for 8 (nbits = 128) MFMAs, against ~9 vector
+// operations per pair for XOR + popcount.  The tile is computed transposed (keys down, queries
+// across), so that a lane ends up with 16 scores of ITS query; their table entries are the A operand
+// of the P * V products as they stand (the k index of an MFMA may be any fixed permutation of the
+// keys as long as the V operand uses the same one: here element e of step t is key
+// 16 t + 8 (e / 4) + 4 (lane / 32) + e % 4 of the tile).
+template <int DV, int W, bool ROWREF>
+__global__ __launch_bounds__(kMaxWaves *kWave, (DV <= 64 && W <= 2) ? 4 : 2) void hamming_mm_kernel(
+    const uint64_t *__restrict__ q_codes, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
+    float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2, int8_t *__restrict__ xq,
+    _Float16 *__restrict__ xh, float act_inv_scale) {
+    constexpr int JT = DV / 32;
+    constexpr int NBITS = W * 64;
+    constexpr int KS = NBITS / 16;                 // MFMA steps of a score tile
+    constexpr int kVtStride8 = kKeyChunk + 4;     // 264-byte V^T rows: the 8-byte operand reads of 32 columns cover the 64 banks once
+    constexpr int KSTRIDE = NBITS + 8;             // bf16 elements per key row of signs (16-byte multiple, conflict-free)
+    __shared__ __attribute__((aligned(16))) uint16_t ksign_s[kKeyChunk * KSTRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t vth_s[DV * kVtStride8];   // V^T, upper bf16 term
+    __shared__ __attribute__((aligned(16))) uint16_t vtl_s[DV * kVtStride8];   // V^T, lower bf16 term
+    __shared__ __attribute__((aligned(8))) TableEntry tab_s[NBITS + 1];
+    __shared__ __attribute__((aligned(16))) uint4 sign_s[256];
+    __shared__ float den_s[kMaxWaves * 32];
+    static_assert(sizeof(ksign_s) >= kKeyChunk * W * 8, "the first pass keeps the raw key codes there");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_threads = blockDim.x;
+    const long bh = blockIdx.x / q_chunks;
+    const int chunk = blockIdx.x % q_chunks;
+    const int b = (int)(bh / H), h = (int)(bh % H);
+    const int i_loc = lane & 31, kg = lane >> 5;
+    const int qi = chunk * (kMaxWaves * 32) + wave * 32 + i_loc;      // this lane's query
+    const int qi_ld = min(qi, Nq - 1);
+
+    uint64_t q[W];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int row = 8 * g + 4 * kg + q4;                  // the row this lane holds after the transpose
-        const int qo = q_tile0 + row;
-        const float inv = 1.0f / den_s[wave * 32 + row];
-        const size_t at = (((size_t)b * Nq + min(qo, Nq - 1)) * H + h) * DV + (i_loc & ~3);
+    for (int w = 0; w < W; ++w) q[w] = q_codes[((size_t)bh * Nq + qi_ld) * W + w];
+    const uint64_t *kc_g = k_codes + (size_t)bh * Nk * W;
+
+    // byte -> its 8 bits as bf16 signs (element e = bit e); numerators by t = |dist - dist_ref|
+    for (int t = tid; t < 256; t += n_threads) {
+        uint32_t d[4];
 #pragma unroll
-        for (int jt = 0; jt < JT; ++jt) {
-            float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
-            transpose_in_quad(x, q4);
-            if (qo < Nq) {
-                const float4 val = make_float4(x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv);
-                *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
-                // what the MLP reads: the int8 codes of the activation quantiser, and the fp16 rounding
-                if (xq) {
-                    const uint32_t c0 = (uint8_t)sa::requant_code(val.x * act_inv_scale);
-                    const uint32_t c1 = (uint8_t)sa::requant_code(val.y * act_inv_scale);
-                    const uint32_t c2b = (uint8_t)sa::requant_code(val.z * act_inv_scale);
-                    const uint32_t c3 = (uint8_t)sa::requant_code(val.w * act_inv_scale);
-                    *reinterpret_cast<uint32_t *>(xq + at + jt * 32) = c0 | (c1 << 8) | (c2b << 16) | (c3 << 24);
-                }
-                if (xh) {
-                    v4h hv;
-                    hv[0] = (_Float16)val.x; hv[1] = (_Float16)val.y; hv[2] = (_Float16)val.z; hv[3] = (_Float16)val.w;
-                    *reinterpret_cast<v4h *>(xh + at + jt * 32) = hv;
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t nl = ((uint32_t)~t >> (2 * e2)) & 1u, nh = ((uint32_t)~t >> (2 * e2 + 1)) & 1u;
+            d[e2] = 0x3F803F80u | (nl << 15) | (nh << 31);
+        }
+        sign_s[t] = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+    const float c2n = c2 <= 0.0f ? c2 : -c2;
+    for (int t = tid; t <= NBITS; t += n_threads) {
+        const float pt = __builtin_amdgcn_exp2f(c2n * (float)t);
+        tab_s[t].hl = split_bf16(pt);
+        tab_s[t].p = pt;
+    }
+
+    int dref = 0;
+    if (ROWREF) {
+        // the distance whose score scale*S is largest: the smallest if scale >= 0 (c2 <= 0)
+        uint64_t *kc_s = reinterpret_cast<uint64_t *>(ksign_s);
+        int dmin = 1 << 30, dmax = -1;
+        for (int j0 = 0; j0 < Nk; j0 += kKeyChunk) {
+            const int n = min(kKeyChunk, Nk - j0);
+            __syncthreads();
+            for (int t = tid; t < n * W; t += n_threads) kc_s[t] = kc_g[(size_t)j0 * W + t];
+            __syncthreads();
+            for (int j = 0; j < n; ++j) {
+                const int dist = distance<W>(q, kc_s + j * W);
+                dmin = min(dmin, dist);
+                dmax = max(dmax, dist);
+            }
+        }
+        dref = (c2 <= 0.0f) ? dmin : dmax;
+    }
+    __syncthreads();                               // the sign table is there (and the first pass is over)
+
+    // this lane's query as the B operand of the score tiles: bits 16 ks + 8 kg .. + 7 per step
+    v8bf qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const uint64_t wd = q[ks / 4];
+        const uint32_t half = (ks & 2) ? (uint32_t)(wd >> 32) : (uint32_t)wd;
+        qf[ks] = __builtin_bit_cast(v8bf, sign_s[__builtin_amdgcn_ubfe(half, 16 * (ks & 1) + 8 * kg, 8)]);
+    }
+    // byte offset into the table from a score S: 8 t, t = |dist - dref|, dist = (NBITS - S) / 2
+    const float off_slope = (c2 <= 0.0f) ? -4.0f : 4.0f;
+    const float off_base = (c2 <= 0.0f) ? (float)(4 * NBITS - 8 * dref) : (float)(8 * dref - 4 * NBITS);
+
+    v16f acc[JT];
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
+    float den = 0.0f;
+
+    // One step: 32 keys from k0.  MASK: keys from n on do not count.
+    auto step = [&](int k0, int n, auto mask_c) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        v16f sc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[r] = 0.0f;
+        const uint16_t *kp = ksign_s + (k0 + i_loc) * KSTRIDE + 8 * kg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const v8bf kf = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(kp + 16 * ks));
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0);
+        }
+        // register r: key k0 + 8 (r / 4) + 4 kg + r % 4 against this lane's query
+        uint32_t hl[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float fo = __builtin_fmaf(sc[r], off_slope, off_base);
+            if (MASK) fo = __builtin_fminf(__builtin_fmaxf(fo, 0.0f), (float)(8 * NBITS));   // padding keys
+            const TableEntry te = *reinterpret_cast<const TableEntry *>(reinterpret_cast<const char *>(tab_s) + (uint32_t)fo);
+            hl[r] = te.hl;
+            den += (!MASK || k0 + 8 * (r >> 2) + 4 * kg + (r & 3) < n) ? te.p : 0.0f;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint32_t ah[4], al[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                ah[e2] = __builtin_amdgcn_perm(hl[8 * t + 2 * e2 + 1], hl[8 * t + 2 * e2], 0x07060302u);   // upper halves
+                al[e2] = __builtin_amdgcn_perm(hl[8 * t + 2 * e2 + 1], hl[8 * t + 2 * e2], 0x05040100u);   // lower halves
+            }
+            const v8bf ph = __builtin_bit_cast(v8bf, make_uint4(ah[0], ah[1], ah[2], ah[3]));
+            const v8bf pl = __builtin_bit_cast(v8bf, make_uint4(al[0], al[1], al[2], al[3]));
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) {
+                // keys 16 t + 4 kg .. + 3 and 16 t + 8 + 4 kg .. + 3 of the tile, column jt * 32 + i_loc
+                const int off = (jt * 32 + i_loc) * kVtStride8 + k0 + 16 * t + 4 * kg;
+                const uint2 h0 = *reinterpret_cast<const uint2 *>(vth_s + off), h1 = *reinterpret_cast<const uint2 *>(vth_s + off + 8);
+                const uint2 l0 = *reinterpret_cast<const uint2 *>(vtl_s + off), l1 = *reinterpret_cast<const uint2 *>(vtl_s + off + 8);
+                const v8bf vh = __builtin_bit_cast(v8bf, make_uint4(h0.x, h0.y, h1.x, h1.y));
+                const v8bf vl = __builtin_bit_cast(v8bf, make_uint4(l0.x, l0.y, l1.x, l1.y));
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vh, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vl, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, vh, acc[jt], 0, 0, 0);
+            }
+        }
+    };
+
+    for (int j0 = 0; j0 < Nk; j0 += kKeyChunk) {
+        const int n = min(kKeyChunk, Nk - j0);
+        const int n_pad = (n + 31) & ~31;
+        __syncthreads();                           // the previous chunk has been consumed
+        // key codes -> rows of +-1.0: one task = one 64-bit word of one key (zeros past the last key:
+        // a score of 0 is a distance inside the table)
+        for (int t = tid; t < n_pad * W; t += n_threads) {
+            const int j = t / W, w = t % W;
+            const uint64_t wd = (j < n) ? kc_g[(size_t)(j0 + j) * W + w] : 0ull;
+            uint4 *dst = reinterpret_cast<uint4 *>(ksign_s + j * KSTRIDE + 64 * w);
+#pragma unroll
+            for (int bi = 0; bi < 8; ++bi) {
+                const uint32_t byte = (uint32_t)(wd >> (8 * bi)) & 0xFFu;
+                dst[bi] = (j < n) ? sign_s[byte] : make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+        // V: as in the kernel above, padded to whole 32-key steps
+        const int n_tasks = (n_pad / 2) * (DV / 4);
+        for (int base = 0; base < n_tasks; base += n_threads * kStageBatch) {
+            float4 v0[kStageBatch], v1[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int t = base + u * n_threads + tid;
+                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
+                v0[u] = v1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c4 * 4;
+                if (t < n_tasks && j < n) v0[u] = *reinterpret_cast<const float4 *>(vp);
+                if (t < n_tasks && j + 1 < n) v1[u] = *reinterpret_cast<const float4 *>(vp + (size_t)H * DV);
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int t = base + u * n_threads + tid;
+                if (t >= n_tasks) continue;
+                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
+                const float a0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, a1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    uint32_t up, lo;
+                    split_bf16_pair(a0[c], a1[c], up, lo);
+                    const int off = (c4 * 4 + c) * kVtStride8 + j;      // even: 4-byte aligned
+                    *reinterpret_cast<uint32_t *>(vth_s + off) = up;
+                    *reinterpret_cast<uint32_t *>(vtl_s + off) = lo;
                 }
             }
         }
+        __syncthreads();
+        const int n_full = n & ~31;                // whole steps first, then at most one masked step
+        for (int k0 = 0; k0 < n_full; k0 += 32) step(k0, n, std::false_type{});
+        if (n_full < n) step(n_full, n, std::true_type{});
     }
+
+    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane);
 }
 
 // Optional dump of the integer scores, one thread per (query, key) pair.
@@ -295,6 +518,7 @@ struct Launch {
     int H, Nq, Nk, q_chunks;
     float c2;
     bool rowref;
+    bool mm_scores;         // scores as sign dot products on the matrix cores (else XOR + popcount on the vector ALU)
     int8_t *xq;
     _Float16 *xh;
     float act_inv_scale;
@@ -302,6 +526,18 @@ struct Launch {
 
 template <int DV, int W>
 void launch_hamming(const Launch &L) {
+    // scores on the matrix cores on request, for codes up to 256 bits (the query's sign fragments live in registers)
+    if constexpr (W <= 4) {
+        if (L.mm_scores) {
+            if (L.rowref)
+                hamming_mm_kernel<DV, W, true><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks,
+                                                                             L.c2, L.xq, L.xh, L.act_inv_scale);
+            else
+                hamming_mm_kernel<DV, W, false><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks,
+                                                                              L.c2, L.xq, L.xh, L.act_inv_scale);
+            return;
+        }
+    }
     if (L.rowref)
         hamming_mfma_kernel<DV, W, true><<<L.grid, L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks, L.c2,
                                                                        L.xq, L.xh, L.act_inv_scale);
@@ -330,14 +566,15 @@ extern "C" int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_c
                                     float scale, int16_t *scores_or_null, void *stream) {
     sa::clear_error();
     return sa_hamming_attention_fused(q_codes, k_codes, v, out, B, H, Nq, Nk, nbits, dv, scale, scores_or_null,
-                                      nullptr, nullptr, 0.0f, stream);
+                                      nullptr, nullptr, 0.0f, SA_VARIANT_AUTO, stream);
 }
 
 extern "C" int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
                                           float *out, int B, int H, int Nq, int Nk, int nbits, int dv, float scale,
                                           int16_t *scores_or_null, int8_t *xq_or_null, void *xh_or_null,
-                                          float act_inv_scale, void *stream) {
+                                          float act_inv_scale, int variant, void *stream) {
     sa::clear_error();
+    SA_REQUIRE(variant >= 0 && variant <= 2, SA_ERR_INVALID, "sa_hamming_attention: unknown variant %d", variant);
     SA_REQUIRE(B >= 0 && H >= 0 && Nq >= 0 && Nk >= 0 && nbits > 0 && dv > 0, SA_ERR_INVALID,
                "sa_hamming_attention: negative size");
     SA_REQUIRE(nbits % 64 == 0, SA_ERR_SHAPE, "sa_hamming_attention: nbits %d is not a multiple of 64", nbits);
@@ -372,6 +609,11 @@ extern "C" int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_
     L.c2 = -2.0f * scale * 1.4426950408889634f;
     // exp2 of c2*dist stays a normal float for every possible distance -> no row reference needed
     L.rowref = !(scale >= 0.0f && -L.c2 * (float)nbits <= 100.0f);
+    // measured at the DeiT-Base shape: 38 us with popcount scores, 44 us with matrix-core scores (more LDS
+    // traffic and MFMA time than the vector work it saves), so AUTO keeps the popcount
+    L.mm_scores = (variant == SA_VARIANT_MFMA);
+    SA_REQUIRE(variant != SA_VARIANT_MFMA || W <= 4, SA_ERR_UNSUPPORTED,
+               "sa_hamming_attention: scores on the matrix cores need nbits <= 256 (got %d)", nbits);
     int rc;
     switch (dv) {
         case 32: rc = dispatch_w<32>(W, L); break;

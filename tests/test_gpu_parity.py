@@ -184,6 +184,9 @@ def test_additive_attention_is_reproducible(sa):
     (1, 2, 33, 50, 128, 64, 3.0),       # sharp softmax -> row-reference path
     (1, 2, 33, 50, 128, 64, -0.2),      # negative scale -> row-reference path
     (1, 1, 5, 1, 64, 64, None),         # one key
+    (1, 2, 300, 333, 128, 64, None),    # two query chunks, three key chunks, ragged tails
+    (1, 1, 40, 150, 512, 32, None),     # 512-bit codes: popcount scores only
+    (1, 1, 70, 200, 256, 64, 2.0),      # 256-bit codes, row-reference path, two key chunks
 ])
 def test_hamming_attention_matches_oracle(sa, B, H, Nq, Nk, nbits, dv, scale):
     q = wl.random_codes(11, (B, H, Nq), nbits)
@@ -196,6 +199,11 @@ def test_hamming_attention_matches_oracle(sa, B, H, Nq, Nk, nbits, dv, scale):
     out, scores = sa.sa_hamming_attention(dev(q), dev(k), dev(v), scale, nbits, want_scores=True)
     assert np.array_equal(host(scores), s_ref)
     assert_close(host(out), ref, ATTN_RTOL, ATTN_ATOL, "Hamming attention")
+    # scores by XOR + popcount on the vector ALU, and (up to 256 bits) as sign dot products on the matrix cores
+    for variant in ((0, 1) if nbits <= 256 else (0,)):
+        o2, _, _ = sa.sa_hamming_attention_fused(dev(q), dev(k), dev(v), scale, nbits, 1.0, want_xq=False,
+                                                 want_xh=False, variant=variant)
+        assert_close(host(o2), ref, ATTN_RTOL, ATTN_ATOL, "Hamming attention, variant %d" % variant)
 
 
 # --------------------------------------------------------------- shift layer ----
