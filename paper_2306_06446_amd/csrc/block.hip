@@ -151,6 +151,10 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
 
     rc = sa_binarize_pair(d->q, d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, qc, kc, stream);
     if (rc != SA_OK) return rc;
+    // The routing lists are needed after the attention kernel; the wait is enqueued before it (the
+    // routing is long done by then), so that the first Shift layer follows the attention kernel
+    // without a dependency packet in between.
+    if (moe) SA_HIP(hipStreamWaitEvent(main_st, lane->routed, 0));
     // The attention output leaves in three forms: fp32 (the block's output o), the int8 codes the
     // Shift layers read, and (with a Mult expert) the fp16 rounding its first layer reads.  The
     // Hamming kernel writes all three from its accumulators; the linear path adds one pass over o.
@@ -183,7 +187,6 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
         return sa_shift_mlp(xq, &all, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, nullptr,
                             d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
     }
-    SA_HIP(hipStreamWaitEvent(main_st, lane->routed, 0));
     const sa_rows shift_rows{perm, counts, 1, T};
     rc = sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
                       d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
