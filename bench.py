@@ -38,7 +38,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c4", "c5"])
+    ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="c3 times the two shift linear layers alone, in both variants")
     ap.add_argument("--rotate", type=int, default=0,
                     help="input/workspace sets cycled through (0 = enough to exceed the 256 MiB last-level cache)")
     ap.add_argument("--shift-variant", type=int, default=3, choices=[0, 1, 2, 3],
@@ -122,6 +123,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     sa.load_library()
+    if args.config == "c3":
+        return bench_shift_linear(args, sa, wl, torch, np)
     cfg = {"c1": wl.C1, "c2": wl.C2, "c4": wl.C4, "c5": wl.C5}[args.config]
     moe = cfg.E > 0 and cfg.shift_frac is not None
 
@@ -224,6 +227,14 @@ def main():
         roofline = dict(kernel=dom["name"], bound=dom["bound"], achieved=round(ach, 3), peak=peak, unit=unit,
                         frac=round(ach / peak, 4), traffic=read_traffic(args.config, dom["name"]),
                         us_per_launch=dom["us"])
+    # experts timed one after the other, counted as if they ran perfectly in parallel (the paper's
+    # "modularized" latency: the layer costs its slower expert)
+    modularized_us = None
+    if timed and moe:
+        by = {r["name"]: r["us"] for r in timed}
+        experts = [by.get("mult_fc1", 0) + by.get("mult_fc2", 0), by.get("shift_fc1", 0) + by.get("shift_fc2", 0)]
+        rest = sum(us for n, us in by.items() if not n.startswith(("mult_", "shift_")) and n != "dispatch")
+        modularized_us = round(rest + max(experts), 2)
     block_bytes = sum(t["bytes"] for t in table)
     block_hbm_frac = block_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
@@ -244,8 +255,57 @@ def main():
                    "input_sets_rotated": n_sets, "shift_variant": args.shift_variant},
         "block_hbm_roofline_frac": round(block_hbm_frac, 4),
         "block_algorithmic_bytes": block_bytes,
+        "block_us_sum_of_kernels_modularized": modularized_us,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": report,
     }
+    print(json.dumps(out))
+
+
+def bench_shift_linear(args, sa, wl, torch, np):
+    """Config 3: the two shift linear layers at DeiT-Small shapes, alone, VALU and matrix-core variants."""
+    M = wl.C3_M
+    rows = []
+    total_us = {0: 0.0, 1: 0.0}
+    for li, (K, N) in enumerate(wl.C3_SHAPES):
+        x = torch.from_numpy(wl.int8_activations(3, M, K, extra=li)).cuda()
+        w4 = torch.from_numpy(wl.shift_weights(3, 4 + li, N, K)).cuda()
+        n_sets = 4
+        ys = [torch.empty((M, N), dtype=torch.int32, device="cuda") for _ in range(n_sets)]
+        lib = sa.load_library()
+        for variant in (1, 0):
+            ws = torch.empty(max(16, lib.sa_shift_linear_workspace_bytes(sa._l(M), K, N, variant)), dtype=torch.uint8,
+                             device="cuda")
+            steps = args.steps if variant == 1 else max(3, args.steps // 10)
+            for y in ys:
+                sa.sa_shift_linear(x, w4, variant=variant, y=y, workspace=ws)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(steps):
+                sa.sa_shift_linear(x, w4, variant=variant, y=ys[i % n_sets], workspace=ws)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / steps
+            total_us[variant] += us
+            nbytes = M * K + K * N // 2 + 4 * M * N                  # int8 in, 4-bit weights, int32 out
+            ops = 2 * M * K * N
+            comp = "mfma_i8" if variant == 1 else "alu_int"
+            t_hbm, t_cmp = nbytes / (HBM_PEAK_GBS * 1e9) * 1e6, ops / (PEAK_TFLOPS[comp] * 1e12) * 1e6
+            rows.append(dict(name="shift_%dx%d_%s" % (K, N, "mfma" if variant == 1 else "valu"), us=round(us, 2), bytes=nbytes,
+                             ops=ops, hbm_floor_us=round(t_hbm, 2), compute_floor_us=round(t_cmp, 2),
+                             bound="hbm" if t_hbm >= t_cmp else ("mfma" if variant == 1 else "alu"), compute_peak=comp,
+                             hbm_frac=round(t_hbm / us, 4), binding_frac=round(max(t_hbm, t_cmp) / us, 4)))
+    dom = max((r for r in rows if r["name"].endswith("mfma")), key=lambda r: r["us"])
+    roofline = dict(kernel=dom["name"], bound=dom["bound"], achieved=round(dom["bytes"] / (dom["us"] * 1e-6) / 1e9, 3),
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=dom["hbm_frac"], traffic=None, us_per_launch=dom["us"])
+    ms = total_us[1] * 1e-3
+    out = {"metric": "shift linear tokens/s (both layers, int8 matrix-core variant) at 1 GPU; % HBM roofline",
+           "value": round(M / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "i8 x 4-bit -> i32", "data": "synthetic",
+           "config": {"workload": "c3-deit-small-shift-linear", "M": M, "layers": [list(s) for s in wl.C3_SHAPES]},
+           "valu_variant_ms_per_step": round(total_us[0] * 1e-3, 5), "roofline": roofline, "cpu_baseline": None,
+           "kernels": rows}
     print(json.dumps(out))
 
 
