@@ -201,6 +201,39 @@ def combine(expert_out, perm, gate):
     return y
 
 
+def layernorm(x, gamma, beta, eps):
+    x = _c(x, np.float32)
+    T, E = x.shape
+    gamma = _c(gamma, np.float32)
+    beta = _c(beta, np.float32)
+    assert gamma.shape == (E,) and beta.shape == (E,)
+    y = np.zeros((T, E), dtype=np.float64)
+    _load().oracle_layernorm(_p(x), ctypes.c_long(T), E, _p(gamma), _p(beta), ctypes.c_double(eps), _p(y))
+    return y
+
+
+def dequant_residual(acc, scale, residual=None):
+    acc = _c(acc, np.int32)
+    if residual is not None:
+        residual = _c(residual, np.float32)
+        assert residual.shape == acc.shape
+    y = np.zeros(acc.shape, dtype=np.float32)
+    _load().oracle_dequant_residual(_p(acc), ctypes.c_long(acc.size), ctypes.c_float(scale), _p(residual), _p(y))
+    return y
+
+
+def router_logits(z, wg, bg):
+    z = _c(z, np.float64)
+    wg = _c(wg, np.float32)
+    bg = _c(bg, np.float32)
+    T, E = z.shape
+    n_exp = wg.shape[1]
+    assert wg.shape == (E, n_exp) and bg.shape == (n_exp,)
+    logits = np.zeros((T, n_exp), dtype=np.float64)
+    _load().oracle_router_logits(_p(z), ctypes.c_long(T), E, _p(wg), _p(bg), n_exp, _p(logits))
+    return logits
+
+
 # ------------------------------------------------------------- compositions --
 
 def shift_mlp(xq, w1, w2, requant_scale, lut):
@@ -243,3 +276,47 @@ def block_forward(cfg, q, k, v, proj, scale, logits, p):
         return o, None
     x = o.reshape(cfg.T, cfg.E).astype(np.float32)
     return o, mlp_stage(x, logits, p)
+
+
+def layer_forward(cfg, x, lp, p, proj, scale):
+    """The whole block of Eq. 2 on tokens x [T, E] fp32.
+
+    LayerNorm -> int8 -> shift Linears Wq, Wk, Wv -> fp32 Q, K, V -> hash -> attention ->
+    int8 -> shift Linear Wo + residual -> LayerNorm -> router + MLP / MoE + residual.
+    lp holds the attention-side parameters (see workloads.LayerParams), p the MLP's.
+    Returns a dict of every intermediate; floats are fp64 except where the definition
+    rounds to fp32 (the dequantised Linears), integers are exact.
+    """
+    x = _c(x, np.float32)
+    T, E = x.shape
+    B, N, H = cfg.B, cfg.N, cfg.H
+    r = {}
+    r["ln1"] = layernorm(x, lp.gamma1, lp.beta1, lp.eps)
+    r["z1q"] = quantize_act(r["ln1"].astype(np.float32), lp.ln_inv_scale)
+    for name, w in (("q", lp.wq), ("k", lp.wk), ("v", lp.wv)):
+        r[name] = dequant_residual(shift_linear(r["z1q"], w), lp.qkv_scale)
+    q4, k4, v4 = (r[n].reshape(B, N, H, E // H) for n in ("q", "k", "v"))
+    r["qc"] = binarize(q4, proj, cfg.nbits)
+    r["kc"] = binarize(k4, proj, cfg.nbits)
+    if cfg.attention == "linear":
+        o, _ = additive_attention(r["qc"], r["kc"], v4, cfg.nbits, scale)
+    else:
+        o = hamming_attention(r["qc"], r["kc"], v4, cfg.nbits, scale)
+    r["o"] = o.reshape(T, E)
+    r["oq"] = quantize_act(r["o"].astype(np.float32), p.act_inv_scale)
+    r["x1"] = dequant_residual(shift_linear(r["oq"], lp.wo), lp.o_scale, x)
+    r["ln2"] = layernorm(r["x1"], lp.gamma2, lp.beta2, lp.eps)
+    z2 = r["ln2"].astype(np.float32)
+    logits = None
+    if lp.wg is not None:
+        r["logits"] = router_logits(r["ln2"], lp.wg, lp.bg)
+        logits = r["logits"].astype(np.float32)
+    p2 = _replace_inv_scale(p, lp.ln_inv_scale)
+    r["mlp"] = mlp_stage(z2, logits, p2)
+    r["y"] = r["x1"].astype(np.float64) + r["mlp"]
+    return r
+
+
+def _replace_inv_scale(p, inv_scale):
+    import dataclasses
+    return dataclasses.replace(p, act_inv_scale=inv_scale)

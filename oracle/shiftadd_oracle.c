@@ -353,3 +353,59 @@ void oracle_combine(const double *expert_out, const int32_t *perm, const double 
         for (int c = 0; c < E; ++c) y[(size_t)t * E + c] = gate[t] * expert_out[(size_t)i * E + c];
     }
 }
+
+/* ------------------------------------------------------------------------
+ * The remaining pieces of the block of Eq. 2: LayerNorm, the four attention
+ * Linears as shift layers (Sec. 4.1: the Linears of the attention module are
+ * reparameterised with sign flips and power-of-two shifts), the residual sums
+ * and the router G (Sec. 4.2).
+ * ------------------------------------------------------------------------ */
+
+/* LayerNorm over the last dimension (Eq. 2), fp64 from fp32 inputs:
+ *   y = (x - mean) / sqrt(var + eps) * gamma + beta,  var = mean((x - mean)^2). */
+void oracle_layernorm(const float *x, long T, int E, const float *gamma, const float *beta,
+                      double eps, double *y) {
+#pragma omp parallel for
+    for (long t = 0; t < T; ++t) {
+        const float *row = x + (size_t)t * E;
+        double mean = 0.0, var = 0.0;
+        for (int j = 0; j < E; ++j) mean += (double)row[j];
+        mean /= (double)E;
+        for (int j = 0; j < E; ++j) {
+            const double c = (double)row[j] - mean;
+            var += c * c;
+        }
+        var /= (double)E;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int j = 0; j < E; ++j)
+            y[(size_t)t * E + j] = ((double)row[j] - mean) * rstd * (double)gamma[j] + (double)beta[j];
+    }
+}
+
+/* Output side of a shift Linear that feeds fp32 consumers (Q, K, V; the output
+ * projection with its residual, Eq. 2).  The integer accumulator of Eq. 3 is
+ * exact; its real value is acc * scale (the common power of two of the weights
+ * and the activation scale folded into one factor).  The paper does not say
+ * how the factor is applied; the reading taken is one fused multiply-add in
+ * fp32 with the int32 converted round-to-nearest-even first:
+ *   y = fmaf((float)acc, scale, residual)       (residual = 0 when absent)
+ * which both sides can follow to the bit. */
+void oracle_dequant_residual(const int32_t *acc, long n, float scale, const float *residual,
+                             float *y) {
+#pragma omp parallel for
+    for (long i = 0; i < n; ++i)
+        y[i] = fmaf((float)acc[i], scale, residual ? residual[i] : 0.0f);
+}
+
+/* Router (Sec. 4.2, the gate G over the experts): logits = z Wg + bg in fp64;
+ * z [T, E] fp64, Wg [E, n_exp] fp32, bg [n_exp] fp32. */
+void oracle_router_logits(const double *z, long T, int E, const float *wg, const float *bg,
+                          int n_exp, double *logits) {
+#pragma omp parallel for
+    for (long t = 0; t < T; ++t)
+        for (int e = 0; e < n_exp; ++e) {
+            double s = 0.0;
+            for (int j = 0; j < E; ++j) s += z[(size_t)t * E + j] * (double)wg[(size_t)j * n_exp + e];
+            logits[(size_t)t * n_exp + e] = s + (double)bg[e];
+        }
+}

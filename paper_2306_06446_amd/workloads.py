@@ -21,6 +21,7 @@ the interface, not an implementation detail):
   e = p + 7; w4[n, k // 2] holds k even in the low nibble, k odd in the high
   nibble; shape [N_out, K // 2] uint8.
 * router logits          fp32  [T, 2]            column 0 = Mult, 1 = Shift
+* router weight Wg       fp32  [E, 2], bias bg [2]   (whole-layer path: logits = LN2(x) Wg + bg)
 """
 from __future__ import annotations
 
@@ -67,6 +68,7 @@ BLOCK_CONFIGS = {1: C1, 2: C2, 4: C4, 5: C5}
 
 # tensor ids (second word of the seed sequence)
 _Q, _K, _V, _PROJ, _W1, _W2, _ROUTER, _MW1, _MW2, _X8, _XF = range(11)
+_XIN, _LN1, _LN2, _WQ, _WK, _WV, _WO, _WG = range(11, 19)
 
 
 def _rng(cfg_id: int, tensor_id: int, extra: int = 0) -> np.random.Generator:
@@ -221,3 +223,56 @@ def random_logits(seed: int, T: int, tie_every: int = 0) -> np.ndarray:
     if tie_every:
         logits[::tie_every, 1] = logits[::tie_every, 0]
     return logits
+
+
+# ------------------------------------------------ the whole layer of Eq. 2 --
+
+@dataclasses.dataclass
+class LayerParams:
+    """Attention-side parameters of the complete block: two LayerNorms, the four attention
+    Linears as packed 4-bit shift weights [E, E/2], their static scales, and the router."""
+    gamma1: np.ndarray
+    beta1: np.ndarray
+    gamma2: np.ndarray
+    beta2: np.ndarray
+    eps: float
+    ln_inv_scale: float     # LayerNorm output (unit variance) -> int8, clip at 4 sigma
+    wq: np.ndarray
+    wk: np.ndarray
+    wv: np.ndarray
+    wo: np.ndarray
+    qkv_scale: float        # int32 accumulator -> fp32 Q, K, V (~ unit variance)
+    o_scale: float          # int32 accumulator of Wo -> fp32 (~ unit variance)
+    wg: np.ndarray | None   # [E, 2] fp32 router weight (None: no MoE)
+    bg: np.ndarray | None   # [2]
+
+
+def layer_input(cfg: BlockConfig) -> np.ndarray:
+    """Tokens entering the layer, fp32 [T, E] ~ N(0,1)."""
+    return _rng(cfg.cfg_id, _XIN).standard_normal((cfg.T, cfg.E), dtype=np.float32)
+
+
+def layer_params(cfg: BlockConfig) -> LayerParams:
+    E = cfg.E
+
+    def affine(tid):
+        g = _rng(cfg.cfg_id, tid)
+        gamma = (1.0 + 0.1 * g.standard_normal(E)).astype(np.float32)
+        beta = (0.1 * g.standard_normal(E)).astype(np.float32)
+        return gamma, beta
+
+    gamma1, beta1 = affine(_LN1)
+    gamma2, beta2 = affine(_LN2)
+    acc_std = (127.0 / 4.0) * _RMS_W * math.sqrt(E)
+    scale = float(np.float32(1.0 / acc_std))
+    wg = bg = None
+    if cfg.shift_frac is not None:
+        import statistics
+        wg = (_rng(cfg.cfg_id, _WG).standard_normal((E, 2), dtype=np.float32) / np.float32(math.sqrt(E)))
+        # logit difference ~ N(b, 2): b places the requested share of tokens on the Shift expert
+        b = math.sqrt(2.0) * statistics.NormalDist().inv_cdf(cfg.shift_frac)
+        bg = np.array([0.0, b], dtype=np.float32)
+    return LayerParams(gamma1, beta1, gamma2, beta2, 1e-6, float(np.float32(127.0 / 4.0)),
+                       shift_weights(cfg.cfg_id, _WQ, E, E), shift_weights(cfg.cfg_id, _WK, E, E),
+                       shift_weights(cfg.cfg_id, _WV, E, E), shift_weights(cfg.cfg_id, _WO, E, E),
+                       scale, scale, wg, bg)
