@@ -148,6 +148,22 @@ int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t *bias_or_n
                     void *stream);
 
 /*
+ * A shift Linear whose consumers are fp32 (Sec. 4.1: the four Linears of the
+ * attention module as shift layers; Eq. 2 for the residual):
+ *   y[m, n] = fma(float(acc[m, n]), scale, residual[m, n]),  acc as in sa_shift_linear
+ * (int32 accumulator converted round-to-nearest-even, one fused multiply-add;
+ * residual_or_null == NULL stands for 0).  The N columns leave as `parts`
+ * (1..3) column blocks of N / parts columns each, block p to y0 / y1 / y2 as a
+ * dense [M, N / parts] matrix: a fused Q/K/V projection (weight rows = Wq, Wk,
+ * Wv stacked) writes its three outputs in the layout the attention calls read.
+ * N % (4 * parts) == 0; a residual [M, N] needs parts == 1 and may be y0 itself
+ * (in place).  Variants, weights and workspace as for sa_shift_linear.
+ */
+int sa_shift_linear_f32(const int8_t *x, const uint8_t *w4, long M, int K, int N, int variant,
+                        float scale, const float *residual_or_null, int parts, float *y0, float *y1,
+                        float *y2, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Top-1 routing (Sec. 4.2: p = softmax(logits), G(x) = p_i * 1{p_i >= p_j}).
  * Expert 0 = Mult, expert 1 = Shift.  The decision compares raw logits; ties
  * go to the lowest index.  2 <= E <= 8.
@@ -172,6 +188,22 @@ int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *st
  * is not NULL: the input form of the Mult expert (Sec. 4.2), so x is read once for both. */
 int sa_quantize_act_half(const float *x, long n, float inv_scale, int8_t *q, void *xh_or_null,
                          void *stream);
+
+/*
+ * LayerNorm over the rows of x [T, E] (Eq. 2), fp32, biased variance:
+ *   y = (x - mean) / sqrt(var + eps) * gamma + beta
+ * fused with the forms its consumers read; each output is optional (NULL):
+ *   ln_or_null     fp32 [T, E]   y itself
+ *   q_or_null      int8 [T, E]   clamp(rne(y * inv_scale), -127, 127), the input of shift Linears
+ *   xh_or_null     fp16 [T, E]   y rounded to half, the input of the Mult expert (Sec. 4.2)
+ *   logits_or_null fp32 [T, n_experts] = y * wg + bg, the router G of Sec. 4.2;
+ *                  wg fp32 [E, n_experts], bg fp32 [n_experts], 2 <= n_experts <= 8
+ * E % 4 == 0 and E <= 8192.
+ */
+int sa_layernorm_quant(const float *x, long T, int E, const float *gamma, const float *beta, float eps,
+                       float inv_scale, float *ln_or_null, int8_t *q_or_null, void *xh_or_null,
+                       const float *wg_or_null, const float *bg_or_null, int n_experts,
+                       float *logits_or_null, void *stream);
 
 /*
  * Between the two shift linears of the Shift expert:
@@ -206,7 +238,11 @@ typedef struct sa_rows {
  * Workspace holds the int8 hidden rows.  E % 64 == 0 and hid % 64 == 0.
  * stages: 1 = first layer only (fills the workspace), 2 = second layer only
  * (reads the workspace a stage-1 call with the same rows filled), 3 = both.
+ * stages | SA_MLP_ACCUMULATE: y_or_null is added to instead of overwritten,
+ *   y[rows[i], :] = fma(gate, out_scale * y2[i, :], y[rows[i], :])
+ * (the residual sum of Eq. 2 when y holds the block's input rows).
  */
+#define SA_MLP_ACCUMULATE 4
 size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid);
 int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hid, const uint8_t *w1,
                  const uint8_t *w2, float requant_scale, const int8_t *lut, int32_t *y2_or_null,

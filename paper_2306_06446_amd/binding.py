@@ -16,11 +16,12 @@ LIB_PATH = os.path.join(_HERE, "libshiftadd.so")
 _lib = None
 
 SA_VARIANT_VALU, SA_VARIANT_MFMA, SA_VARIANT_AUTO, SA_VARIANT_MFMA_PREPARED = 0, 1, 2, 3
+SA_MLP_ACCUMULATE = 4
 
 EXPORTS = [
     "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_binarize_pair", "sa_additive_attention_workspace_bytes",
     "sa_additive_attention", "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
-    "sa_shift_linear_workspace_bytes", "sa_shift_linear",
+    "sa_shift_linear_workspace_bytes", "sa_shift_linear", "sa_shift_linear_f32", "sa_layernorm_quant",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
@@ -213,6 +214,38 @@ def sa_shift_linear(x, w4, bias=None, variant=SA_VARIANT_AUTO, y=None, workspace
     _check(lib.sa_shift_linear(_ptr(x), _ptr(w4), _ptr(bias), _ptr(y), _l(M), K, N, variant,
                                _ptr(workspace), _z(workspace.numel()), _stream()))
     return y
+
+
+def sa_shift_linear_f32(x, w4, scale, residual=None, parts=1, variant=SA_VARIANT_AUTO, ys=None, workspace=None):
+    """fp32 outputs y_p = fma(float(acc), scale, residual): a tuple of `parts` [M, N / parts] tensors."""
+    lib = load_library()
+    M, K = x.shape
+    N = _out_width(w4, variant)
+    if ys is None:
+        ys = tuple(torch.empty((M, N // parts), dtype=torch.float32, device=x.device) for _ in range(parts))
+    if workspace is None:
+        workspace = _workspace(lib.sa_shift_linear_workspace_bytes(_l(M), K, N, variant), x.device)
+    y = list(ys) + [None] * (3 - len(ys))
+    _check(lib.sa_shift_linear_f32(_ptr(x), _ptr(w4), _l(M), K, N, variant, _f(scale), _ptr(residual), parts,
+                                   _ptr(y[0]), _ptr(y[1]), _ptr(y[2]), _ptr(workspace), _z(workspace.numel()),
+                                   _stream()))
+    return tuple(ys)
+
+
+def sa_layernorm_quant(x, gamma, beta, eps, inv_scale=1.0, want_ln=True, want_q=False, want_half=False,
+                       wg=None, bg=None):
+    """Returns (ln, q, xh, logits); entries not asked for are None."""
+    T, E = x.shape
+    dev = x.device
+    ln = torch.empty((T, E), dtype=torch.float32, device=dev) if want_ln else None
+    q = torch.empty((T, E), dtype=torch.int8, device=dev) if want_q else None
+    xh = torch.empty((T, E), dtype=torch.float16, device=dev) if want_half else None
+    n_exp = 0 if wg is None else wg.shape[1]
+    logits = torch.empty((T, n_exp), dtype=torch.float32, device=dev) if wg is not None else None
+    _check(load_library().sa_layernorm_quant(_ptr(x), _l(T), E, _ptr(gamma), _ptr(beta), _f(eps), _f(inv_scale),
+                                             _ptr(ln), _ptr(q), _ptr(xh), _ptr(wg), _ptr(bg), n_exp, _ptr(logits),
+                                             _stream()))
+    return ln, q, xh, logits
 
 
 def sa_moe_dispatch(logits, out=None, workspace=None):

@@ -13,6 +13,7 @@ enum EpiMode : int {
     kEpiFloat,         // of[m, n] = acc                                          fp32
     kEpiGeluHalf,      // hh[m, n] = half(gelu(acc))                              fp16
     kEpiScatterF32,    // yf[rows[m], n] = gate[rows[m]] * acc
+    kEpiLinearF32,     // parts[n / part_width][m, n % part_width] = fma(float(acc), lin_scale, residual[m, n])
 };
 
 struct Epilogue {
@@ -26,6 +27,11 @@ struct Epilogue {
     float out_scale = 1.0f;
     float *of = nullptr;           // compact fp32 out
     _Float16 *hh = nullptr;        // compact fp16 out
+    bool accumulate = false;       // scattered fp32 out: add to what yf holds (fma(gate, value, old)) instead of overwriting
+    float *parts[3] = {nullptr, nullptr, nullptr};   // kEpiLinearF32: column block p of width part_width goes to parts[p]
+    int part_width = 0;
+    const float *residual = nullptr;                 // kEpiLinearF32: [rows, N] or null
+    float lin_scale = 1.0f;
 };
 
 __device__ inline int8_t requant_code(float t) {

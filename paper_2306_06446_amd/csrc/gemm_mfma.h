@@ -96,7 +96,10 @@ __device__ inline void load_to_lds_16(const void *src, uint32_t lds_base) {
 //   static constexpr bool kScatter    : output row of tile row m is sel.rows[m] (else m)
 //   uint32_t convert(acc, int n, const uint8_t *lds_table) const : the element's bits for column n
 //   void *out : [rows, N] elements;  const void *table;  const float *gate : null, or a factor per
-//       destination row that multiplies fp32 outputs (kScatter && kBytes == 4 only)
+//       destination row that multiplies fp32 outputs (kScatter && kBytes == 4 only);  bool accumulate :
+//       (same case) the product is added to what the destination holds, as fma(gate, value, old)
+//   static constexpr bool kLinear     : fp32 outputs leave as fma(value, scale, residual[m, n]) into
+//       column blocks: float *parts[3], int part_width (a multiple of 4), const float *residual, float scale
 // Wait until at most N of this wavefront's vector-memory loads are still in flight (loads
 // complete in issue order, so the oldest ones are the ones that have landed).
 template <int N>
@@ -348,16 +351,42 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
             if (m < n_rows && n < N) {
                 uint4 v = *reinterpret_cast<const uint4 *>(tile + (ml * CPR + cc) * 16);
                 const long t = (Store::kScatter && rows) ? (long)rows[m] : m;
+                uint8_t *dst = static_cast<uint8_t *>(store.out) + (size_t)t * out_row_bytes + (size_t)n * ES;
+                if constexpr (Store::kLinear) {
+                    // whole chunks by construction: part_width and N are multiples of 4
+                    float4 res = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    if (store.residual) res = *reinterpret_cast<const float4 *>(store.residual + (size_t)t * N + n);
+                    v.x = __builtin_bit_cast(uint32_t, __builtin_fmaf(__builtin_bit_cast(float, v.x), store.scale, res.x));
+                    v.y = __builtin_bit_cast(uint32_t, __builtin_fmaf(__builtin_bit_cast(float, v.y), store.scale, res.y));
+                    v.z = __builtin_bit_cast(uint32_t, __builtin_fmaf(__builtin_bit_cast(float, v.z), store.scale, res.z));
+                    v.w = __builtin_bit_cast(uint32_t, __builtin_fmaf(__builtin_bit_cast(float, v.w), store.scale, res.w));
+                    const int part = n / store.part_width;
+                    float *base = part == 0 ? store.parts[0] : part == 1 ? store.parts[1] : store.parts[2];
+                    dst = reinterpret_cast<uint8_t *>(base + (size_t)t * store.part_width + (n - part * store.part_width));
+                }
                 if constexpr (ES == 4 && Store::kScatter) {
-                    if (store.gate) {
-                        const float gt = store.gate[t];
+                    const float gt = store.gate ? store.gate[t] : 1.0f;
+                    if (store.accumulate) {
+                        float old[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (whole_chunks) {
+                            const float4 o4 = *reinterpret_cast<const float4 *>(dst);
+                            old[0] = o4.x; old[1] = o4.y; old[2] = o4.z; old[3] = o4.w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (n + e < N) old[e] = reinterpret_cast<const float *>(dst)[e];
+                        }
+                        v.x = __builtin_bit_cast(uint32_t, __builtin_fmaf(gt, __builtin_bit_cast(float, v.x), old[0]));
+                        v.y = __builtin_bit_cast(uint32_t, __builtin_fmaf(gt, __builtin_bit_cast(float, v.y), old[1]));
+                        v.z = __builtin_bit_cast(uint32_t, __builtin_fmaf(gt, __builtin_bit_cast(float, v.z), old[2]));
+                        v.w = __builtin_bit_cast(uint32_t, __builtin_fmaf(gt, __builtin_bit_cast(float, v.w), old[3]));
+                    } else if (store.gate) {
                         v.x = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.x));
                         v.y = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.y));
                         v.z = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.z));
                         v.w = __builtin_bit_cast(uint32_t, gt * __builtin_bit_cast(float, v.w));
                     }
                 }
-                uint8_t *dst = static_cast<uint8_t *>(store.out) + (size_t)t * out_row_bytes + (size_t)n * ES;
                 if (ES < 4 || whole_chunks) {
                     *reinterpret_cast<uint4 *>(dst) = v;
                 } else {                          // 32-bit rows that are not a multiple of 16 bytes

@@ -38,12 +38,15 @@ struct MultStore {
     static constexpr int kBytes = (MODE == kEpiGeluHalf) ? 2 : 4;
     static constexpr int kTableBytes = 0;
     static constexpr bool kScatter = (MODE == kEpiScatterF32);
+    static constexpr bool kLinear = false;
     void *out;                      // compact fp32 rows | fp16 hidden rows | scattered fp32 rows
     const void *table = nullptr;
     const float *gate;
+    bool accumulate;
     explicit MultStore(const Epilogue &epi)
         : out(MODE == kEpiFloat ? (void *)epi.of : MODE == kEpiGeluHalf ? (void *)epi.hh : (void *)epi.yf),
-          gate(MODE == kEpiScatterF32 ? epi.gate : nullptr) {}
+          gate(MODE == kEpiScatterF32 ? epi.gate : nullptr),
+          accumulate(MODE == kEpiScatterF32 && epi.accumulate) {}
     __device__ inline uint32_t convert(float a, int, const uint8_t *) const {
         if (MODE == kEpiGeluHalf) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)gelu_erf(a));
         return __builtin_bit_cast(uint32_t, a);
@@ -118,6 +121,7 @@ int mult_mlp_impl(const float *x, const _Float16 *xh_all, const sa::RowSel &sel,
         sa::Epilogue e3;
         e3.yf = y_or_null;
         e3.gate = gate_or_null;
+        e3.accumulate = (stages & SA_MLP_ACCUMULATE) != 0;
         MultStore<sa::kEpiScatterF32> s3(e3);
         rc = sa::launch_gemm<sa::F16Traits>(g2, s3, st, "sa_mult_mlp_f16(fc2 scatter)");
         if (rc != SA_OK) return rc;
@@ -135,7 +139,8 @@ int check_mult_args(const void *x, const sa_rows *rows, sa::RowSel *sel, int E, 
                "sa_mult_mlp_f16: E (%d) and hid (%d) must be multiples of 32", E, hid);
     if (sel->max_rows == 0) return SA_OK;
     SA_REQUIRE(x && w1_f16 && w2_f16, SA_ERR_INVALID, "sa_mult_mlp_f16: NULL buffer");
-    SA_REQUIRE(stages >= 1 && stages <= 3, SA_ERR_INVALID, "sa_mult_mlp_f16: stages must be 1, 2 or 3");
+    SA_REQUIRE((stages & 3) != 0 && (stages & ~(3 | SA_MLP_ACCUMULATE)) == 0, SA_ERR_INVALID,
+               "sa_mult_mlp_f16: stages must be 1, 2 or 3, optionally | SA_MLP_ACCUMULATE");
     SA_REQUIRE(!(stages & 2) || out_or_null || y_or_null, SA_ERR_INVALID, "sa_mult_mlp_f16: no output requested");
     SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w1_f16) && sa::aligned16(w2_f16) && sa::aligned16(out_or_null) &&
                    sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) && sa::aligned16(workspace) &&

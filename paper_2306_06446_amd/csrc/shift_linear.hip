@@ -26,10 +26,16 @@ __device__ inline void epi_store(const Epilogue &e, long m, int n, int N, int32_
     } else if (MODE == kEpiRequantLut) {
         const float t = (float)acc * e.rq;
         e.h[(size_t)m * N + n] = e.lut[(int)requant_code(t) + 128];
+    } else if (MODE == kEpiLinearF32) {
+        const float res = e.residual ? e.residual[(size_t)m * N + n] : 0.0f;
+        const int part = n / e.part_width;
+        e.parts[part][(size_t)m * e.part_width + (n - part * e.part_width)] = __builtin_fmaf((float)acc, e.lin_scale, res);
     } else {
         const long t = rows ? rows[m] : m;
         const float g = e.gate ? e.gate[t] : 1.0f;
-        e.yf[(size_t)t * N + n] = g * (e.out_scale * (float)acc);
+        const float val = e.out_scale * (float)acc;
+        float *dst = e.yf + (size_t)t * N + n;
+        *dst = e.accumulate ? __builtin_fmaf(g, val, *dst) : g * val;
     }
 }
 
@@ -165,18 +171,31 @@ struct ShiftStore {
     static constexpr int kBytes = (MODE == kEpiRequantLut) ? 1 : 4;
     static constexpr int kTableBytes = (MODE == kEpiRequantLut) ? 256 : 0;
     static constexpr bool kScatter = (MODE == kEpiScatterI32);
+    static constexpr bool kLinear = (MODE == kEpiLinearF32);
     Epilogue e;
     void *out;             // int32 rows | int8 hidden rows | scattered fp32 rows
     const void *table;     // the 256-entry activation table
     const float *gate;
+    bool accumulate;
+    float *parts[3];       // kEpiLinearF32: column blocks, residual and scale
+    int part_width;
+    const float *residual;
+    float scale;
     explicit ShiftStore(const Epilogue &epi)     // epi.rq is made finite here: convert() relies on it
         : e(with_finite_scale(epi)),
-          out(MODE == kEpiInt32 ? (void *)epi.y : MODE == kEpiRequantLut ? (void *)epi.h : (void *)epi.yf),
+          out(MODE == kEpiInt32 ? (void *)epi.y : MODE == kEpiRequantLut ? (void *)epi.h
+              : MODE == kEpiLinearF32 ? (void *)epi.parts[0] : (void *)epi.yf),
           table(epi.lut),
-          gate(MODE == kEpiScatterI32 ? epi.gate : nullptr) {}
+          gate(MODE == kEpiScatterI32 ? epi.gate : nullptr),
+          accumulate(MODE == kEpiScatterI32 && epi.accumulate),
+          parts{epi.parts[0], epi.parts[1], epi.parts[2]},
+          part_width(epi.part_width > 0 ? epi.part_width : 4),
+          residual(epi.residual),
+          scale(epi.lin_scale) {}
     __device__ inline uint32_t convert(int32_t acc, int n, const uint8_t *lds_table) const {
         if (MODE == kEpiInt32) return (uint32_t)(acc + (e.bias ? e.bias[n] : 0));
         if (MODE == kEpiRequantLut) return lds_table[requant_index(acc, e.rq)];
+        if (MODE == kEpiLinearF32) return __builtin_bit_cast(uint32_t, (float)acc);   // scaled at the store
         return __builtin_bit_cast(uint32_t, e.out_scale * (float)acc);
     }
 };
@@ -322,6 +341,42 @@ extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t
     return SA_OK;
 }
 
+extern "C" int sa_shift_linear_f32(const int8_t *x, const uint8_t *w4, long M, int K, int N, int variant,
+                                   float scale, const float *residual_or_null, int parts, float *y0, float *y1,
+                                   float *y2, void *workspace, size_t workspace_bytes, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(M >= 0 && K >= 0 && N >= 0, SA_ERR_INVALID, "sa_shift_linear_f32: negative size");
+    SA_REQUIRE(variant >= 0 && variant <= 3, SA_ERR_INVALID, "sa_shift_linear_f32: unknown variant %d", variant);
+    SA_REQUIRE(parts >= 1 && parts <= 3, SA_ERR_INVALID, "sa_shift_linear_f32: parts must be 1, 2 or 3");
+    SA_REQUIRE(K % 32 == 0, SA_ERR_SHAPE, "sa_shift_linear_f32: K (%d) must be a multiple of 32", K);
+    SA_REQUIRE(K <= 131072, SA_ERR_SHAPE, "sa_shift_linear_f32: K too large for int32 accumulation");
+    SA_REQUIRE(N % (4 * parts) == 0, SA_ERR_SHAPE,
+               "sa_shift_linear_f32: N (%d) must split into %d column blocks of whole 16-byte chunks", N, parts);
+    SA_REQUIRE(parts == 1 || residual_or_null == nullptr, SA_ERR_INVALID,
+               "sa_shift_linear_f32: a residual needs parts == 1");
+    SA_REQUIRE(M < 65535L * kValuRows, SA_ERR_SHAPE, "sa_shift_linear_f32: too many rows for one call");
+    if (M == 0 || N == 0) return SA_OK;
+    SA_REQUIRE(x && w4 && y0 && (parts < 2 || y1) && (parts < 3 || y2), SA_ERR_INVALID,
+               "sa_shift_linear_f32: NULL buffer");
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(w4) && sa::aligned16(y0) && sa::aligned16(y1) && sa::aligned16(y2) &&
+                   sa::aligned16(residual_or_null) && sa::aligned16(workspace),
+               SA_ERR_ALIGN, "sa_shift_linear_f32: pointers must be 16-byte aligned");
+    if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED)
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear_f32: the MFMA variants need K %% 64 == 0 (K = %d)", K);
+    const size_t need = sa_shift_linear_workspace_bytes(M, K, N, variant);
+    SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
+               "sa_shift_linear_f32: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    sa::Epilogue epi;
+    epi.parts[0] = y0;
+    epi.parts[1] = parts > 1 ? y1 : y0;
+    epi.parts[2] = parts > 2 ? y2 : y0;
+    epi.part_width = N / parts;
+    epi.residual = residual_or_null;
+    epi.lin_scale = scale;
+    sa::RowSel sel{nullptr, nullptr, 0, M};
+    return launch_shift<sa::kEpiLinearF32>(variant, x, w4, sel, false, K, N, epi, workspace, sa::as_stream(stream));
+}
+
 extern "C" int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *stream) {
     sa::clear_error();
     return sa_quantize_act_half(x, n, inv_scale, q, nullptr, stream);
@@ -378,7 +433,8 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     SA_REQUIRE(E <= 131072 && hid <= 131072, SA_ERR_SHAPE, "sa_shift_mlp: width too large");
     if (sel.max_rows == 0) return SA_OK;
     SA_REQUIRE(xq && w1 && w2 && lut, SA_ERR_INVALID, "sa_shift_mlp: NULL buffer");
-    SA_REQUIRE(stages >= 1 && stages <= 3, SA_ERR_INVALID, "sa_shift_mlp: stages must be 1, 2 or 3");
+    SA_REQUIRE((stages & 3) != 0 && (stages & ~(3 | SA_MLP_ACCUMULATE)) == 0, SA_ERR_INVALID,
+               "sa_shift_mlp: stages must be 1, 2 or 3, optionally | SA_MLP_ACCUMULATE");
     SA_REQUIRE(!(stages & 2) || y2_or_null || y_or_null, SA_ERR_INVALID, "sa_shift_mlp: no output requested");
     SA_REQUIRE(sa::aligned16(xq) && sa::aligned16(w1) && sa::aligned16(w2) && sa::aligned16(lut) &&
                    sa::aligned16(y2_or_null) && sa::aligned16(y_or_null) && sa::aligned16(gate_or_null) &&
@@ -415,6 +471,7 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
         e3.yf = y_or_null;
         e3.gate = gate_or_null;
         e3.out_scale = out_scale;
+        e3.accumulate = (stages & SA_MLP_ACCUMULATE) != 0;
         rc = launch_shift<sa::kEpiScatterI32>(variant, hbuf, w2, sel, false, hid, E, e3, planes2, st);
         if (rc != SA_OK) return rc;
     }

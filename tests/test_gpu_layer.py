@@ -1,0 +1,137 @@
+"""GPU parity of the rest of the block of Eq. 2: LayerNorm with its fused outputs, shift Linears
+with fp32 outputs (Q/K/V in column blocks, output projection with residual), the accumulating
+expert epilogues, and the composed layer.  Every stage runs on inputs the CPU oracle produced."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import assert_close, dev, host
+from paper_2306_06446_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+# ---------------------------------------------------------------- LayerNorm ---
+
+def check_codes(q, y_ref, inv_scale, slack):
+    """int8 codes of a float that the two sides know to ~1e-6: the code must be a correct rounding of
+    some value within `slack` of the oracle's (unique away from the rounding boundaries)."""
+    t = np.clip(y_ref * np.float64(np.float32(inv_scale)), -127.0, 127.0)
+    assert np.all(np.abs(q.astype(np.float64) - t) <= 0.5 + slack * (1.0 + np.abs(t)))
+    exact = np.clip(np.rint(t), -127, 127)
+    far = np.abs(t - np.floor(t) - 0.5) > 1e-3                 # not within 1e-3 of a tie
+    assert np.array_equal(q[far], exact[far].astype(np.int8))
+
+
+@pytest.mark.parametrize("T,E", [(197, 192), (50, 768), (33, 256), (5, 1024), (3, 4096), (2, 8192), (9, 68)])
+def test_layernorm_outputs_match_oracle(sa, T, E):
+    g = np.random.default_rng([51, T, E])
+    x = (g.standard_normal((T, E)) * 2.0 + 0.5).astype(np.float32)
+    gamma = (1.0 + 0.1 * g.standard_normal(E)).astype(np.float32)
+    beta = (0.1 * g.standard_normal(E)).astype(np.float32)
+    wg = (g.standard_normal((E, 2)) / np.sqrt(E)).astype(np.float32)
+    bg = np.array([0.1, -0.2], dtype=np.float32)
+    inv = 127.0 / 4.0
+    ref = oracle.layernorm(x, gamma, beta, 1e-6)
+    ln, q, xh, logits = sa.sa_layernorm_quant(dev(x), dev(gamma), dev(beta), 1e-6, inv, want_ln=True, want_q=True,
+                                              want_half=True, wg=dev(wg), bg=dev(bg))
+    assert_close(host(ln), ref, 2e-5, 2e-6, "LayerNorm")
+    check_codes(host(q), ref, inv, 1e-4)
+    assert_close(host(xh).astype(np.float64), ref, 1e-3, 1e-6, "fp16 rows")          # half rounding: 2^-11 relative
+    assert_close(host(logits), oracle.router_logits(ref, wg, bg), 1e-5, 2e-5, "router logits")
+    # a single requested output gives the same values
+    _, q2, _, _ = sa.sa_layernorm_quant(dev(x), dev(gamma), dev(beta), 1e-6, inv, want_ln=False, want_q=True)
+    assert torch.equal(q2, q)
+
+
+def test_layernorm_eight_experts_and_constant_rows(sa):
+    T, E = 70, 384
+    g = np.random.default_rng(52)
+    x = g.standard_normal((T, E)).astype(np.float32)
+    x[3] = 2.5                                                  # zero variance: y = beta
+    gamma = np.ones(E, np.float32)
+    beta = (0.1 * g.standard_normal(E)).astype(np.float32)
+    wg = (g.standard_normal((E, 8)) / np.sqrt(E)).astype(np.float32)
+    bg = g.standard_normal(8).astype(np.float32)
+    ref = oracle.layernorm(x, gamma, beta, 1e-6)
+    ln, _, _, logits = sa.sa_layernorm_quant(dev(x), dev(gamma), dev(beta), 1e-6, wg=dev(wg), bg=dev(bg))
+    assert_close(host(ln), ref, 2e-5, 2e-6, "LayerNorm")
+    assert np.array_equal(host(ln)[3], beta)
+    assert_close(host(logits), oracle.router_logits(ref, wg, bg), 1e-5, 2e-5, "router logits")
+
+
+# ------------------------------------------------------ fp32 shift Linears ---
+
+@pytest.mark.parametrize("variant", [0, 1, 3])
+@pytest.mark.parametrize("M,K,N,parts", [(300, 192, 576, 3), (261, 768, 768, 1), (130, 64, 24, 2), (1, 128, 4, 1),
+                                         (70, 1536, 200, 1)])
+def test_shift_linear_f32_bit_exact(sa, variant, M, K, N, parts):
+    x = wl.int8_activations(3, M, K, extra=N)
+    w4 = wl.shift_weights(3, 4, N, K)
+    scale = float(np.float32(3.7e-5))
+    acc = oracle.shift_linear(x, w4)
+    d_w = dev(w4)
+    if variant == 3:
+        d_w = sa.sa_shift_planes_prepare(d_w)
+    ys = sa.sa_shift_linear_f32(dev(x), d_w, scale, parts=parts, variant=variant)
+    ref = oracle.dequant_residual(acc, scale)
+    pw = N // parts
+    for p in range(parts):
+        assert np.array_equal(host(ys[p]), ref[:, p * pw:(p + 1) * pw]), "part %d" % p
+    if parts == 1:
+        res = wl.float_activations(3, M, N)
+        ref_r = oracle.dequant_residual(acc, scale, res)
+        (y,) = sa.sa_shift_linear_f32(dev(x), d_w, scale, residual=dev(res), variant=variant)
+        assert np.array_equal(host(y), ref_r)
+        buf = dev(res)                                           # in place: the residual buffer is the output
+        sa.sa_shift_linear_f32(dev(x), d_w, scale, residual=buf, variant=variant, ys=(buf,))
+        assert np.array_equal(host(buf), ref_r)
+
+
+def test_shift_linear_f32_large_accumulators_round_once(sa):
+    """Accumulators beyond 2^24 (K = 3072, all weights +-128, activations +-127) are converted
+    round-to-nearest-even before the fused multiply-add, as the definition says."""
+    M, K, N = 64, 3072, 64
+    x = np.full((M, K), 127, dtype=np.int8)
+    x[1::2] = -127
+    x[:, ::7] = 126
+    neg = np.zeros((N, K), dtype=np.uint8)
+    neg[::3] = 1
+    w4 = wl.pack_w4(neg, np.full((N, K), 7, dtype=np.uint8))
+    acc = oracle.shift_linear(x, w4)
+    assert np.abs(acc).max() > 2**24
+    res = wl.float_activations(3, M, N)
+    ref = oracle.dequant_residual(acc, float(np.float32(1.0 + 2.0**-20)), res)
+    for variant in (0, 1):
+        (y,) = sa.sa_shift_linear_f32(dev(x), dev(w4), float(np.float32(1.0 + 2.0**-20)), residual=dev(res), variant=variant)
+        assert np.array_equal(host(y), ref)
+
+
+# ----------------------------------------------- experts adding to the output ---
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_experts_accumulate_into_the_residual_rows(sa, variant):
+    cfg = wl.scaled_down(wl.C1, B=2, N=150)
+    p = wl.mlp_params(cfg)
+    T, E = cfg.T, cfg.E
+    xq = wl.int8_activations(1, T, E)
+    x = wl.float_activations(1, T, E)
+    base = wl.float_activations(2, T, E)
+    logits = wl.router_logits(cfg)
+    perm_r, _, cnt_r, gate_r = oracle.moe_dispatch(logits)
+    rows_m, rows_s = perm_r[: cnt_r[0]], perm_r[cnt_r[0]:]
+    y_ref = base.astype(np.float64)
+    y_ref[rows_s] += gate_r[rows_s, None] * (np.float64(np.float32(p.out_scale)) *
+                                             oracle.shift_mlp(xq[rows_s], p.w1, p.w2, p.requant_scale, p.lut))
+    y_ref[rows_m] += gate_r[rows_m, None] * oracle.mult_mlp(x, rows_m, p.mw1, p.mw2)
+    perm, _, cnt, gate = sa.sa_moe_dispatch(dev(logits))
+    y = dev(base)
+    acc = sa.binding.SA_MLP_ACCUMULATE
+    sa.sa_shift_mlp(dev(xq), dev(p.w1), dev(p.w2), p.requant_scale, dev(p.lut), rows=perm, counts=cnt, expert=1,
+                    max_rows=T, want_y2=False, y=y, gate=gate, out_scale=p.out_scale, variant=variant, stages=3 | acc)
+    sa.sa_mult_mlp_f16(dev(x), dev(p.mw1), dev(p.mw2), rows=perm, counts=cnt, expert=0, max_rows=T, want_out=False,
+                       y=y, gate=gate, stages=3 | acc)
+    got = host(y)
+    assert_close(got[rows_s], y_ref[rows_s], 2e-6, 1e-6, "shift expert + residual")
+    assert_close(got[rows_m], y_ref[rows_m], 2e-3, 1e-3, "Mult expert + residual")
