@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--shift-variant", type=int, default=3, choices=[0, 1, 2, 3],
                     help="0 VALU, 1 MFMA (weights decoded per call), 2 auto, 3 MFMA on planes decoded once "
                          "before the timed region (a layout change of the constant weights)")
+    ap.add_argument("--layer", action="store_true",
+                    help="time the complete block of Eq. 2 (sa_layer_forward: LayerNorms, the four attention Linears "
+                         "as shift layers, residuals, router) on tokens of the chosen configuration's shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
@@ -126,6 +129,8 @@ def main():
     if args.config == "c3":
         return bench_shift_linear(args, sa, wl, torch, np)
     cfg = {"c1": wl.C1, "c2": wl.C2, "c4": wl.C4, "c5": wl.C5}[args.config]
+    if args.layer:
+        return bench_layer(args, sa, wl, torch, np, cfg)
     moe = cfg.E > 0 and cfg.shift_frac is not None
 
     def dev(a):
@@ -306,6 +311,165 @@ def bench_shift_linear(args, sa, wl, torch, np):
            "config": {"workload": "c3-deit-small-shift-linear", "M": M, "layers": [list(s) for s in wl.C3_SHAPES]},
            "valu_variant_ms_per_step": round(total_us[0] * 1e-3, 5), "roofline": roofline, "cpu_baseline": None,
            "kernels": rows}
+    print(json.dumps(out))
+
+
+def bench_layer(args, sa, wl, torch, np, cfg):
+    """The complete block of Eq. 2 (sa_layer_forward) and each of its kernels through the stage entry points."""
+    assert cfg.E, "--layer needs a configuration with an MLP (c1, c4, c5)"
+    T, E, H, hid = cfg.T, cfg.E, cfg.H, cfg.hid
+    moe = cfg.shift_frac is not None
+    lp, p = wl.layer_params(cfg), wl.mlp_params(cfg)
+    scale = wl.attention_scale(cfg)
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    var = args.shift_variant
+    ws_ = [dev(np.concatenate([lp.wq, lp.wk, lp.wv], axis=0)), dev(lp.wo), dev(p.w1), dev(p.w2)]
+    if var == 3:
+        ws_ = [sa.sa_shift_planes_prepare(w) for w in ws_]
+    wqkv, wo, w1, w2 = ws_
+    shared = dict(B=cfg.B, N=cfg.N, H=H, nbits=cfg.nbits, E=E, hid=hid, attention=0 if cfg.attention == "linear" else 1,
+                  moe=int(moe), shift_variant=var, eps=lp.eps, ln_inv_scale=lp.ln_inv_scale, qkv_scale=lp.qkv_scale,
+                  attn_scale=scale, act_inv_scale=p.act_inv_scale, o_scale=lp.o_scale, requant_scale=p.requant_scale,
+                  out_scale=p.out_scale, gamma1=dev(lp.gamma1), beta1=dev(lp.beta1), gamma2=dev(lp.gamma2),
+                  beta2=dev(lp.beta2), wqkv=wqkv, wo=wo, proj=dev(wl.proj(cfg)), w1=w1, w2=w2, lut=dev(p.lut))
+    if moe:
+        shared.update(wg=dev(lp.wg), bg=dev(lp.bg), mw1=dev(p.mw1), mw2=dev(p.mw2))
+    x_host = wl.layer_input(cfg)
+    n_sets = args.rotate or max(2, min(8, math.ceil(600e6 / (10 * x_host.nbytes))))
+    layers = [sa.Layer(x=dev(x_host), **shared) for _ in range(n_sets)]
+    for i in range(args.warmup):
+        layers[i % n_sets].forward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layers[i % n_sets].forward()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per kernel, through the stage entry points on one buffer set (the chain of the layer)
+    x = layers[0]._keep[0]
+    B, N, d = cfg.B, cfg.N, E // H
+    z8 = torch.empty((T, E), dtype=torch.int8, device="cuda")
+    q, k, v, x1 = (torch.empty((T, E), dtype=torch.float32, device="cuda") for _ in range(4))
+    q4, k4, v4 = (t.view(B, N, H, d) for t in (q, k, v))
+    qc = torch.empty((B, H, N, cfg.nbits // 64), dtype=torch.int64, device="cuda")
+    kc = torch.empty_like(qc)
+    lib = sa.load_library()
+    lin_ws = torch.empty(max(16, lib.sa_shift_linear_workspace_bytes(sa._l(T), E, 3 * E, var)), dtype=torch.uint8, device="cuda")
+    n_shift = int(math.floor(cfg.shift_frac * T + 0.5)) if moe else T
+    n_mult = T - n_shift
+    rows = T * H
+    code_b, v_b = rows * cfg.nbits // 8, rows * d * 4
+    stages = []
+
+    def add(name, fn, nbytes, ops, comp):
+        stages.append((name, fn, nbytes, ops, comp))
+
+    add("ln1_quant", lambda: sa.sa_layernorm_quant(x, shared["gamma1"], shared["beta1"], lp.eps, lp.ln_inv_scale,
+                                                   want_ln=False, q=z8), T * E * 5, 8 * T * E, "alu_fp32")
+    add("qkv_linear", lambda: sa.sa_shift_linear_f32(z8, wqkv, lp.qkv_scale, parts=3, variant=var, ys=(q, k, v), workspace=lin_ws),
+        T * E + 3 * E * E // 2 + 3 * T * E * 4, 2 * T * E * 3 * E, "mfma_i8")
+    add("binarize_qk", lambda: sa.sa_binarize_pair(q4, k4, shared["proj"], cfg.nbits, q_codes=qc, k_codes=kc),
+        2 * (rows * d * 4 + code_b) + d * cfg.nbits * 4, 4 * rows * cfg.nbits * d, "mfma_bf16x3")
+    o = torch.empty((B, N, H, d), dtype=torch.float32, device="cuda")
+    if cfg.attention == "linear":
+        kv = torch.empty((B, H, cfg.nbits, d), dtype=torch.float32, device="cuda")
+        aws = torch.empty(max(16, lib.sa_additive_attention_workspace_bytes(B, H, N, cfg.nbits, d)), dtype=torch.uint8, device="cuda")
+        kv_b = B * H * cfg.nbits * d * 4
+        add("ktv", lambda: sa.sa_additive_attention(None, kc, v4, scale, cfg.nbits, phases=1, kv=kv, workspace=aws),
+            code_b + v_b + kv_b, 2 * rows * cfg.nbits * d, "mfma_bf16x3")
+        add("qkv", lambda: sa.sa_additive_attention(qc, None, None, scale, cfg.nbits, phases=2, kv=kv, out=o, workspace=aws),
+            code_b + v_b + kv_b, 2 * rows * cfg.nbits * d, "mfma_bf16x3")
+        add("quantize", lambda: sa.sa_quantize_act(o.view(T, E), p.act_inv_scale, q=z8), T * E * 5, 2 * T * E, "alu_fp32")
+    else:
+        add("hamming", lambda: sa.sa_hamming_attention_fused(qc, kc, v4, scale, cfg.nbits, p.act_inv_scale, out=o, xq=z8, want_xh=False),
+            2 * code_b + 2 * v_b + T * E, 2 * B * H * N * N * d, "mfma_bf16x3")
+    add("o_linear", lambda: sa.sa_shift_linear_f32(z8, wo, lp.o_scale, residual=x, variant=var, ys=(x1,), workspace=lin_ws),
+        T * E + E * E // 2 + 2 * T * E * 4, 2 * T * E * E, "mfma_i8")
+    xh = torch.empty((T, E), dtype=torch.float16, device="cuda") if moe else None
+    logits = torch.empty((T, 2), dtype=torch.float32, device="cuda") if moe else None
+    add("ln2_quant_router", lambda: sa.sa_layernorm_quant(x1, shared["gamma2"], shared["beta2"], lp.eps, lp.ln_inv_scale,
+                                                          want_ln=False, q=z8, xh=xh, wg=shared.get("wg"),
+                                                          bg=shared.get("bg"), logits=logits),
+        T * E * (5 + (2 if moe else 0)) + (T * 8 if moe else 0), (8 + (4 if moe else 0)) * T * E, "alu_fp32")
+    acc = sa.SA_MLP_ACCUMULATE
+    sws = torch.empty(max(16, lib.sa_shift_mlp_workspace_bytes(sa._l(T), E, hid)), dtype=torch.uint8, device="cuda")
+    if moe:
+        disp = None
+        perm = torch.empty(T, dtype=torch.int32, device="cuda")
+        eo = torch.empty(T, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(4, dtype=torch.int32, device="cuda")[:2]
+        gate = torch.empty(T, dtype=torch.float32, device="cuda")
+        dws = torch.empty(max(16, lib.sa_moe_dispatch_workspace_bytes(sa._l(T), 2)), dtype=torch.uint8, device="cuda")
+        mws = torch.empty(max(16, lib.sa_mult_mlp_workspace_bytes(sa._l(T), E, hid)), dtype=torch.uint8, device="cuda")
+        add("dispatch", lambda: sa.sa_moe_dispatch(logits, out=(perm, eo, cnt, gate), workspace=dws), T * 20, 4 * T, "alu_fp32")
+        for st_, nm in ((1, "mult_fc1"), (2 | acc, "mult_fc2")):
+            add(nm, (lambda st_=st_: sa.sa_mult_mlp_f16_half(xh, shared["mw1"], shared["mw2"], rows=perm, counts=cnt, expert=0,
+                                                            max_rows=T, want_out=False, y=x1, gate=gate, stages=st_, workspace=mws)),
+                n_mult * E * 2 + E * hid * 2 + n_mult * hid * 2 + (n_mult * E * 6 if st_ != 1 else 0), 2 * n_mult * E * hid, "mfma_f16")
+        sel = dict(rows=perm, counts=cnt, expert=1, max_rows=T, gate=gate)
+    else:
+        sel = {}
+    for st_, nm in ((1, "shift_fc1"), (2 | acc, "shift_fc2")):
+        add(nm, (lambda st_=st_: sa.sa_shift_mlp(z8, w1, w2, p.requant_scale, shared["lut"], want_y2=False, y=x1,
+                                                out_scale=p.out_scale, variant=var, stages=st_, workspace=sws, **sel)),
+            n_shift * (E + hid) + E * hid // 2 + (n_shift * E * 7 if st_ != 1 else 0), 2 * n_shift * E * hid, "mfma_i8")
+
+    report = []
+    for name, fn, nbytes, ops, comp in stages:
+        fn()
+        us = None
+        if not args.no_kernels:
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.steps
+        t_hbm, t_cmp = nbytes / (HBM_PEAK_GBS * 1e9) * 1e6, ops / (PEAK_TFLOPS[comp] * 1e12) * 1e6
+        row = dict(name=name, us=None if us is None else round(us, 2), bytes=nbytes, ops=ops, hbm_floor_us=round(t_hbm, 2),
+                   compute_floor_us=round(t_cmp, 2), bound="hbm" if t_hbm >= t_cmp else ("mfma" if comp.startswith("mfma") else "alu"),
+                   compute_peak=comp)
+        if us:
+            row.update(hbm_frac=round(t_hbm / us, 4), binding_frac=round(max(t_hbm, t_cmp) / us, 4))
+        report.append(row)
+    roofline = None
+    timed = [r for r in report if r["us"]]
+    if timed:
+        dom = max(timed, key=lambda r: r["us"])
+        if dom["bound"] == "hbm":
+            ach, peak, unit = dom["bytes"] / (dom["us"] * 1e-6) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = dom["ops"] / (dom["us"] * 1e-6) / 1e12, PEAK_TFLOPS[dom["compute_peak"]], "TFLOP/s"
+        roofline = dict(kernel=dom["name"], bound=dom["bound"], achieved=round(ach, 3), peak=peak, unit=unit,
+                        frac=round(ach / peak, 4), traffic=None, us_per_launch=dom["us"])
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        bs = args.cpu_sample_batch or {1: 1, 4: 16, 5: 1}.get(cfg.cfg_id, 1)
+        small = wl.scaled_down(cfg, B=min(bs, cfg.B))
+        xs = x_host[: small.T]
+        t0 = time.perf_counter()
+        oracle.layer_forward(small, xs, lp, p, wl.proj(cfg), scale)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(small.T / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%d of %d batch items (%d tokens), one pass of oracle.layer_forward" % (small.B, cfg.B, small.T)}
+    layer_bytes = sum(r["bytes"] for r in report)
+    out = {"metric": "layer tokens/s (complete block of Eq. 2: LayerNorms, shift Linears, attention, MoE, residuals) at 1 GPU; % HBM roofline",
+           "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32+u64 codes+i8/i32 shift+f16 mult", "data": "synthetic",
+           "config": {"workload": cfg.name.replace("block", "layer"), "B": cfg.B, "N": cfg.N, "H": H, "nbits": cfg.nbits, "E": E,
+                      "hid": hid, "attention": cfg.attention, "mlp": "moe" if moe else "shift", "input_sets_rotated": n_sets,
+                      "shift_variant": var},
+           "layer_hbm_roofline_frac": round(layer_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
+           "layer_algorithmic_bytes": layer_bytes, "roofline": roofline, "cpu_baseline": cpu, "kernels": report}
     print(json.dumps(out))
 
 

@@ -309,6 +309,50 @@ typedef struct sa_block_desc {
 size_t sa_block_workspace_bytes(const sa_block_desc *desc /* host */);
 int sa_block_forward(const sa_block_desc *desc /* host */, void *stream);
 
+/*
+ * The complete block of Eq. 2 on tokens x [T, E] fp32, T = B * N:
+ *   z1 = int8(LayerNorm1(x))                          sa_layernorm_quant
+ *   Q, K, V = qkv_scale * ShiftLinear(z1, wqkv)       one launch, rows of wqkv = Wq, Wk, Wv stacked
+ *   O = attention(binarize(Q), binarize(K), V)        heads are column blocks of width E / H
+ *   x1 = fma(ShiftLinear(int8(O), wo), o_scale, x)    residual, Eq. 2 (left)
+ *   z2 = LayerNorm2(x1): int8, fp16, router logits z2 * wg + bg
+ *   y  = x1 + MoE{Mult, Shift}(z2)  or  x1 + ShiftMLP(z2)        Eq. 2 (right)
+ * The four attention Linears are shift layers (Sec. 4.1); all scales are static
+ * and passed in.  Weights follow shift_variant (packed 4-bit rows, or planes
+ * from sa_shift_planes_prepare for SA_VARIANT_MFMA_PREPARED; wqkv as one
+ * [3E, E] matrix).  E % 64 == 0, hid % 64 == 0, E / H in {32, 64, 128} for the
+ * Hamming variant.  y must not overlap x.
+ */
+typedef struct sa_layer_desc {
+    int B, N, H, nbits;
+    int E, hid;
+    int attention;          /* 0 = linear additive, 1 = quadratic Hamming            */
+    int moe;                /* 1 = router + two experts, 0 = Shift MLP for all rows  */
+    int shift_variant;      /* SA_VARIANT_*                                          */
+    float eps;              /* both LayerNorms                                       */
+    float ln_inv_scale;     /* LayerNorm output -> int8                              */
+    float qkv_scale;        /* int32 accumulator -> fp32 Q, K, V                     */
+    float attn_scale;
+    float act_inv_scale;    /* attention output -> int8                              */
+    float o_scale;          /* int32 accumulator of the output projection -> fp32    */
+    float requant_scale, out_scale;              /* Shift expert                     */
+    const float *x;         /* [T, E]                                                */
+    const float *gamma1, *beta1, *gamma2, *beta2; /* [E] each                        */
+    const uint8_t *wqkv;    /* [3E, E/2] packed (or planes of the [3E, E] matrix)    */
+    const uint8_t *wo;      /* [E, E/2]                                              */
+    const float *proj;      /* [E/H, nbits] or NULL (then nbits == E/H)              */
+    const float *wg, *bg;   /* router [E, 2], [2] (moe == 1)                         */
+    const uint8_t *w1, *w2; /* Shift expert                                          */
+    const int8_t *lut;      /* [256]                                                 */
+    const void *mw1, *mw2;  /* Mult expert fp16 (moe == 1)                           */
+    float *y;               /* [T, E] block output                                   */
+    void *workspace;
+    size_t workspace_bytes;
+} sa_layer_desc;
+
+size_t sa_layer_workspace_bytes(const sa_layer_desc *desc /* host */);
+int sa_layer_forward(const sa_layer_desc *desc /* host */, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
-    "sa_block_forward",
+    "sa_block_forward", "sa_layer_workspace_bytes", "sa_layer_forward",
 ]
 
 
@@ -51,6 +51,18 @@ class SaBlockDesc(ctypes.Structure):
                [("workspace_bytes", ctypes.c_size_t)]
 
 
+class SaLayerDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("B", "N", "H", "nbits", "E", "hid", "attention", "moe", "shift_variant")] + \
+               [(n, ctypes.c_float) for n in
+                ("eps", "ln_inv_scale", "qkv_scale", "attn_scale", "act_inv_scale", "o_scale", "requant_scale",
+                 "out_scale")] + \
+               [(n, ctypes.c_void_p) for n in
+                ("x", "gamma1", "beta1", "gamma2", "beta2", "wqkv", "wo", "proj", "wg", "bg", "w1", "w2", "lut",
+                 "mw1", "mw2", "y", "workspace")] + \
+               [("workspace_bytes", ctypes.c_size_t)]
+
+
 def load_library():
     """Load the in-tree library; raises if it has not been built."""
     global _lib, LIB_PATH
@@ -65,7 +77,7 @@ def load_library():
         for name in ("sa_additive_attention_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
                      "sa_shift_linear_workspace_bytes", "sa_shift_planes_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
-                     "sa_block_workspace_bytes"):
+                     "sa_block_workspace_bytes", "sa_layer_workspace_bytes"):
             getattr(lib, name).restype = ctypes.c_size_t
         _lib = lib
     return _lib
@@ -233,15 +245,19 @@ def sa_shift_linear_f32(x, w4, scale, residual=None, parts=1, variant=SA_VARIANT
 
 
 def sa_layernorm_quant(x, gamma, beta, eps, inv_scale=1.0, want_ln=True, want_q=False, want_half=False,
-                       wg=None, bg=None):
-    """Returns (ln, q, xh, logits); entries not asked for are None."""
+                       wg=None, bg=None, ln=None, q=None, xh=None, logits=None):
+    """Returns (ln, q, xh, logits); entries not asked for (want_* false and no buffer given) are None."""
     T, E = x.shape
     dev = x.device
-    ln = torch.empty((T, E), dtype=torch.float32, device=dev) if want_ln else None
-    q = torch.empty((T, E), dtype=torch.int8, device=dev) if want_q else None
-    xh = torch.empty((T, E), dtype=torch.float16, device=dev) if want_half else None
+    if ln is None and want_ln:
+        ln = torch.empty((T, E), dtype=torch.float32, device=dev)
+    if q is None and want_q:
+        q = torch.empty((T, E), dtype=torch.int8, device=dev)
+    if xh is None and want_half:
+        xh = torch.empty((T, E), dtype=torch.float16, device=dev)
     n_exp = 0 if wg is None else wg.shape[1]
-    logits = torch.empty((T, n_exp), dtype=torch.float32, device=dev) if wg is not None else None
+    if logits is None and wg is not None:
+        logits = torch.empty((T, n_exp), dtype=torch.float32, device=dev)
     _check(load_library().sa_layernorm_quant(_ptr(x), _l(T), E, _ptr(gamma), _ptr(beta), _f(eps), _f(inv_scale),
                                              _ptr(ln), _ptr(q), _ptr(xh), _ptr(wg), _ptr(bg), n_exp, _ptr(logits),
                                              _stream()))
@@ -393,3 +409,39 @@ class Block:
     def forward(self):
         _check(load_library().sa_block_forward(ctypes.byref(self.desc), _stream()))
         return self.o, self.y
+
+
+class Layer:
+    """Descriptor and workspace of one complete block (Eq. 2); forward() enqueues it and returns y."""
+
+    _INTS = ("B", "N", "H", "nbits", "E", "hid", "attention", "moe", "shift_variant")
+    _FLOATS = ("eps", "ln_inv_scale", "qkv_scale", "attn_scale", "act_inv_scale", "o_scale", "requant_scale",
+               "out_scale")
+    _TENSORS = ("x", "gamma1", "beta1", "gamma2", "beta2", "wqkv", "wo", "proj", "wg", "bg", "w1", "w2", "lut",
+                "mw1", "mw2")
+
+    def __init__(self, **kw):
+        lib = load_library()
+        d_ = SaLayerDesc()
+        for n in self._INTS:
+            setattr(d_, n, int(kw.get(n, 0)))
+        for n in self._FLOATS:
+            setattr(d_, n, float(kw.get(n, 1.0)))
+        self._keep = [kw.get(n) for n in self._TENSORS]
+        for n in self._TENSORS:
+            t = kw.get(n)
+            setattr(d_, n, None if t is None else t.data_ptr())
+        x = kw["x"]
+        self.y = torch.empty_like(x)
+        d_.y = self.y.data_ptr()
+        nbytes = lib.sa_layer_workspace_bytes(ctypes.byref(d_))
+        if nbytes == 0:
+            _check(lib.sa_layer_forward(ctypes.byref(d_), _stream()))    # raises with the reason
+        self.ws = _workspace(nbytes, x.device)
+        d_.workspace = self.ws.data_ptr()
+        d_.workspace_bytes = self.ws.numel()
+        self.desc = d_
+
+    def forward(self):
+        _check(load_library().sa_layer_forward(ctypes.byref(self.desc), _stream()))
+        return self.y

@@ -194,3 +194,157 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     SA_HIP(hipStreamWaitEvent(main_st, lane->joined, 0));     // the caller's stream sees both experts done
     return SA_OK;
 }
+
+// ---------------------------------------------------------------------------------------
+// sa_layer_forward: the complete block of Eq. 2.  LayerNorm -> int8 -> fused Q/K/V shift
+// Linear -> hash -> attention -> int8 -> output shift Linear + residual -> LayerNorm (int8,
+// fp16 and router logits in one pass) -> dispatch -> experts adding into the residual rows.
+namespace {
+
+struct LayerLayout {
+    size_t codes8, q, k, v, qc, kc, kv, attn_ws, xh, logits, perm, expert_of, counts, gate, disp_ws, shift_ws,
+        mult_ws, lin_ws, total;
+    size_t attn_ws_bytes, disp_ws_bytes, shift_ws_bytes, mult_ws_bytes, lin_ws_bytes;
+};
+
+int plan_layer(const sa_layer_desc *d, LayerLayout *L) {
+    SA_REQUIRE(d != nullptr, SA_ERR_INVALID, "layer: descriptor is NULL");
+    SA_REQUIRE(d->B > 0 && d->N > 0 && d->H > 0 && d->nbits > 0 && d->E > 0 && d->hid > 0, SA_ERR_INVALID,
+               "layer: sizes must be positive");
+    SA_REQUIRE(d->E % d->H == 0, SA_ERR_SHAPE, "layer: E (%d) is not a multiple of H (%d)", d->E, d->H);
+    SA_REQUIRE(d->E % 64 == 0 && d->hid % 64 == 0, SA_ERR_SHAPE, "layer: E and hid must be multiples of 64");
+    SA_REQUIRE(d->nbits % 64 == 0, SA_ERR_SHAPE, "layer: nbits must be a multiple of 64");
+    SA_REQUIRE(d->attention == 0 || d->attention == 1, SA_ERR_INVALID, "layer: attention must be 0 or 1");
+    SA_REQUIRE(d->shift_variant >= 0 && d->shift_variant <= 3, SA_ERR_INVALID, "layer: unknown shift variant");
+    const size_t T = (size_t)d->B * d->N, E = (size_t)d->E;
+    const int dv = d->E / d->H;
+    SA_REQUIRE(T < (size_t)65535 * 8, SA_ERR_SHAPE, "layer: too many tokens for one call");
+    size_t off = 0;
+    L->codes8 = off; off += up(T * E);
+    L->q = off; off += up(T * E * 4);
+    L->k = off; off += up(T * E * 4);
+    L->v = off; off += up(T * E * 4);
+    const size_t code_bytes = up(T * d->H * (d->nbits / 64) * 8);
+    L->qc = off; off += code_bytes;
+    L->kc = off; off += code_bytes;
+    L->kv = off;
+    L->attn_ws_bytes = 0;
+    if (d->attention == 0) {
+        off += up((size_t)d->B * d->H * d->nbits * dv * 4);
+        L->attn_ws_bytes = sa_additive_attention_workspace_bytes(d->B, d->H, d->N, d->nbits, dv);
+    }
+    L->attn_ws = off; off += up(L->attn_ws_bytes);
+    L->shift_ws_bytes = sa_shift_mlp_workspace_bytes((long)T, d->E, d->hid);
+    L->shift_ws = off; off += up(L->shift_ws_bytes);
+    const size_t lin_qkv = sa_shift_linear_workspace_bytes((long)T, d->E, 3 * d->E, d->shift_variant);
+    const size_t lin_o = sa_shift_linear_workspace_bytes((long)T, d->E, d->E, d->shift_variant);
+    L->lin_ws_bytes = lin_qkv > lin_o ? lin_qkv : lin_o;
+    L->lin_ws = off; off += up(L->lin_ws_bytes);
+    L->xh = L->logits = L->perm = L->expert_of = L->counts = L->gate = L->disp_ws = L->mult_ws = off;
+    L->disp_ws_bytes = L->mult_ws_bytes = 0;
+    if (d->moe) {
+        L->xh = off; off += up(T * E * 2);
+        L->logits = off; off += up(T * 2 * 4);
+        L->perm = off; off += up(T * 4);
+        L->expert_of = off; off += up(T * 4);
+        L->counts = off; off += 256;
+        L->gate = off; off += up(T * 4);
+        L->disp_ws_bytes = sa_moe_dispatch_workspace_bytes((long)T, 2);
+        L->disp_ws = off; off += up(L->disp_ws_bytes);
+        L->mult_ws_bytes = sa_mult_mlp_workspace_bytes((long)T, d->E, d->hid);
+        L->mult_ws = off; off += up(L->mult_ws_bytes);
+    }
+    L->total = off;
+    return SA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t sa_layer_workspace_bytes(const sa_layer_desc *desc) {
+    LayerLayout L;
+    if (plan_layer(desc, &L) != SA_OK) return 0;
+    return L.total;
+}
+
+extern "C" int sa_layer_forward(const sa_layer_desc *d, void *stream) {
+    sa::clear_error();
+    LayerLayout L;
+    int rc = plan_layer(d, &L);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(d->x && d->y && d->gamma1 && d->beta1 && d->gamma2 && d->beta2 && d->wqkv && d->wo && d->w1 && d->w2 &&
+                   d->lut,
+               SA_ERR_INVALID, "layer: x, y, the LayerNorm parameters, wqkv, wo, w1, w2 and lut are required");
+    if (d->moe) SA_REQUIRE(d->wg && d->bg && d->mw1 && d->mw2, SA_ERR_INVALID, "layer: wg, bg, mw1, mw2 are required");
+    SA_REQUIRE(d->workspace != nullptr && d->workspace_bytes >= L.total, SA_ERR_WORKSPACE,
+               "layer: workspace of %zu bytes needed, %zu given", L.total, d->workspace_bytes);
+    SA_REQUIRE(sa::aligned16(d->workspace), SA_ERR_ALIGN, "layer: workspace must be 16-byte aligned");
+    uint8_t *ws = static_cast<uint8_t *>(d->workspace);
+    const long T = (long)d->B * d->N;
+    const int E = d->E, dv = d->E / d->H;
+    int8_t *codes8 = reinterpret_cast<int8_t *>(ws + L.codes8);
+    float *q = reinterpret_cast<float *>(ws + L.q), *k = reinterpret_cast<float *>(ws + L.k);
+    float *v = reinterpret_cast<float *>(ws + L.v);
+    float *o = q;                                 // Q is dead once it is hashed
+    uint64_t *qc = reinterpret_cast<uint64_t *>(ws + L.qc), *kc = reinterpret_cast<uint64_t *>(ws + L.kc);
+    hipStream_t main_st = sa::as_stream(stream);
+
+    // attention half: X_attn = Attn(LayerNorm(X)) + X, left in y
+    rc = sa_layernorm_quant(d->x, T, E, d->gamma1, d->beta1, d->eps, d->ln_inv_scale, nullptr, codes8, nullptr, nullptr,
+                            nullptr, 0, nullptr, stream);
+    if (rc != SA_OK) return rc;
+    rc = sa_shift_linear_f32(codes8, d->wqkv, T, E, 3 * E, d->shift_variant, d->qkv_scale, nullptr, 3, q, k, v,
+                             ws + L.lin_ws, L.lin_ws_bytes, stream);
+    if (rc != SA_OK) return rc;
+    rc = sa_binarize_pair(q, k, d->B, d->N, d->H, dv, d->proj, d->nbits, qc, kc, stream);
+    if (rc != SA_OK) return rc;
+    if (d->attention == 0) {
+        rc = sa_additive_attention(qc, kc, v, o, d->B, d->H, d->N, d->N, d->nbits, dv, d->attn_scale,
+                                   reinterpret_cast<float *>(ws + L.kv), 3, ws + L.attn_ws, L.attn_ws_bytes, stream);
+        if (rc == SA_OK) rc = sa_quantize_act(o, T * E, d->act_inv_scale, codes8, stream);
+    } else {
+        rc = sa_hamming_attention_fused(qc, kc, v, o, d->B, d->H, d->N, d->N, d->nbits, dv, d->attn_scale, nullptr,
+                                         codes8, nullptr, d->act_inv_scale, SA_VARIANT_AUTO, stream);
+    }
+    if (rc != SA_OK) return rc;
+    rc = sa_shift_linear_f32(codes8, d->wo, T, E, E, d->shift_variant, d->o_scale, d->x, 1, d->y, nullptr, nullptr,
+                             ws + L.lin_ws, L.lin_ws_bytes, stream);
+    if (rc != SA_OK) return rc;
+
+    // MLP half: y += MLP(LayerNorm(y)); every row is read by the LayerNorm before an expert adds to it
+    const bool moe = d->moe != 0;
+    void *xh = moe ? static_cast<void *>(ws + L.xh) : nullptr;
+    float *logits = moe ? reinterpret_cast<float *>(ws + L.logits) : nullptr;
+    rc = sa_layernorm_quant(d->y, T, E, d->gamma2, d->beta2, d->eps, d->ln_inv_scale, nullptr, codes8, xh,
+                            moe ? d->wg : nullptr, moe ? d->bg : nullptr, moe ? 2 : 0, logits, stream);
+    if (rc != SA_OK) return rc;
+    if (!moe) {
+        const sa_rows all{nullptr, nullptr, 0, T};
+        return sa_shift_mlp(codes8, &all, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, nullptr,
+                            d->out_scale, d->shift_variant, 3 | SA_MLP_ACCUMULATE, ws + L.shift_ws, L.shift_ws_bytes,
+                            stream);
+    }
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
+    int32_t *expert_of = reinterpret_cast<int32_t *>(ws + L.expert_of);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
+    float *gate = reinterpret_cast<float *>(ws + L.gate);
+    rc = sa_moe_dispatch(logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes, stream);
+    if (rc != SA_OK) return rc;
+    // the Mult expert on the side lane, the Shift expert on the caller's stream; they add to disjoint rows of y
+    SideLane *lane = nullptr;
+    std::lock_guard<std::mutex> lock(g_lane_mutex);
+    rc = side_lane(&lane);
+    if (rc != SA_OK) return rc;
+    SA_HIP(hipEventRecord(lane->routed, main_st));
+    SA_HIP(hipStreamWaitEvent(lane->stream, lane->routed, 0));
+    const sa_rows mult_rows{perm, counts, 0, T};
+    rc = sa_mult_mlp_f16_half(xh, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3 | SA_MLP_ACCUMULATE,
+                              ws + L.mult_ws, L.mult_ws_bytes, lane->stream);
+    if (rc != SA_OK) return rc;
+    SA_HIP(hipEventRecord(lane->joined, lane->stream));
+    const sa_rows shift_rows{perm, counts, 1, T};
+    rc = sa_shift_mlp(codes8, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
+                      d->out_scale, d->shift_variant, 3 | SA_MLP_ACCUMULATE, ws + L.shift_ws, L.shift_ws_bytes, stream);
+    if (rc != SA_OK) return rc;
+    SA_HIP(hipStreamWaitEvent(main_st, lane->joined, 0));
+    return SA_OK;
+}

@@ -37,83 +37,120 @@ struct LnArgs {
     float *logits;      // [T, n_exp]
 };
 
-template <int CH>
-__global__ __launch_bounds__(64 * kRowsPerBlock) void layernorm_kernel(LnArgs a) {
+// ROUTE: the router has two experts and its weight columns live in registers next to gamma and
+// beta (all three depend on the column only), so a wavefront that walks over several rows loads
+// them once.  More experts take the weights from memory (the table is small and stays in cache).
+template <int CH, bool ROUTE2>
+__global__ __launch_bounds__(64 * kRowsPerBlock) void layernorm_kernel(LnArgs a, int rows_per_wave) {
     const int lane = threadIdx.x & 63;
-    const long t = (long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-    if (t >= a.T) return;
     const int E = a.E;
-    const float *row = a.x + (size_t)t * E;
-    float4 v[CH];
-    float s = 0.0f;
+    const long t0 = ((long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6)) * rows_per_wave;
+    if (t0 >= a.T) return;
+    constexpr bool CACHE = CH <= 8;               // wider rows re-read gamma and beta per row (registers)
+    constexpr int PC = CACHE ? CH : 1;
+    float4 gm[PC], bt[PC], w0[PC], w1[PC];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
+    for (int c = 0; c < PC; ++c) {
         const int j = (c * 64 + lane) * 4;
-        v[c] = j < E ? *reinterpret_cast<const float4 *>(row + j) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        s += (v[c].x + v[c].y) + (v[c].z + v[c].w);
-    }
-    const float mean = wave_sum(s) / (float)E;
-    float ss = 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const int j = (c * 64 + lane) * 4;
-        if (j < E) {
-            const float d0 = v[c].x - mean, d1 = v[c].y - mean, d2 = v[c].z - mean, d3 = v[c].w - mean;
-            ss += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+        const bool in = j < E;
+        gm[c] = in ? *reinterpret_cast<const float4 *>(a.gamma + j) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        bt[c] = in ? *reinterpret_cast<const float4 *>(a.beta + j) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (ROUTE2) {                             // wg rows j..j+3: (e0, e1) pairs
+            w0[c] = in ? *reinterpret_cast<const float4 *>(a.wg + 2 * j) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            w1[c] = in ? *reinterpret_cast<const float4 *>(a.wg + 2 * j + 4) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         }
     }
-    const float rstd = 1.0f / __builtin_sqrtf(wave_sum(ss) / (float)E + a.eps);
-    float part[kMaxExperts];
+    const long t_end = t0 + rows_per_wave < a.T ? t0 + rows_per_wave : a.T;
+    for (long t = t0; t < t_end; ++t) {
+        const float *row = a.x + (size_t)t * E;
+        float4 v[CH];
+        float s = 0.0f;
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) part[e] = 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const int j = (c * 64 + lane) * 4;
-        if (j >= E) continue;
-        const float4 g = *reinterpret_cast<const float4 *>(a.gamma + j);
-        const float4 b = *reinterpret_cast<const float4 *>(a.beta + j);
-        float y[4];
-        y[0] = (v[c].x - mean) * rstd * g.x + b.x;
-        y[1] = (v[c].y - mean) * rstd * g.y + b.y;
-        y[2] = (v[c].z - mean) * rstd * g.z + b.z;
-        y[3] = (v[c].w - mean) * rstd * g.w + b.w;
-        const size_t o = (size_t)t * E + j;
-        if (a.ln) *reinterpret_cast<float4 *>(a.ln + o) = make_float4(y[0], y[1], y[2], y[3]);
-        if (a.q) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) w |= (uint32_t)(uint8_t)requant_code(y[i] * a.inv_scale) << (8 * i);
-            *reinterpret_cast<uint32_t *>(a.q + o) = w;
+        for (int c = 0; c < CH; ++c) {
+            const int j = (c * 64 + lane) * 4;
+            v[c] = j < E ? *reinterpret_cast<const float4 *>(row + j) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            s += (v[c].x + v[c].y) + (v[c].z + v[c].w);
         }
-        if (a.xh) {
-            v4h_t h;
+        const float mean = wave_sum(s) / (float)E;
+        float ss = 0.0f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[i] = (_Float16)y[i];
-            *reinterpret_cast<v4h_t *>(a.xh + o) = h;
+        for (int c = 0; c < CH; ++c) {
+            const int j = (c * 64 + lane) * 4;
+            if (j < E) {
+                const float d0 = v[c].x - mean, d1 = v[c].y - mean, d2 = v[c].z - mean, d3 = v[c].w - mean;
+                ss += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+        }
+        const float rstd = 1.0f / __builtin_sqrtf(wave_sum(ss) / (float)E + a.eps);
+        float part[kMaxExperts];
+#pragma unroll
+        for (int e = 0; e < kMaxExperts; ++e) part[e] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int j = (c * 64 + lane) * 4;
+            if (j >= E) continue;
+            const float4 g = CACHE ? gm[CACHE ? c : 0] : *reinterpret_cast<const float4 *>(a.gamma + j);
+            const float4 b = CACHE ? bt[CACHE ? c : 0] : *reinterpret_cast<const float4 *>(a.beta + j);
+            float y[4];
+            y[0] = (v[c].x - mean) * rstd * g.x + b.x;
+            y[1] = (v[c].y - mean) * rstd * g.y + b.y;
+            y[2] = (v[c].z - mean) * rstd * g.z + b.z;
+            y[3] = (v[c].w - mean) * rstd * g.w + b.w;
+            const size_t o = (size_t)t * E + j;
+            if (a.ln) *reinterpret_cast<float4 *>(a.ln + o) = make_float4(y[0], y[1], y[2], y[3]);
+            if (a.q) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w |= (uint32_t)(uint8_t)requant_code(y[i] * a.inv_scale) << (8 * i);
+                *reinterpret_cast<uint32_t *>(a.q + o) = w;
+            }
+            if (a.xh) {
+                v4h_t h;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) h[i] = (_Float16)y[i];
+                *reinterpret_cast<v4h_t *>(a.xh + o) = h;
+            }
+            if (ROUTE2 && CACHE) {
+                part[0] = __builtin_fmaf(y[0], w0[c].x, part[0]);
+                part[1] = __builtin_fmaf(y[0], w0[c].y, part[1]);
+                part[0] = __builtin_fmaf(y[1], w0[c].z, part[0]);
+                part[1] = __builtin_fmaf(y[1], w0[c].w, part[1]);
+                part[0] = __builtin_fmaf(y[2], w1[c].x, part[0]);
+                part[1] = __builtin_fmaf(y[2], w1[c].y, part[1]);
+                part[0] = __builtin_fmaf(y[3], w1[c].z, part[0]);
+                part[1] = __builtin_fmaf(y[3], w1[c].w, part[1]);
+            } else if (a.logits) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int e = 0; e < kMaxExperts; ++e)
+                        if (e < a.n_exp) part[e] = __builtin_fmaf(y[i], a.wg[(size_t)(j + i) * a.n_exp + e], part[e]);
+            }
         }
         if (a.logits) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int e = 0; e < kMaxExperts; ++e)
-                    if (e < a.n_exp) part[e] = __builtin_fmaf(y[i], a.wg[(size_t)(j + i) * a.n_exp + e], part[e]);
-        }
-    }
-    if (a.logits) {
-#pragma unroll
-        for (int e = 0; e < kMaxExperts; ++e) {
-            if (e >= a.n_exp) break;
-            const float sum = wave_sum(part[e]);
-            if (lane == 0) a.logits[(size_t)t * a.n_exp + e] = sum + a.bg[e];
+            for (int e = 0; e < kMaxExperts; ++e) {
+                if (e >= a.n_exp) break;
+                const float sum = wave_sum(part[e]);
+                if (lane == 0) a.logits[(size_t)t * a.n_exp + e] = sum + a.bg[e];
+            }
         }
     }
 }
 
 template <int CH>
 int launch(const LnArgs &a, hipStream_t st) {
-    const long blocks = (a.T + kRowsPerBlock - 1) / kRowsPerBlock;
+    // a few rows per wavefront amortise the per-column parameters; keep >= ~2000 wavefronts in flight
+    int rows_per_wave = 1;
+    while (rows_per_wave < 8 && a.T / (2 * rows_per_wave) >= 2048) rows_per_wave *= 2;
+    const long waves = (a.T + rows_per_wave - 1) / rows_per_wave;
+    const long blocks = (waves + kRowsPerBlock - 1) / kRowsPerBlock;
     SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_layernorm_quant: too many rows");
-    layernorm_kernel<CH><<<dim3((unsigned)blocks), dim3(64 * kRowsPerBlock), 0, st>>>(a);
+    const dim3 grid((unsigned)blocks), block(64 * kRowsPerBlock);
+    if (a.logits && a.n_exp == 2 && CH <= 8)
+        layernorm_kernel<CH, true><<<grid, block, 0, st>>>(a, rows_per_wave);
+    else
+        layernorm_kernel<CH, false><<<grid, block, 0, st>>>(a, rows_per_wave);
     return check_launch("sa_layernorm_quant");
 }
 

@@ -135,3 +135,99 @@ def test_experts_accumulate_into_the_residual_rows(sa, variant):
     got = host(y)
     assert_close(got[rows_s], y_ref[rows_s], 2e-6, 1e-6, "shift expert + residual")
     assert_close(got[rows_m], y_ref[rows_m], 2e-3, 1e-3, "Mult expert + residual")
+
+
+# ------------------------------------------------------------ the whole layer ---
+
+def layer_kwargs(sa, cfg, x, lp, p, proj, scale, prepared=False):
+    wqkv = dev(np.concatenate([lp.wq, lp.wk, lp.wv], axis=0))
+    wo, w1, w2 = dev(lp.wo), dev(p.w1), dev(p.w2)
+    variant = 1
+    if prepared:
+        wqkv, wo, w1, w2 = (sa.sa_shift_planes_prepare(w) for w in (wqkv, wo, w1, w2))
+        variant = 3
+    moe = lp.wg is not None
+    kw = dict(B=cfg.B, N=cfg.N, H=cfg.H, nbits=cfg.nbits, E=cfg.E, hid=cfg.hid,
+              attention=0 if cfg.attention == "linear" else 1, moe=int(moe), shift_variant=variant, eps=lp.eps,
+              ln_inv_scale=lp.ln_inv_scale, qkv_scale=lp.qkv_scale, attn_scale=scale, act_inv_scale=p.act_inv_scale,
+              o_scale=lp.o_scale, requant_scale=p.requant_scale, out_scale=p.out_scale, x=dev(x),
+              gamma1=dev(lp.gamma1), beta1=dev(lp.beta1), gamma2=dev(lp.gamma2), beta2=dev(lp.beta2), wqkv=wqkv, wo=wo,
+              proj=None if proj is None else dev(proj), w1=w1, w2=w2, lut=dev(p.lut))
+    if moe:
+        kw.update(wg=dev(lp.wg), bg=dev(lp.bg), mw1=dev(p.mw1), mw2=dev(p.mw2))
+    return kw
+
+
+def chain_entry_points(sa, cfg, kw):
+    """The same layer as a chain of the library's stage entry points (all on the GPU)."""
+    T, E, H = cfg.T, cfg.E, cfg.H
+    var = kw["shift_variant"]
+    _, z1q, _, _ = sa.sa_layernorm_quant(kw["x"], kw["gamma1"], kw["beta1"], kw["eps"], kw["ln_inv_scale"],
+                                         want_ln=False, want_q=True)
+    q, k, v = sa.sa_shift_linear_f32(z1q, kw["wqkv"], kw["qkv_scale"], parts=3, variant=var)
+    q4, k4, v4 = (t.view(cfg.B, cfg.N, H, E // H) for t in (q, k, v))
+    qc, kc = sa.sa_binarize_pair(q4, k4, kw["proj"], cfg.nbits)
+    if cfg.attention == "linear":
+        o, _ = sa.sa_additive_attention(qc, kc, v4, kw["attn_scale"], cfg.nbits)
+        oq = sa.sa_quantize_act(o.view(T, E), kw["act_inv_scale"])
+    else:
+        _, oq, _ = sa.sa_hamming_attention_fused(qc, kc, v4, kw["attn_scale"], cfg.nbits, kw["act_inv_scale"],
+                                                 want_xh=False)
+        oq = oq.view(T, E)
+    (x1,) = sa.sa_shift_linear_f32(oq, kw["wo"], kw["o_scale"], residual=kw["x"], variant=var)
+    x1_copy = x1.clone()
+    moe = bool(kw["moe"])
+    _, z2q, xh, logits = sa.sa_layernorm_quant(x1, kw["gamma2"], kw["beta2"], kw["eps"], kw["ln_inv_scale"], want_ln=False,
+                                               want_q=True, want_half=moe, wg=kw.get("wg"), bg=kw.get("bg"))
+    acc = sa.binding.SA_MLP_ACCUMULATE
+    if not moe:
+        sa.sa_shift_mlp(z2q, kw["w1"], kw["w2"], kw["requant_scale"], kw["lut"], want_y2=False, y=x1,
+                        out_scale=kw["out_scale"], variant=var, stages=3 | acc)
+    else:
+        perm, _, cnt, gate = sa.sa_moe_dispatch(logits)
+        sa.sa_mult_mlp_f16_half(xh, kw["mw1"], kw["mw2"], rows=perm, counts=cnt, expert=0, max_rows=T, want_out=False,
+                                y=x1, gate=gate, stages=3 | acc)
+        sa.sa_shift_mlp(z2q, kw["w1"], kw["w2"], kw["requant_scale"], kw["lut"], rows=perm, counts=cnt, expert=1,
+                        max_rows=T, want_y2=False, y=x1, gate=gate, out_scale=kw["out_scale"], variant=var,
+                        stages=3 | acc)
+    return x1_copy, x1
+
+
+LAYER_CASES = [
+    wl.C1,
+    wl.scaled_down(wl.C4, B=2),
+    wl.scaled_down(wl.C5, B=1, N=1100),
+]
+
+
+@pytest.mark.parametrize("cfg", LAYER_CASES, ids=lambda c: c.name)
+def test_layer_forward_matches_oracle(sa, cfg):
+    """End to end against the oracle.  Four int8 quantisers sit in the path (after both LayerNorms, after
+    the attention, inside the Shift expert) and one hash; an fp32 input that differs from the oracle's fp64
+    value in its last bits lands on the other side of a rounding boundary now and then, and a flipped code of
+    a key row reaches every query of its (batch, head).  The two sides therefore agree as signals, not element
+    by element: the test bounds the relative Frobenius error of both residual sums; the element-wise and
+    bit-exact claims are carried by the stage tests above, which feed every entry point the oracle's own
+    intermediate values, and by the identity of sa_layer_forward with the chain of those entry points."""
+    x = wl.layer_input(cfg)
+    lp = wl.layer_params(cfg)
+    p = wl.mlp_params(cfg)
+    proj = wl.proj(cfg)
+    scale = wl.attention_scale(cfg)
+    r = oracle.layer_forward(cfg, x, lp, p, proj, scale)
+    kw = layer_kwargs(sa, cfg, x, lp, p, proj, scale)
+    y = host(sa.binding.Layer(**kw).forward())
+    x1_chain, y_chain = chain_entry_points(sa, cfg, kw)
+    torch.cuda.synchronize()
+    assert np.array_equal(y, host(y_chain)), "sa_layer_forward differs from the chain of its entry points"
+    y_prep = host(sa.binding.Layer(**layer_kwargs(sa, cfg, x, lp, p, proj, scale, prepared=True)).forward())
+    assert np.array_equal(y_prep, y)
+
+    def rel(a, b):
+        return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
+
+    e1 = rel(host(x1_chain) - x, r["x1"].astype(np.float64) - x)        # the attention branch alone
+    e2 = rel(y - host(x1_chain), r["mlp"])                              # the MLP branch alone
+    ey = rel(y, r["y"])
+    print("layer %s: attention-branch error %.3g, MLP-branch error %.3g, output error %.3g" % (cfg.name, e1, e2, ey))
+    assert e1 < 5e-3 and e2 < 3e-2 and ey < 1e-2
