@@ -139,6 +139,17 @@ int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes,
  * sa_shift_linear, sa_shift_mlp and sa_block_forward (w4, w1, w2) point at such
  * planes instead of packed nibbles, and no decode runs.
  */
+/*
+ * Dense weights to shift weights (Sec. 4.1, below Eq. 3: s = sign(W),
+ * P = round(log2 |W|)), in the 4-bit storage format of this library:
+ *   w [N,K] fp32  ->  w4 [N,K/2],  nibble = (W < 0) << 3 | (clamp(P, -7, 0) + 7)
+ * sign(0) = +1; W = 0 and every |W| < 2^-7.5 take P = -7, |W| > 2^-0.5 takes P = 0
+ * (weights are expected in [-1, 1], as after the usual normalisation); NaN
+ * counts as +1.0.  log2 |W| is never half-way for a float, so the rounding is
+ * unambiguous; the result is bit-exact.  K % 8 == 0.
+ */
+int sa_shift_weights_from_float(const float *w, int N, int K, uint8_t *w4, void *stream);
+
 size_t sa_shift_planes_bytes(int K, int N);
 int sa_shift_planes_prepare(const uint8_t *w4, int K, int N, void *planes, size_t planes_bytes,
                             void *stream);

@@ -138,6 +138,15 @@ def shift_linear(x, w4, bias=None):
     return y
 
 
+def shift_weights_from_float(w):
+    w = _c(w, np.float32)
+    N, K = w.shape
+    assert K % 2 == 0
+    w4 = np.zeros((N, K // 2), dtype=np.uint8)
+    _load().oracle_shift_weights_from_float(_p(w), ctypes.c_long(N), K, _p(w4))
+    return w4
+
+
 def quantize_act(x, inv_scale):
     x = _c(x, np.float32)
     q = np.zeros(x.shape, dtype=np.int8)

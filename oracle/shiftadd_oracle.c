@@ -409,3 +409,32 @@ void oracle_router_logits(const double *z, long T, int E, const float *wg, const
             logits[(size_t)t * n_exp + e] = s + (double)bg[e];
         }
 }
+
+/* ------------------------------------------------------------------------
+ * Dense weights -> shift weights (Sec. 4.1, below Eq. 3): s = sign(W) in
+ * {-1, +1}, P = round(log2 |W|).  Stored as the nibble (neg << 3) | (P + 7)
+ * with P clamped to [-7, 0] (weights in [-1, 1]); sign(0) = +1; W = 0 has
+ * log2 = -inf and takes P = -7; NaN is treated as +1.0.  log2 |W| = n + 1/2
+ * would need |W| = 2^n * sqrt(2), which no float is, so the rounding rule at
+ * one half never applies and fp64 log2 decides every fp32 input correctly (the
+ * nearest floats to 2^n * sqrt(2) are 1e-8 away in log2).
+ * ------------------------------------------------------------------------ */
+void oracle_shift_weights_from_float(const float *w, long N, int K, uint8_t *w4) {
+#pragma omp parallel for
+    for (long n = 0; n < N; ++n)
+        for (int k = 0; k < K; k += 2) {
+            uint8_t byte = 0;
+            for (int i = 0; i < 2; ++i) {
+                const double a = fabs((double)w[(size_t)n * K + k + i]);
+                double p;
+                if (a != a) p = 0.0;
+                else if (a == 0.0) p = -7.0;
+                else p = nearbyint(log2(a));
+                if (p < -7.0) p = -7.0;
+                if (p > 0.0) p = 0.0;
+                const int neg = w[(size_t)n * K + k + i] < 0.0f;
+                byte |= (uint8_t)(((neg << 3) | ((int)p + 7)) << (4 * i));
+            }
+            w4[(size_t)n * (K / 2) + k / 2] = byte;
+        }
+}

@@ -22,6 +22,7 @@ EXPORTS = [
     "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_binarize_pair", "sa_additive_attention_workspace_bytes",
     "sa_additive_attention", "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear", "sa_shift_linear_f32", "sa_layernorm_quant",
+    "sa_shift_weights_from_float",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
@@ -196,6 +197,14 @@ def sa_hamming_attention_fused(q_codes, k_codes, v, scale, nbits, act_inv_scale,
                                                      nbits, dv, _f(scale), _ptr(None), _ptr(xq), _ptr(xh),
                                                      _f(act_inv_scale), variant, _stream()))
     return out, xq, xh
+
+
+def sa_shift_weights_from_float(w):
+    """fp32 weights [N, K] -> packed 4-bit shift weights [N, K/2] (sign, rounded log2 magnitude)."""
+    N, K = w.shape
+    w4 = torch.empty((N, K // 2), dtype=torch.uint8, device=w.device)
+    _check(load_library().sa_shift_weights_from_float(_ptr(w), N, K, _ptr(w4), _stream()))
+    return w4
 
 
 def sa_shift_planes_prepare(w4):

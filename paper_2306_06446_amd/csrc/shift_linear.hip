@@ -273,6 +273,31 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
     }
 }
 
+// One weight -> its 4-bit form (neg << 3) | e, e = clamp(round(log2 |w|), -7, 0) + 7.  log2 |w| is
+// never half-way between two integers for a float (2^(n + 1/2) is irrational), so rounding is a
+// comparison of the mantissa with that of sqrt(2): integer logic, no transcendental.  The fp32
+// neighbours of sqrt(2) are 0x3FB504F3 < sqrt(2) < 0x3FB504F4.
+__device__ inline uint32_t weight_nibble(float w) {
+    const uint32_t bits = __builtin_bit_cast(uint32_t, w) & 0x7FFFFFFFu;
+    int p = (int)(bits >> 23) - 127 + ((bits & 0x7FFFFFu) >= 0x3504F4u ? 1 : 0);   // zero, subnormals: <= -126
+    p = p < -7 ? -7 : (p > 0 ? 0 : p);                                              // Inf, NaN: exponent 255 -> 0
+    return (uint32_t)(p + 7) | (w < 0.0f ? 8u : 0u);                                // -0 and NaN count as positive
+}
+
+// Eight consecutive weights of a row per thread: two 16-byte loads, one 4-byte store.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float *__restrict__ w, long n8,
+                                                           uint32_t *__restrict__ w4) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n8) return;
+    const float4 a = *reinterpret_cast<const float4 *>(w + 8 * i);
+    const float4 b = *reinterpret_cast<const float4 *>(w + 8 * i + 4);
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint32_t word = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) word |= weight_nibble(v[k]) << (4 * k);      // even k = low nibble of byte k / 2
+    w4[i] = word;
+}
+
 __global__ __launch_bounds__(256) void requant_lut_kernel(const int32_t *__restrict__ y, long n, float s,
                                                           const int8_t *__restrict__ lut,
                                                           int8_t *__restrict__ h) {
@@ -298,6 +323,22 @@ extern "C" int sa_shift_planes_prepare(const uint8_t *w4, int K, int N, void *pl
     SA_REQUIRE(planes_bytes_given >= planes_bytes(K, N), SA_ERR_WORKSPACE,
                "sa_shift_planes_prepare: %zu bytes needed, %zu given", planes_bytes(K, N), planes_bytes_given);
     return decode_planes(w4, K, N, planes, sa::as_stream(stream));
+}
+
+extern "C" int sa_shift_weights_from_float(const float *w, int N, int K, uint8_t *w4, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(N >= 0 && K >= 0, SA_ERR_INVALID, "sa_shift_weights_from_float: negative size");
+    SA_REQUIRE(K % 8 == 0, SA_ERR_SHAPE, "sa_shift_weights_from_float: K (%d) must be a multiple of 8", K);
+    if (N == 0 || K == 0) return SA_OK;
+    SA_REQUIRE(w && w4, SA_ERR_INVALID, "sa_shift_weights_from_float: NULL buffer");
+    SA_REQUIRE(sa::aligned16(w) && sa::aligned16(w4), SA_ERR_ALIGN,
+               "sa_shift_weights_from_float: pointers must be 16-byte aligned");
+    const long n8 = (long)N * K / 8;
+    const long blocks = (n8 + 255) / 256;
+    SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_shift_weights_from_float: too many weights");
+    pack_weights_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(
+        w, n8, reinterpret_cast<uint32_t *>(w4));
+    return sa::check_launch("sa_shift_weights_from_float");
 }
 
 extern "C" size_t sa_shift_linear_workspace_bytes(long M, int K, int N, int variant) {

@@ -231,3 +231,20 @@ def test_layer_forward_matches_oracle(sa, cfg):
     ey = rel(y, r["y"])
     print("layer %s: attention-branch error %.3g, MLP-branch error %.3g, output error %.3g" % (cfg.name, e1, e2, ey))
     assert e1 < 5e-3 and e2 < 3e-2 and ey < 1e-2
+
+
+# ------------------------------------------ dense weights -> shift weights ---
+
+def test_shift_weights_from_float_bit_exact(sa):
+    g = np.random.default_rng(62)
+    w = (g.standard_normal((300, 384)) * 0.2).astype(np.float32)
+    lo, hi = np.float32(1.41421354), np.float32(1.41421366)
+    edge = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-40, -1e-40, 2.0**-7.6, 2.0**-7.4, 1.0, -1.0, 3.0])
+    w[0, :12] = edge
+    w[1, :16] = [s * lo * 2.0**p for p in (-1, -3, -6, -7) for s in (1, -1)] + [s * hi * 2.0**p for p in (-1, -3, -6, -7) for s in (1, -1)]
+    ref = oracle.shift_weights_from_float(w)
+    got = host(sa.sa_shift_weights_from_float(dev(w)))
+    assert np.array_equal(got, ref)
+    # the packed weights drive the shift layers like any others
+    x = wl.int8_activations(3, 70, 384)
+    assert np.array_equal(host(sa.sa_shift_linear(dev(x), dev(got))), oracle.shift_linear(x, ref))

@@ -184,3 +184,46 @@ def test_mlp_stage_composition_all_shift_and_moe():
     y_all = oracle.mlp_stage(x, None, p)
     y2 = oracle.shift_mlp(xq, p.w1, p.w2, p.requant_scale, p.lut)
     np.testing.assert_allclose(y_all, float(np.float32(p.out_scale)) * y2, rtol=1e-15)
+
+
+# ------------------------------------------ dense weights -> shift weights ---
+
+def unpack_nibbles(w4):
+    nib = np.empty((w4.shape[0], w4.shape[1] * 2), dtype=np.uint8)
+    nib[:, 0::2] = w4 & 15
+    nib[:, 1::2] = w4 >> 4
+    return nib
+
+
+def test_shift_weights_from_float_powers_of_two_round_trip():
+    """W = +-2^p, p in [-7, 0], converts to exactly (sign, p) and decodes back to W * 2^7."""
+    p = np.arange(-7, 1)
+    w = np.concatenate([np.exp2(p), -np.exp2(p)]).astype(np.float32)[None]
+    nib = unpack_nibbles(oracle.shift_weights_from_float(w))[0]
+    assert np.array_equal(nib & 7, np.concatenate([p + 7, p + 7]))
+    assert np.array_equal(nib >> 3, np.concatenate([np.zeros(8), np.ones(8)]))
+    x = np.eye(16, dtype=np.int8)
+    y = oracle.shift_linear(x, oracle.shift_weights_from_float(w))
+    assert np.array_equal(y[:, 0], (w[0] * 128).astype(np.int32))
+
+
+def test_shift_weights_from_float_rounds_log2_at_sqrt2_and_clamps():
+    lo, hi = np.float32(1.41421354), np.float32(1.41421366)        # the fp32 neighbours of sqrt(2)
+    assert float(lo) ** 2 < 2.0 < float(hi) ** 2
+    w = np.array([[0.25 * lo, 0.25 * hi, 0.3, 0.4, 0.7, 0.71, 1.0, 1.5, 3.0, 1e-3, 0.0, -0.0,
+                   -0.25 * lo, -0.25 * hi, 2.0**-7.6, np.inf]], dtype=np.float32)
+    nib = unpack_nibbles(oracle.shift_weights_from_float(w))[0]
+    expect_p = np.array([-2, -1, -2, -1, -1, 0, 0, 0, 0, -7, -7, -7, -2, -1, -7, 0])
+    assert np.array_equal((nib & 7).astype(int) - 7, expect_p)
+    assert np.array_equal(nib >> 3, np.array([0] * 12 + [1, 1, 0, 0]))
+
+
+def test_shift_weights_from_float_equals_library_log2_rounding():
+    g = np.random.default_rng(61)
+    w = (g.standard_normal((64, 256)) * 0.2).astype(np.float32)
+    nib = unpack_nibbles(oracle.shift_weights_from_float(w))
+    p_ref = np.clip(np.rint(np.log2(np.abs(w.astype(np.float64)))), -7, 0).astype(int)
+    assert np.array_equal((nib & 7).astype(int) - 7, p_ref)
+    assert np.array_equal(nib >> 3, (w < 0).astype(np.uint8))
+    inside = (np.abs(w) > 2.0**-7) & (np.abs(w) < 1.0)
+    assert np.all(np.abs(np.log2(np.abs(w[inside])) - p_ref[inside]) <= 0.5)
