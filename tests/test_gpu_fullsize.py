@@ -103,3 +103,23 @@ def test_config4_dispatch_full_size_properties(sa):
     assert np.all(np.diff(perm[:cnt[0]]) > 0) and np.all(np.diff(perm[cnt[0]:]) > 0)
     assert np.array_equal(eo, (logits[:, 1] > logits[:, 0]).astype(np.int32))
     assert np.all(gate >= 0.5) and np.all(gate < 1.0)
+
+
+@pytest.mark.parametrize("cfg,batches", [(wl.C4, [0, 41]), (wl.C5, [3])], ids=lambda c: getattr(c, "name", str(c)))
+def test_full_size_layer_on_sampled_batches(sa, cfg, batches):
+    """The complete block of Eq. 2 at the benchmark shapes, prepared planes as bench.py --layer runs it.
+    Batch elements are independent in every step of the layer, so the oracle recomputes whole sampled
+    batch elements; the bounds are those of the small-size test (see there for why they are statistical)."""
+    from test_gpu_layer import layer_kwargs
+    x = wl.layer_input(cfg)
+    lp, p, proj, scale = wl.layer_params(cfg), wl.mlp_params(cfg), wl.proj(cfg), wl.attention_scale(cfg)
+    y = host(sa.binding.Layer(**layer_kwargs(sa, cfg, x, lp, p, proj, scale, prepared=True)).forward())
+    assert np.isfinite(y).all()
+    one = dataclasses.replace(cfg, B=1)
+    for b in batches:
+        rows = slice(b * cfg.N, (b + 1) * cfg.N)
+        r = oracle.layer_forward(one, x[rows], lp, p, proj, scale)
+        err = float(np.linalg.norm(y[rows] - r["y"]) / np.linalg.norm(r["y"]))
+        err_branches = float(np.linalg.norm((y[rows] - x[rows]) - (r["y"] - x[rows])) / np.linalg.norm(r["y"] - x[rows]))
+        print("layer %s batch %d: output error %.3g, both branches %.3g" % (cfg.name, b, err, err_branches))
+        assert err < 1e-2 and err_branches < 3e-2
