@@ -100,6 +100,51 @@ def additive_attention(q_codes, k_codes, v, nbits, scale):
     return qkv(q_codes, kv, scale), kv
 
 
+def ktv01(k_codes, v, nbits):
+    """{0,1}-code K^T V and the per-bit counts of set key bits: (kv fp64 [B,H,nbits,dv], ksum int64 [B,H,nbits])."""
+    k_codes = _c(k_codes, np.uint64)
+    v = _c(v, np.float32)
+    B, H, Nk, W = k_codes.shape
+    assert W * 64 == nbits and v.shape[:3] == (B, Nk, H)
+    dv = v.shape[3]
+    kv = np.zeros((B, H, nbits, dv), dtype=np.float64)
+    ksum = np.zeros((B, H, nbits), dtype=np.int64)
+    _load().oracle_ktv01(_p(k_codes), _p(v), B, H, Nk, nbits, dv, _p(kv), _p(ksum))
+    return kv, ksum
+
+
+def qkv01(q_codes, kv, ksum, eps):
+    """Normalised {0,1}-code Q(K^T V): (out fp64 [B,Nq,H,dv], den int64 [B,H,Nq])."""
+    q_codes = _c(q_codes, np.uint64)
+    kv = _c(kv, np.float64)
+    ksum = _c(ksum, np.int64)
+    B, H, Nq, W = q_codes.shape
+    nbits, dv = kv.shape[2], kv.shape[3]
+    out = np.zeros((B, Nq, H, dv), dtype=np.float64)
+    den = np.zeros((B, H, Nq), dtype=np.int64)
+    _load().oracle_qkv01(_p(q_codes), _p(kv), _p(ksum), B, H, Nq, nbits, dv, ctypes.c_double(eps), _p(out), _p(den))
+    return out, den
+
+
+def linear_attention_01(q_codes, k_codes, v, nbits, eps):
+    kv, ksum = ktv01(k_codes, v, nbits)
+    out, den = qkv01(q_codes, kv, ksum, eps)
+    return out, kv, ksum, den
+
+
+def dwconv3x3(v, w, bias=None):
+    """v [B,gh,gw,E] fp32, w [E,3,3] fp32, bias [E] or None -> fp64 [B,gh,gw,E]."""
+    v = _c(v, np.float32)
+    w = _c(w, np.float32)
+    B, gh, gw, E = v.shape
+    assert w.shape == (E, 3, 3)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+    out = np.zeros((B, gh, gw, E), dtype=np.float64)
+    _load().oracle_dwconv3x3(_p(v), _p(w), _p(bias), B, gh, gw, E, _p(out))
+    return out
+
+
 def hamming_scores(q_codes, k_codes, nbits):
     q_codes = _c(q_codes, np.uint64)
     k_codes = _c(k_codes, np.uint64)

@@ -438,3 +438,83 @@ void oracle_shift_weights_from_float(const float *w, long N, int K, uint8_t *w4)
             w4[(size_t)n * (K / 2) + k / 2] = byte;
         }
 }
+
+/* ------------------------------------------------------------------------
+ * Linear attention on {0,1} codes with its row normaliser, and the depthwise
+ * convolution on the V branch (Sec. 4.1: the Add layer of Eq. 3 accumulates
+ * where the binary weight is non-zero and skips zeros; the attention is built
+ * on kernel-based linear attention, Q(K^T V), with a light depthwise
+ * convolution on V in parallel; Sec. 5 names the normalisation among the extra
+ * operations of linear attention).  The paper prints neither formula; the
+ * reading taken is the standard kernel-based form with the code bits c in
+ * {0,1} as the feature map:
+ *   KV[j,:]  = sum_n cK[n,j] * V[n,:]          ksum[j] = sum_n cK[n,j]
+ *   O[n,:]   = (sum_j cQ[n,j] * KV[j,:]) / (sum_j cQ[n,j] * ksum[j] + eps)
+ * The denominator is an integer count (plus eps), exact on both sides.
+ * ------------------------------------------------------------------------ */
+void oracle_ktv01(const uint64_t *k_codes, const float *v, int B, int H, int Nk, int nbits, int dv,
+                  double *kv, int64_t *ksum) {
+    const int W = nbits / 64;
+#pragma omp parallel for collapse(2)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h)
+            for (int j = 0; j < nbits; ++j) {
+                double *row = kv + (((size_t)b * H + h) * nbits + j) * dv;
+                for (int c = 0; c < dv; ++c) row[c] = 0.0;
+                int64_t cnt = 0;
+                for (int n = 0; n < Nk; ++n) {
+                    const uint64_t *code = k_codes + (((size_t)b * H + h) * Nk + n) * W;
+                    if (!code_bit(code, j)) continue;            /* zeros are skipped */
+                    ++cnt;
+                    const float *vr = v + (((size_t)b * Nk + n) * H + h) * dv;
+                    for (int c = 0; c < dv; ++c) row[c] += (double)vr[c];
+                }
+                ksum[((size_t)b * H + h) * nbits + j] = cnt;
+            }
+}
+
+void oracle_qkv01(const uint64_t *q_codes, const double *kv, const int64_t *ksum, int B, int H, int Nq,
+                  int nbits, int dv, double eps, double *out, int64_t *den_out) {
+    const int W = nbits / 64;
+#pragma omp parallel for collapse(2)
+    for (int b = 0; b < B; ++b)
+        for (int n = 0; n < Nq; ++n)
+            for (int h = 0; h < H; ++h) {
+                const uint64_t *code = q_codes + (((size_t)b * H + h) * Nq + n) * W;
+                double *o = out + (((size_t)b * Nq + n) * H + h) * dv;
+                for (int c = 0; c < dv; ++c) o[c] = 0.0;
+                int64_t den = 0;
+                for (int j = 0; j < nbits; ++j) {
+                    if (!code_bit(code, j)) continue;
+                    den += ksum[((size_t)b * H + h) * nbits + j];
+                    const double *row = kv + (((size_t)b * H + h) * nbits + j) * dv;
+                    for (int c = 0; c < dv; ++c) o[c] += row[c];
+                }
+                for (int c = 0; c < dv; ++c) o[c] /= ((double)den + eps);
+                if (den_out) den_out[((size_t)b * H + h) * Nq + n] = den;
+            }
+}
+
+/* Depthwise 3x3 convolution over the token grid, stride 1, zero padding 1
+ * (the "lightweight DWConv on the V branch", Sec. 4.1), added by the caller to
+ * the attention output.  v, out: [B, gh, gw, E] (tokens row-major over the
+ * grid, channels = heads x dv inner); w: [E, 3, 3] (w[c][dy+1][dx+1] applies to
+ * the neighbour at (y+dy, x+dx)); bias: [E] or NULL. */
+void oracle_dwconv3x3(const float *v, const float *w, const float *bias, int B, int gh, int gw, int E,
+                      double *out) {
+#pragma omp parallel for collapse(2)
+    for (int b = 0; b < B; ++b)
+        for (int y = 0; y < gh; ++y)
+            for (int x = 0; x < gw; ++x)
+                for (int c = 0; c < E; ++c) {
+                    double s = bias ? (double)bias[c] : 0.0;
+                    for (int dy = -1; dy <= 1; ++dy)
+                        for (int dx = -1; dx <= 1; ++dx) {
+                            const int yy = y + dy, xx = x + dx;
+                            if (yy < 0 || yy >= gh || xx < 0 || xx >= gw) continue;
+                            s += (double)w[(size_t)c * 9 + (dy + 1) * 3 + (dx + 1)] *
+                                 (double)v[(((size_t)b * gh + yy) * gw + xx) * E + c];
+                        }
+                    out[(((size_t)b * gh + y) * gw + x) * E + c] = s;
+                }
+}

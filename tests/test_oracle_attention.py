@@ -253,3 +253,68 @@ def test_hamming_attention_special_cases():
     # scale 0: uniform weights
     o = oracle.hamming_attention(q, k, v, nbits, 0.0)
     np.testing.assert_allclose(o[0, :, 0], np.tile(mean, (4, 1)), rtol=1e-13)
+
+
+# ----------------------------------- {0,1} codes, normaliser, depthwise conv ---
+
+def _unpack01(codes, nbits):
+    bits = ((codes[..., :, None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1))
+    return bits.reshape(codes.shape[:-1] + (nbits,)).astype(np.float64)
+
+
+@pytest.mark.parametrize("B,H,Nq,Nk,nbits,dv", [(2, 3, 17, 23, 64, 8), (1, 2, 40, 9, 128, 16)])
+def test_linear_attention_01_equals_dense_matmuls_with_01_matrices(B, H, Nq, Nk, nbits, dv):
+    g = np.random.default_rng([71, Nq, Nk])
+    qc = wl.random_codes(1, (B, H, Nq), nbits)
+    kc = wl.random_codes(2, (B, H, Nk), nbits)
+    v = g.standard_normal((B, Nk, H, dv)).astype(np.float32)
+    out, kv, ksum, den = oracle.linear_attention_01(qc, kc, v, nbits, 0.5)
+    cq, ck = _unpack01(qc, nbits), _unpack01(kc, nbits)                # [B,H,N,nbits]
+    vv = v.astype(np.float64).transpose(0, 2, 1, 3)                     # [B,H,Nk,dv]
+    kv_ref = np.matmul(ck.transpose(0, 1, 3, 2), vv)
+    assert np.allclose(kv, kv_ref, rtol=1e-13, atol=1e-13)
+    assert np.array_equal(ksum, ck.sum(axis=2).astype(np.int64))
+    den_ref = np.matmul(cq, ck.transpose(0, 1, 3, 2)).sum(axis=3)       # row sums of CQ CK^T
+    assert np.array_equal(den, np.rint(den_ref).astype(np.int64))
+    out_ref = np.matmul(np.matmul(cq, ck.transpose(0, 1, 3, 2)), vv) / (den_ref[..., None] + 0.5)
+    assert np.allclose(out, out_ref.transpose(0, 2, 1, 3), rtol=1e-12, atol=1e-13)
+
+
+def test_linear_attention_01_relates_to_the_pm1_form_and_normalises_constants():
+    """sum c v = (sum sigma v + sum v) / 2 ties the {0,1} K^T V to the +-1 one; with V constant along tokens the
+    normalised output is that constant times den / (den + eps)."""
+    B, H, N, nbits, dv = 1, 2, 31, 64, 4
+    kc = wl.random_codes(3, (B, H, N), nbits)
+    qc = wl.random_codes(4, (B, H, N), nbits)
+    g = np.random.default_rng(72)
+    v = g.standard_normal((B, N, H, dv)).astype(np.float32)
+    kv01, _ = oracle.ktv01(kc, v, nbits)
+    kv_pm = oracle.ktv(kc, v, nbits)
+    colsum = v.astype(np.float64).sum(axis=1).transpose(0, 1, 2)[:, :, None, :]     # [B,H,1,dv]
+    assert np.allclose(kv01, 0.5 * (kv_pm + colsum), rtol=1e-13, atol=1e-13)
+    vc = np.broadcast_to(np.array([1.5, -2.0, 0.25, 3.0], np.float32), (B, N, H, dv)).copy()
+    out, _, _, den = oracle.linear_attention_01(qc, kc, vc, nbits, 2.0)
+    ratio = (den / (den + 2.0)).transpose(0, 2, 1)[..., None]                        # [B,N,H,1]
+    assert np.allclose(out, vc.astype(np.float64) * ratio, rtol=1e-13)
+    # an all-zero query code selects nothing: numerator 0, denominator eps
+    qz = np.zeros((B, H, N, 1), dtype=np.uint64)
+    out0, _, _, den0 = oracle.linear_attention_01(qz, kc, v, nbits, 1.0)
+    assert np.all(out0 == 0.0) and np.all(den0 == 0)
+
+
+@pytest.mark.parametrize("B,gh,gw,E", [(2, 5, 7, 12), (1, 1, 4, 3), (1, 14, 14, 8)])
+def test_dwconv3x3_equals_library_grouped_conv(B, gh, gw, E):
+    g = np.random.default_rng([73, gh, gw])
+    v = g.standard_normal((B, gh, gw, E)).astype(np.float32)
+    w = g.standard_normal((E, 3, 3)).astype(np.float32)
+    bias = g.standard_normal(E).astype(np.float32)
+    got = oracle.dwconv3x3(v, w, bias)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(v).double().permute(0, 3, 1, 2), torch.from_numpy(w).double()[:, None],
+                                     torch.from_numpy(bias).double(), padding=1, groups=E).permute(0, 2, 3, 1).numpy()
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-12)
+    # a kernel with only the centre tap is a per-channel scale; only the right tap shifts the grid left
+    wc = np.zeros((E, 3, 3), np.float32); wc[:, 1, 1] = 2.0
+    assert np.array_equal(oracle.dwconv3x3(v, wc), 2.0 * v.astype(np.float64))
+    wr = np.zeros((E, 3, 3), np.float32); wr[:, 1, 2] = 1.0
+    shifted = np.zeros_like(v, dtype=np.float64); shifted[:, :, :-1] = v[:, :, 1:]
+    assert np.array_equal(oracle.dwconv3x3(v, wr), shifted)
