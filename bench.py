@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--layer", action="store_true",
                     help="time the complete block of Eq. 2 (sa_layer_forward: LayerNorms, the four attention Linears "
                          "as shift layers, residuals, router) on tokens of the chosen configuration's shape")
+    ap.add_argument("--zero-one", action="store_true",
+                    help="time the {0,1}-code normalised linear attention with the depthwise convolution on V "
+                         "(sa_linear_attention_01 + sa_dwconv3x3) at the chosen configuration's attention shape (c2, c5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
@@ -131,6 +134,8 @@ def main():
     cfg = {"c1": wl.C1, "c2": wl.C2, "c4": wl.C4, "c5": wl.C5}[args.config]
     if args.layer:
         return bench_layer(args, sa, wl, torch, np, cfg)
+    if args.zero_one:
+        return bench_zero_one(args, sa, wl, torch, np, cfg)
     moe = cfg.E > 0 and cfg.shift_frac is not None
 
     def dev(a):
@@ -311,6 +316,110 @@ def bench_shift_linear(args, sa, wl, torch, np):
            "config": {"workload": "c3-deit-small-shift-linear", "M": M, "layers": [list(s) for s in wl.C3_SHAPES]},
            "valu_variant_ms_per_step": round(total_us[0] * 1e-3, 5), "roofline": roofline, "cpu_baseline": None,
            "kernels": rows}
+    print(json.dumps(out))
+
+
+def bench_zero_one(args, sa, wl, torch, np, cfg):
+    """Hash Q and K, linear attention on {0,1} codes with its normaliser, depthwise 3x3 on V added to the output."""
+    gh = int(round(math.sqrt(cfg.N)))
+    assert gh * gh == cfg.N, "--zero-one needs a square token grid (c2: 56 x 56, c5: 128 x 128)"
+    B, N, H, d, dv, nbits = cfg.B, cfg.N, cfg.H, cfg.d, cfg.dv, cfg.nbits
+    E = H * dv
+    q, k, v = wl.qkv(cfg)
+    rng = np.random.default_rng([cfg.cfg_id, 40])
+    wconv = (rng.standard_normal((E, 3, 3)) / 3.0).astype(np.float32)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    pr, dw = dev(wl.proj(cfg)), dev(wconv)
+    n_sets = args.rotate or max(2, min(8, math.ceil(600e6 / (4 * q.nbytes))))
+    sets = []
+    lib = sa.load_library()
+    for _ in range(n_sets):
+        dq, dk, dv_ = dev(q), dev(k), dev(v)
+        sets.append(dict(q=dq, k=dk, v=dv_, qc=torch.empty((B, H, N, nbits // 64), dtype=torch.int64, device="cuda"),
+                         kc=torch.empty((B, H, N, nbits // 64), dtype=torch.int64, device="cuda"),
+                         kv=torch.empty((B, H, nbits, dv), dtype=torch.float32, device="cuda"),
+                         ksum=torch.empty((B, H, nbits), dtype=torch.int32, device="cuda"),
+                         o=torch.empty((B, N, H, dv), dtype=torch.float32, device="cuda"),
+                         ws=torch.empty(max(16, lib.sa_linear_attention_01_workspace_bytes(B, H, N, N, nbits, dv)),
+                                        dtype=torch.uint8, device="cuda")))
+    eps = 1.0
+    stages = [
+        ("binarize_qk", lambda s: sa.sa_binarize_pair(s["q"], s["k"], pr, nbits, q_codes=s["qc"], k_codes=s["kc"])),
+        ("ktv01_counts", lambda s: sa.sa_linear_attention_01(None, s["kc"], s["v"], eps, nbits, phases=1, kv=s["kv"], ksum=s["ksum"],
+                                                             workspace=s["ws"])),
+        ("qkv01_normalised", lambda s: sa.sa_linear_attention_01(s["qc"], None, None, eps, nbits, phases=2, kv=s["kv"], ksum=s["ksum"],
+                                                                 out=s["o"], workspace=s["ws"])),
+        ("dwconv3x3_add", lambda s: sa.sa_dwconv3x3(s["v"].view(B, gh, gh, E), dw, None, out=s["o"].view(B, gh, gh, E), accumulate=True)),
+    ]
+
+    def step(s):
+        for _, fn in stages:
+            fn(s)
+
+    for i in range(args.warmup):
+        step(sets[i % n_sets])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % n_sets])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    rows = B * N * H
+    code_b, v_b, kv_b = rows * nbits // 8, rows * dv * 4, B * H * nbits * dv * 4
+    algo = {"binarize_qk": (2 * (rows * d * 4 + code_b) + d * nbits * 4, 4 * rows * nbits * d, "mfma_bf16x3"),
+            "ktv01_counts": (2 * code_b + v_b + kv_b, 2 * rows * nbits * dv, "mfma_bf16x3"),
+            "qkv01_normalised": (2 * code_b + kv_b + v_b, 2 * rows * nbits * dv, "mfma_bf16x3"),
+            "dwconv3x3_add": (3 * v_b, 18 * rows * dv, "alu_fp32")}
+    report = []
+    for name, fn in stages:
+        us = None
+        if not args.no_kernels:
+            for s_ in sets:
+                fn(s_)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                fn(sets[i % n_sets])
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.steps
+        nbytes, ops, comp = algo[name]
+        t_hbm, t_cmp = nbytes / (HBM_PEAK_GBS * 1e9) * 1e6, ops / (PEAK_TFLOPS[comp] * 1e12) * 1e6
+        row = dict(name=name, us=None if us is None else round(us, 2), bytes=nbytes, ops=ops, hbm_floor_us=round(t_hbm, 2),
+                   compute_floor_us=round(t_cmp, 2), bound="hbm" if t_hbm >= t_cmp else ("mfma" if comp.startswith("mfma") else "alu"),
+                   compute_peak=comp)
+        if us:
+            row.update(hbm_frac=round(t_hbm / us, 4), binding_frac=round(max(t_hbm, t_cmp) / us, 4))
+        report.append(row)
+    roofline = None
+    timed = [r for r in report if r["us"]]
+    if timed:
+        dom = max(timed, key=lambda r: r["us"])
+        roofline = dict(kernel=dom["name"], bound=dom["bound"], achieved=round(dom["bytes"] / (dom["us"] * 1e-6) / 1e9, 3),
+                        peak=HBM_PEAK_GBS, unit="GB/s", frac=dom["hbm_frac"], traffic=None, us_per_launch=dom["us"])
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        bs = min(cfg.B, args.cpu_sample_batch or 1)
+        t0 = time.perf_counter()
+        qc = oracle.binarize(q[:bs], wl.proj(cfg), nbits)
+        kc = oracle.binarize(k[:bs], wl.proj(cfg), nbits)
+        oracle.linear_attention_01(qc, kc, v[:bs], nbits, eps)
+        oracle.dwconv3x3(v[:bs].reshape(bs, gh, gh, E), wconv)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(bs * N / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%d of %d batch items (%d tokens)" % (bs, B, bs * N)}
+    total_bytes = sum(r["bytes"] for r in report)
+    out = {"metric": "tokens/s of hash + normalised linear attention on {0,1} codes + depthwise conv on V at 1 GPU; % HBM roofline",
+           "value": round(B * N / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32+u64 codes", "data": "synthetic",
+           "config": {"workload": cfg.name + "-zero-one-normalised", "B": B, "N": N, "H": H, "d": d, "nbits": nbits, "dv": dv,
+                      "grid": [gh, gh], "input_sets_rotated": n_sets},
+           "hbm_roofline_frac": round(total_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
+           "algorithmic_bytes": total_bytes, "roofline": roofline, "cpu_baseline": cpu, "kernels": report}
     print(json.dumps(out))
 
 

@@ -100,6 +100,36 @@ int sa_additive_attention(const uint64_t *q_codes, const uint64_t *k_codes, cons
                           size_t workspace_bytes, void *stream);
 
 /*
+ * Linear attention on {0,1} codes with its row normaliser (Eq. 3: the Add
+ * layer accumulates where the binary weight is non-zero and skips zeros;
+ * Sec. 4.1: kernel-based linear attention in the order Q(K^T V)).  A set code
+ * bit stands for 1, a clear bit for 0:
+ *   phase 1:  kv[b,h,j,:] = sum_n cK[n,j] * v[b,n,h,:]      fp32 [B,H,nbits,dv]
+ *             ksum[b,h,j] = sum_n cK[n,j]                   int32 [B,H,nbits]
+ *   phase 2:  out[b,n,h,:] = (sum_j cQ[n,j] * kv[b,h,j,:]) / (sum_j cQ[n,j] * ksum[b,h,j] + eps)
+ * phases 1, 2 or 3 (| SA_ADDITIVE_VALU as for sa_additive_attention); eps > 0
+ * (a query whose set bits meet no key bit gives 0 / eps = 0).  The normaliser
+ * is an exact integer; Nk * nbits < 2^31.  dv in {32, 64, 128}.
+ */
+size_t sa_linear_attention_01_workspace_bytes(int B, int H, int Nq, int Nk, int nbits, int dv);
+int sa_linear_attention_01(const uint64_t *q_codes, const uint64_t *k_codes, const float *v, float *out,
+                           int B, int H, int Nq, int Nk, int nbits, int dv, float eps, float *kv,
+                           int32_t *ksum, int phases, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
+ * Depthwise 3x3 convolution over the token grid of the V branch (Sec. 4.1: a
+ * light depthwise convolution on V in parallel to the attention), stride 1,
+ * zero padding:  v, out fp32 [B, gh, gw, E] (tokens row-major over the grid,
+ * E = H * dv channels inner, i.e. V's own [B,N,H,dv] with N = gh * gw),
+ * w fp32 [E, 3, 3] (w[c][dy+1][dx+1] weighs the neighbour at (y+dy, x+dx)),
+ * bias fp32 [E] or NULL.  accumulate != 0 adds the result to out (the sum with
+ * the attention output), else out is overwritten.  E % 4 == 0; out != v.
+ */
+int sa_dwconv3x3(const float *v, const float *w, const float *bias_or_null, float *out, int accumulate,
+                 int B, int gh, int gw, int E, void *stream);
+
+/*
  * Quadratic attention on codes (Eq. 1 with Q K^T replaced by the Hamming
  * similarity S[i,j] = nbits - 2 * popcount(q_i xor k_j) of the codes):
  *   out[b,i,h,:] = sum_j softmax_j(scale * S[i,j]) * v[b,j,h,:]

@@ -20,7 +20,8 @@ SA_MLP_ACCUMULATE = 4
 
 EXPORTS = [
     "sa_version", "sa_last_error", "sa_binarize", "sa_binarize_ex", "sa_binarize_pair", "sa_additive_attention_workspace_bytes",
-    "sa_additive_attention", "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
+    "sa_additive_attention", "sa_linear_attention_01_workspace_bytes", "sa_linear_attention_01", "sa_dwconv3x3",
+    "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear", "sa_shift_linear_f32", "sa_layernorm_quant",
     "sa_shift_weights_from_float",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
@@ -75,7 +76,7 @@ def load_library():
                 "g.build()'` first; there is no fallback path" % LIB_PATH)
         lib = ctypes.CDLL(LIB_PATH)
         lib.sa_last_error.restype = ctypes.c_char_p
-        for name in ("sa_additive_attention_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
+        for name in ("sa_additive_attention_workspace_bytes", "sa_linear_attention_01_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
                      "sa_shift_linear_workspace_bytes", "sa_shift_planes_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
                      "sa_block_workspace_bytes", "sa_layer_workspace_bytes"):
@@ -166,6 +167,40 @@ def sa_additive_attention(q_codes, k_codes, v, scale, nbits, phases=3, kv=None, 
                                      nbits, dv, _f(scale), _ptr(kv), phases, _ptr(workspace),
                                      _z(workspace.numel()), _stream()))
     return out, kv
+
+
+def sa_linear_attention_01(q_codes, k_codes, v, eps, nbits, phases=3, kv=None, ksum=None, out=None, workspace=None):
+    """Normalised linear attention on {0,1} codes; returns (out, kv, ksum)."""
+    lib = load_library()
+    B, H, Nq, W = q_codes.shape if q_codes is not None else k_codes.shape
+    if q_codes is None:
+        Nq = 0
+    Nk = k_codes.shape[2] if k_codes is not None else 0
+    dv = v.shape[3] if v is not None else kv.shape[3]
+    dev = (v if v is not None else kv).device
+    if kv is None:
+        kv = torch.empty((B, H, nbits, dv), dtype=torch.float32, device=dev)
+    if ksum is None:
+        ksum = torch.empty((B, H, nbits), dtype=torch.int32, device=dev)
+    if out is None and (phases & 2):
+        out = torch.empty((B, Nq, H, dv), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib.sa_linear_attention_01_workspace_bytes(B, H, Nq, Nk, nbits, dv), dev)
+    _check(lib.sa_linear_attention_01(_ptr(q_codes), _ptr(k_codes), _ptr(v), _ptr(out), B, H, Nq, Nk, nbits, dv,
+                                      _f(eps), _ptr(kv), _ptr(ksum), phases, _ptr(workspace), _z(workspace.numel()),
+                                      _stream()))
+    return out, kv, ksum
+
+
+def sa_dwconv3x3(v, w, bias=None, out=None, accumulate=False):
+    """Depthwise 3x3 over the token grid: v [B, gh, gw, E], w [E, 3, 3]; adds to `out` when accumulate."""
+    B, gh, gw, E = v.shape
+    if out is None:
+        assert not accumulate
+        out = torch.empty_like(v)
+    _check(load_library().sa_dwconv3x3(_ptr(v), _ptr(w), _ptr(bias), _ptr(out), int(bool(accumulate)), B, gh, gw, E,
+                                       _stream()))
+    return out
 
 
 def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, out=None):

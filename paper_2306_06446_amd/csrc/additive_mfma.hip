@@ -88,8 +88,14 @@ __device__ inline void stage_transposed(const float *__restrict__ src, size_t ro
 // The three transposed K^T V planes, the sign table and some slack must fit the LDS of a CU.
 constexpr bool qkv_fits(int dv, int nbits) { return (size_t)3 * dv * (nbits + 8) * 2 + 4096 <= 150 * 1024; }
 
-// Two bf16 signs in one dword: +1.0 (0x3F80) where the bit of `lo` / `hi` at position `pos` is set, else -1.0.
+// Two bf16 code values in one dword: +1.0 (0x3F80) where the bit of `lo` / `hi` at position `pos` is set;
+// a clear bit stands for -1.0, or for 0.0 with ZO ({0,1} codes: the Add layer that skips zeros).
+template <bool ZO>
 __device__ inline uint32_t sign_pair(uint32_t lo, uint32_t hi, int pos) {
+    if (ZO) {
+        const uint32_t bl = __builtin_amdgcn_ubfe(lo, pos, 1), bh = __builtin_amdgcn_ubfe(hi, pos, 1);
+        return (bl * 0x3F80u) | (bh * 0x3F800000u);
+    }
     const uint32_t nl = __builtin_amdgcn_ubfe(~lo, pos, 1), nh = __builtin_amdgcn_ubfe(~hi, pos, 1);
     return 0x3F803F80u | (nl << 15) | (nh << 31);
 }
@@ -153,7 +159,7 @@ __device__ inline void ktv_store(const KtvChunk<DV> &c, uint64_t *kc, uint16_t *
     }
 }
 
-template <int DV>
+template <int DV, bool ZO>
 __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
                                                        float *__restrict__ dst, int H, int Nk, int W, int WB, int PH,
                                                        int splits, int tokens_per_block) {
@@ -218,8 +224,8 @@ __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restric
             uint32_t a0[4], a1[4];
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) {
-                a0[e2] = sign_pair(lo[2 * e2], lo[2 * e2 + 1], m);
-                a1[e2] = sign_pair(hi[2 * e2], hi[2 * e2 + 1], m);
+                a0[e2] = sign_pair<ZO>(lo[2 * e2], lo[2 * e2 + 1], m);
+                a1[e2] = sign_pair<ZO>(hi[2 * e2], hi[2 * e2 + 1], m);
             }
             const v8bf s0 = __builtin_bit_cast(v8bf, make_uint4(a0[0], a0[1], a0[2], a0[3]));
             const v8bf s1 = __builtin_bit_cast(v8bf, make_uint4(a1[0], a1[1], a1[2], a1[3]));
@@ -279,10 +285,13 @@ __global__ __launch_bounds__(256) void ktv_mfma_kernel(const uint64_t *__restric
 // Workgroup: one (b, h) and a range of token tiles; kQkvWaves wavefronts, TM 32-token tiles each per pass.
 constexpr int kQkvWaves = 8;
 
-template <int DV, int W, int TM>
+// den (optional, {0,1} codes): int32 [B*H, Nq], the row normaliser; the row then leaves as acc / (den + eps)
+// instead of scale * acc.
+template <int DV, int W, int TM, bool ZO>
 __global__ __launch_bounds__(kQkvWaves * 64) void qkv_mfma_kernel(const uint64_t *__restrict__ q_codes, const float *__restrict__ kv,
                                                        float *__restrict__ out, int H, int Nq, int blocks_per_bh,
-                                                       int tiles_per_block, float scale) {
+                                                       int tiles_per_block, float scale, const int32_t *__restrict__ den,
+                                                       float eps) {
     constexpr int JT = DV / 32;
     constexpr int NBITS = W * 64;
     constexpr int STRIDE = NBITS + 8;             // bf16 elements per transposed K^T V row
@@ -300,7 +309,7 @@ __global__ __launch_bounds__(kQkvWaves * 64) void qkv_mfma_kernel(const uint64_t
     if (tid < 256) {
         uint32_t d[4];
 #pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) d[e2] = sign_pair((uint32_t)tid, (uint32_t)tid >> 1, 2 * e2);
+        for (int e2 = 0; e2 < 4; ++e2) d[e2] = sign_pair<ZO>((uint32_t)tid, (uint32_t)tid >> 1, 2 * e2);
         sign_s[tid] = make_uint4(d[0], d[1], d[2], d[3]);
     }
     stage_transposed<DV>(kv + (size_t)bh * NBITS * DV, (size_t)DV, NBITS, NBITS, kvt_s[0], kvt_s[1], kvt_s[2], STRIDE, tid,
@@ -362,8 +371,9 @@ __global__ __launch_bounds__(kQkvWaves * 64) void qkv_mfma_kernel(const uint64_t
                 const int n = (tile0 + tm) * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
                 if (n < Nq) {
                     float *o = out + (((size_t)b * Nq + n) * H + h) * DV + m;
+                    const float f = den ? 1.0f / ((float)den[(size_t)bh * Nq + n] + eps) : scale;
 #pragma unroll
-                    for (int jt = 0; jt < JT; ++jt) o[jt * 32] = scale * acc[tm][jt][r];
+                    for (int jt = 0; jt < JT; ++jt) o[jt * 32] = f * acc[tm][jt][r];
                 }
             }
         }
@@ -371,7 +381,8 @@ __global__ __launch_bounds__(kQkvWaves * 64) void qkv_mfma_kernel(const uint64_t
 }
 
 template <int DV, int W>
-void launch_qkv_w(const uint64_t *q_codes, const float *kv, float *out, long BH, int H, int Nq, float scale, hipStream_t st) {
+void launch_qkv_w(const uint64_t *q_codes, const float *kv, float *out, long BH, int H, int Nq, float scale, bool zo,
+                  const int32_t *den, float eps, hipStream_t st) {
     constexpr int TM = DV == 128 ? 1 : 2;       // accumulators: TM * DV / 32 tiles of 16 registers
     const int n_tiles = (Nq + 31) / 32;
     // enough workgroups to fill the chip, but each stages all of K^T V once: several passes of its wavefronts
@@ -381,19 +392,22 @@ void launch_qkv_w(const uint64_t *q_codes, const float *kv, float *out, long BH,
     if (per_bh > max_per_bh) per_bh = max_per_bh;
     if (per_bh < 1) per_bh = 1;
     const int tiles_per_block = (int)((n_tiles + per_bh - 1) / per_bh);
-    qkv_mfma_kernel<DV, W, TM><<<dim3((unsigned)(BH * per_bh)), dim3(kQkvWaves * 64), 0, st>>>(q_codes, kv, out, H, Nq, (int)per_bh,
-                                                                                     tiles_per_block, scale);
+    const dim3 grid((unsigned)(BH * per_bh)), block(kQkvWaves * 64);
+    if (zo)
+        qkv_mfma_kernel<DV, W, TM, true><<<grid, block, 0, st>>>(q_codes, kv, out, H, Nq, (int)per_bh, tiles_per_block, scale, den, eps);
+    else
+        qkv_mfma_kernel<DV, W, TM, false><<<grid, block, 0, st>>>(q_codes, kv, out, H, Nq, (int)per_bh, tiles_per_block, scale, den, eps);
 }
 
 template <int DV>
-bool launch_qkv_dv(int W, const uint64_t *q_codes, const float *kv, float *out, long BH, int H, int Nq, float scale,
-                   hipStream_t st) {
+bool launch_qkv_dv(int W, const uint64_t *q_codes, const float *kv, float *out, long BH, int H, int Nq, float scale, bool zo,
+                   const int32_t *den, float eps, hipStream_t st) {
     switch (W) {
-        case 1: launch_qkv_w<DV, 1>(q_codes, kv, out, BH, H, Nq, scale, st); return true;
-        case 2: launch_qkv_w<DV, 2>(q_codes, kv, out, BH, H, Nq, scale, st); return true;
+        case 1: launch_qkv_w<DV, 1>(q_codes, kv, out, BH, H, Nq, scale, zo, den, eps, st); return true;
+        case 2: launch_qkv_w<DV, 2>(q_codes, kv, out, BH, H, Nq, scale, zo, den, eps, st); return true;
         case 4:
             if constexpr (qkv_fits(DV, 256)) {
-                launch_qkv_w<DV, 4>(q_codes, kv, out, BH, H, Nq, scale, st);
+                launch_qkv_w<DV, 4>(q_codes, kv, out, BH, H, Nq, scale, zo, den, eps, st);
                 return true;
             }
             return false;
@@ -434,28 +448,30 @@ AdditiveMfmaPlan plan_additive_mfma(int B, int H, int Nk, int nbits) {
 }
 
 int launch_ktv_mfma(const uint64_t *k_codes, const float *v, float *dst, int B, int H, int Nk, int nbits, int dv,
-                    const AdditiveMfmaPlan &p, hipStream_t st) {
+                    const AdditiveMfmaPlan &p, bool zero_one, hipStream_t st) {
     const int W = nbits / 64;
     const long blocks = (long)B * H * p.groups * p.splits;
     SA_REQUIRE(blocks < (1L << 31), SA_ERR_SHAPE, "sa_additive_attention: grid too large");
     const dim3 grid((unsigned)blocks), block(p.wb * p.ph * kWave);
+#define SA_KTV(DV_, ZO_) ktv_mfma_kernel<DV_, ZO_><<<grid, block, 0, st>>>(k_codes, v, dst, H, Nk, W, p.wb, p.ph, p.splits, p.tokens_per_block)
     switch (dv) {
-        case 32: ktv_mfma_kernel<32><<<grid, block, 0, st>>>(k_codes, v, dst, H, Nk, W, p.wb, p.ph, p.splits, p.tokens_per_block); break;
-        case 64: ktv_mfma_kernel<64><<<grid, block, 0, st>>>(k_codes, v, dst, H, Nk, W, p.wb, p.ph, p.splits, p.tokens_per_block); break;
-        default: ktv_mfma_kernel<128><<<grid, block, 0, st>>>(k_codes, v, dst, H, Nk, W, p.wb, p.ph, p.splits, p.tokens_per_block); break;
+        case 32: if (zero_one) SA_KTV(32, true); else SA_KTV(32, false); break;
+        case 64: if (zero_one) SA_KTV(64, true); else SA_KTV(64, false); break;
+        default: if (zero_one) SA_KTV(128, true); else SA_KTV(128, false); break;
     }
+#undef SA_KTV
     return check_launch("sa_additive_attention(K^T V)");
 }
 
 int launch_qkv_mfma(const uint64_t *q_codes, const float *kv, float *out, int B, int H, int Nq, int nbits, int dv,
-                    float scale, hipStream_t st) {
+                    float scale, bool zero_one, const int32_t *den, float eps, hipStream_t st) {
     const long BH = (long)B * H;
     const int W = nbits / 64;
     bool ok;
     switch (dv) {
-        case 32: ok = launch_qkv_dv<32>(W, q_codes, kv, out, BH, H, Nq, scale, st); break;
-        case 64: ok = launch_qkv_dv<64>(W, q_codes, kv, out, BH, H, Nq, scale, st); break;
-        default: ok = launch_qkv_dv<128>(W, q_codes, kv, out, BH, H, Nq, scale, st); break;
+        case 32: ok = launch_qkv_dv<32>(W, q_codes, kv, out, BH, H, Nq, scale, zero_one, den, eps, st); break;
+        case 64: ok = launch_qkv_dv<64>(W, q_codes, kv, out, BH, H, Nq, scale, zero_one, den, eps, st); break;
+        default: ok = launch_qkv_dv<128>(W, q_codes, kv, out, BH, H, Nq, scale, zero_one, den, eps, st); break;
     }
     SA_REQUIRE(ok, SA_ERR_UNSUPPORTED, "sa_additive_attention: unsupported code width for the matrix-core path");
     return check_launch("sa_additive_attention(Q(K^T V))");

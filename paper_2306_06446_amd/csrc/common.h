@@ -63,10 +63,12 @@ struct AdditiveMfmaPlan {
 bool additive_mfma_ktv_supported(int nbits, int dv);
 bool additive_mfma_qkv_supported(int nbits, int dv);
 AdditiveMfmaPlan plan_additive_mfma(int B, int H, int Nk, int nbits);
+// zero_one: a clear code bit stands for 0 instead of -1; den (with zero_one): int32 [B*H, Nq] row normaliser, the
+// output row is then acc / (den + eps) instead of scale * acc.
 int launch_ktv_mfma(const uint64_t *k_codes, const float *v, float *dst, int B, int H, int Nk, int nbits, int dv,
-                    const AdditiveMfmaPlan &p, hipStream_t st);
+                    const AdditiveMfmaPlan &p, bool zero_one, hipStream_t st);
 int launch_qkv_mfma(const uint64_t *q_codes, const float *kv, float *out, int B, int H, int Nq, int nbits, int dv,
-                    float scale, hipStream_t st);
+                    float scale, bool zero_one, const int32_t *den, float eps, hipStream_t st);
 
 }  // namespace sa
 

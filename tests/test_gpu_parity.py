@@ -503,3 +503,46 @@ def test_block_forward_matches_oracle(sa, cfg):
         # the same block on Shift weights decoded beforehand: the same kernels on the same planes
         o2, y2 = run_block(sa, cfg, inputs, prepared=True)
         assert np.array_equal(o2, o) and np.array_equal(y2, y)
+
+
+# ------------------------- {0,1} codes with the row normaliser, depthwise conv ----
+
+@pytest.mark.parametrize("valu", [0, 4], ids=["mfma", "valu"])
+@pytest.mark.parametrize("B,H,Nq,Nk,nbits,dv", [
+    (2, 3, 197, 197, 64, 64),      # c1 widths
+    (2, 1, 700, 700, 64, 32),      # c2 widths, ragged token tail
+    (1, 4, 1100, 1100, 256, 64),   # c5 widths
+    (1, 2, 70, 333, 128, 128),     # Nq != Nk, dv = 128
+    (1, 1, 5, 1, 64, 32),          # a single key
+    (1, 2, 300, 300, 192, 64),     # three words: VALU second phase
+])
+def test_linear_attention_01_matches_oracle(sa, B, H, Nq, Nk, nbits, dv, valu):
+    g = np.random.default_rng([81, Nq, Nk, nbits])
+    qc = wl.random_codes(5, (B, H, Nq), nbits)
+    kc = wl.random_codes(6, (B, H, Nk), nbits)
+    qc[0, 0, 0] = 0                                              # a query that selects nothing
+    v = g.standard_normal((B, Nk, H, dv)).astype(np.float32)
+    eps = 1.0
+    ref, kv_ref, ksum_ref, den_ref = oracle.linear_attention_01(qc, kc, v, nbits, eps)
+    out, kv, ksum = sa.sa_linear_attention_01(dev(qc), dev(kc), dev(v), eps, nbits, phases=3 | valu)
+    assert np.array_equal(host(ksum).astype(np.int64), ksum_ref)
+    assert_close(host(kv), kv_ref, *kv_tolerance(kv_ref), "{0,1} K^T V")
+    assert_close(host(out), ref, ATTN_RTOL, ATTN_ATOL, "normalised linear attention")
+    assert np.all(host(out)[0, 0, 0] == 0.0)
+    # the two phases separately give the same bits
+    _, kv1, ksum1 = sa.sa_linear_attention_01(None, dev(kc), dev(v), eps, nbits, phases=1 | valu)
+    out2, _, _ = sa.sa_linear_attention_01(dev(qc), None, None, eps, nbits, phases=2 | valu, kv=kv1, ksum=ksum1)
+    assert torch.equal(out2, out)
+
+
+@pytest.mark.parametrize("B,gh,gw,E", [(2, 14, 14, 192), (1, 56, 56, 32), (3, 5, 7, 12), (1, 1, 9, 64), (1, 4, 3, 1028)])
+def test_dwconv3x3_matches_oracle(sa, B, gh, gw, E):
+    g = np.random.default_rng([82, gh, gw, E])
+    v = g.standard_normal((B, gh, gw, E)).astype(np.float32)
+    w = g.standard_normal((E, 3, 3)).astype(np.float32)
+    bias = g.standard_normal(E).astype(np.float32)
+    ref = oracle.dwconv3x3(v, w, bias)
+    assert_close(host(sa.sa_dwconv3x3(dev(v), dev(w), dev(bias))), ref, 1e-5, 1e-5, "depthwise conv")
+    base = g.standard_normal((B, gh, gw, E)).astype(np.float32)
+    got = host(sa.sa_dwconv3x3(dev(v), dev(w), None, out=dev(base), accumulate=True))
+    assert_close(got, oracle.dwconv3x3(v, w) + base.astype(np.float64), 1e-5, 1e-5, "depthwise conv added to an output")
