@@ -220,6 +220,19 @@ def moe_dispatch(logits):
     return perm, expert_of, counts, gate
 
 
+def moe_balance_loss(logits, alpha, noise_std):
+    """Eq. 4 forward: (losses [2] = (L_IMP, L_LOAD), sums [2, E] = alpha-weighted importance and load)."""
+    logits = _c(logits, np.float32)
+    alpha = _c(alpha, np.float32)
+    T, E = logits.shape
+    assert alpha.shape == (E,) and E <= 64
+    losses = np.zeros(2, dtype=np.float64)
+    sums = np.zeros((2, E), dtype=np.float64)
+    _load().oracle_moe_balance_loss(_p(logits), ctypes.c_long(T), E, _p(alpha), ctypes.c_double(noise_std),
+                                    _p(losses), _p(sums))
+    return losses, sums
+
+
 def mult_mlp(x, rows, w1_half, w2_half):
     x = _c(x, np.float32)
     E = x.shape[1]

@@ -518,3 +518,41 @@ void oracle_dwconv3x3(const float *v, const float *w, const float *bias, int B, 
                     out[(((size_t)b * gh + y) * gw + x) * E + c] = s;
                 }
 }
+
+/* ------------------------------------------------------------------------
+ * Forward value of the latency-aware load-balancing loss (Eq. 4):
+ *   IMP_i  = alpha_i * sum_x p_i(x),     p = softmax(logits(x))
+ *   LOAD_i = alpha_i * sum_x q_i(x),     q_i(x) = P(p_i(x) + eps >= p_j(x) for all j != i)
+ *   L_IMP = SCV(IMP),  L_LOAD = SCV(LOAD),  SCV(u) = var(u) / mean(u)^2 over the experts
+ * The paper calls eps a noise proxy and gives no distribution; the reading
+ * taken is eps ~ N(0, noise_std^2) added to p_i alone, so
+ *   q_i(x) = Phi((p_i(x) - max_{j != i} p_j(x)) / noise_std)
+ * (Phi = standard normal distribution function), and the population variance
+ * (divide by the number of experts) in SCV.  sums: [2 * E] = IMP then LOAD.
+ * ------------------------------------------------------------------------ */
+void oracle_moe_balance_loss(const float *logits, long T, int E, const float *alpha, double noise_std,
+                             double *losses, double *sums) {
+    for (int i = 0; i < 2 * E; ++i) sums[i] = 0.0;
+    for (long t = 0; t < T; ++t) {
+        const float *l = logits + (size_t)t * E;
+        double p[64], mx = (double)l[0], den = 0.0;
+        for (int e = 1; e < E; ++e) if ((double)l[e] > mx) mx = (double)l[e];
+        for (int e = 0; e < E; ++e) { p[e] = exp((double)l[e] - mx); den += p[e]; }
+        for (int e = 0; e < E; ++e) p[e] /= den;
+        for (int e = 0; e < E; ++e) {
+            double other = -1.0;
+            for (int j = 0; j < E; ++j) if (j != e && p[j] > other) other = p[j];
+            const double z = (p[e] - other) / noise_std;
+            sums[e] += p[e];
+            sums[E + e] += 0.5 * erfc(-z / sqrt(2.0));
+        }
+    }
+    for (int k = 0; k < 2; ++k) {
+        double mean = 0.0, var = 0.0;
+        for (int e = 0; e < E; ++e) { sums[k * E + e] *= (double)alpha[e]; mean += sums[k * E + e]; }
+        mean /= (double)E;
+        for (int e = 0; e < E; ++e) { const double c = sums[k * E + e] - mean; var += c * c; }
+        var /= (double)E;
+        losses[k] = var / (mean * mean);
+    }
+}

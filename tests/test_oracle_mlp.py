@@ -227,3 +227,41 @@ def test_shift_weights_from_float_equals_library_log2_rounding():
     assert np.array_equal(nib >> 3, (w < 0).astype(np.uint8))
     inside = (np.abs(w) > 2.0**-7) & (np.abs(w) < 1.0)
     assert np.all(np.abs(np.log2(np.abs(w[inside])) - p_ref[inside]) <= 0.5)
+
+
+# ---------------------------------------- latency-aware balancing loss (Eq. 4) ---
+
+def test_balance_loss_closed_forms():
+    # equal logits, equal alpha: every expert gets T/2 of both sums -> both losses 0
+    logits = np.zeros((100, 2), dtype=np.float32)
+    losses, sums = oracle.moe_balance_loss(logits, np.array([0.5, 0.5], np.float32), 0.1)
+    assert np.allclose(sums, 25.0) and np.allclose(losses, 0.0, atol=1e-30)
+    # everything on expert 0 with certainty: the vector is (a T, 0): mean a T / 2, variance (a T / 2)^2 -> SCV 1
+    logits = np.tile(np.array([[40.0, -40.0]], np.float32), (64, 1))
+    losses, sums = oracle.moe_balance_loss(logits, np.array([0.3, 0.7], np.float32), 0.01)
+    assert np.allclose(sums[:, 0], 0.3 * 64, rtol=1e-6) and np.allclose(sums[:, 1], 0.0, atol=1e-12)
+    assert np.allclose(losses, 1.0, rtol=1e-6)
+    # latency-aware optimum: loads inversely proportional to alpha make the weighted vector flat -> loss 0
+    # 70 tokens certain for expert 1 (alpha 0.3), 30 certain for expert 0 (alpha 0.7)
+    logits = np.concatenate([np.tile([[-40.0, 40.0]], (70, 1)), np.tile([[40.0, -40.0]], (30, 1))]).astype(np.float32)
+    losses, sums = oracle.moe_balance_loss(logits, np.array([0.7, 0.3], np.float32), 0.01)
+    assert np.allclose(sums, 21.0, rtol=1e-6) and np.allclose(losses, 0.0, atol=1e-10)
+
+
+def test_balance_loss_equals_direct_formulas():
+    g = np.random.default_rng(63)
+    T, E = 500, 4
+    logits = g.standard_normal((T, E)).astype(np.float32)
+    alpha = np.array([0.4, 0.3, 0.2, 0.1], np.float32)
+    sigma = 0.05
+    losses, sums = oracle.moe_balance_loss(logits, alpha, sigma)
+    p = torch.softmax(torch.from_numpy(logits).double(), dim=1).numpy()
+    other = np.stack([np.delete(p, e, axis=1).max(axis=1) for e in range(E)], axis=1)
+    q = np.array([[0.5 * (1.0 + math.erf((p[t, e] - other[t, e]) / sigma / math.sqrt(2.0))) for e in range(E)]
+                  for t in range(T)])
+    imp, load = alpha.astype(np.float64) * p.sum(axis=0), alpha.astype(np.float64) * q.sum(axis=0)
+    assert np.allclose(sums[0], imp, rtol=1e-12) and np.allclose(sums[1], load, rtol=1e-10)
+    assert np.allclose(losses, [np.var(imp) / np.mean(imp) ** 2, np.var(load) / np.mean(load) ** 2], rtol=1e-10)
+    # with tiny noise the load is the top-1 count
+    _, sums0 = oracle.moe_balance_loss(logits, np.ones(E, np.float32), 1e-9)
+    assert np.allclose(sums0[1], np.bincount(p.argmax(axis=1), minlength=E), atol=1e-6)
