@@ -220,6 +220,21 @@ int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *
                     void *stream);
 
 /*
+ * Forward value of the latency-aware load-balancing loss (Eq. 4):
+ *   IMP_i  = alpha_i * sum_x p_i(x),   LOAD_i = alpha_i * sum_x q_i(x),   p = softmax(logits)
+ *   q_i(x) = Phi((p_i(x) - max_{j != i} p_j(x)) / noise_std)     (normal noise on p_i as the proxy)
+ *   losses[0] = SCV(IMP), losses[1] = SCV(LOAD),  SCV(u) = var(u) / mean(u)^2 (population variance)
+ * logits [T,E] fp32, alpha [E] fp32 (the latency coefficients Lat_i / sum Lat_j), all device
+ * memory; losses fp32 [2]; sums_or_null fp32 [2,E] = IMP then LOAD.  2 <= E <= 8, T > 0,
+ * noise_std > 0.  Token sums are taken per 256 tokens in fp32, then in fp64 in ascending order
+ * (deterministic).
+ */
+size_t sa_moe_balance_loss_workspace_bytes(long T, int E);
+int sa_moe_balance_loss(const float *logits, long T, int E, const float *alpha, float noise_std,
+                        float *losses, float *sums_or_null, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/*
  * Activation quantisation with a static per-tensor scale (appendix,
  * integer-arithmetic quantisation):  q = clamp(rne(x * inv_scale), -127, 127),
  * NaN -> 0.  One fp32 multiply and one round-to-nearest-even; bit-exact.

@@ -24,7 +24,7 @@ EXPORTS = [
     "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear", "sa_shift_linear_f32", "sa_layernorm_quant",
     "sa_shift_weights_from_float",
-    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
+    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_moe_balance_loss_workspace_bytes", "sa_moe_balance_loss", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
     "sa_block_forward", "sa_layer_workspace_bytes", "sa_layer_forward",
@@ -76,7 +76,7 @@ def load_library():
                 "g.build()'` first; there is no fallback path" % LIB_PATH)
         lib = ctypes.CDLL(LIB_PATH)
         lib.sa_last_error.restype = ctypes.c_char_p
-        for name in ("sa_additive_attention_workspace_bytes", "sa_linear_attention_01_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
+        for name in ("sa_moe_balance_loss_workspace_bytes", "sa_additive_attention_workspace_bytes", "sa_linear_attention_01_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
                      "sa_shift_linear_workspace_bytes", "sa_shift_planes_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
                      "sa_block_workspace_bytes", "sa_layer_workspace_bytes"):
@@ -325,6 +325,18 @@ def sa_moe_dispatch(logits, out=None, workspace=None):
     _check(lib.sa_moe_dispatch(_ptr(logits), _l(T), E, _ptr(perm), _ptr(expert_of), _ptr(counts),
                                _ptr(gate), _ptr(ws), _z(ws.numel()), _stream()))
     return perm, expert_of, counts, gate
+
+
+def sa_moe_balance_loss(logits, alpha, noise_std):
+    """Eq. 4 forward: returns (losses [2], sums [2, E]) as device tensors."""
+    lib = load_library()
+    T, E = logits.shape
+    losses = torch.empty(4, dtype=torch.float32, device=logits.device)[:2]
+    sums = torch.empty((2, E), dtype=torch.float32, device=logits.device)
+    ws = _workspace(lib.sa_moe_balance_loss_workspace_bytes(_l(T), E), logits.device)
+    _check(lib.sa_moe_balance_loss(_ptr(logits), _l(T), E, _ptr(alpha), _f(noise_std), _ptr(losses), _ptr(sums),
+                                   _ptr(ws), _z(ws.numel()), _stream()))
+    return losses, sums
 
 
 def sa_quantize_act(x, inv_scale, q=None):

@@ -122,6 +122,82 @@ __global__ __launch_bounds__(256) void combine_kernel(const float4 *__restrict__
     y[(size_t)t * E4 + c] = make_float4(g * v.x, g * v.y, g * v.z, g * v.w);
 }
 
+// ---- forward value of the balancing loss of Eq. 4 -------------------------------------------
+// Workgroup partial sums of p_i(x) and q_i(x) = Phi((p_i - max_{j != i} p_j) / noise_std) over 256 tokens,
+// then one workgroup adds the partials in ascending order in fp64 and forms the two SCV values.
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(kTok) void balance_partial_kernel(const float *__restrict__ logits, long T, int E,
+                                                               float inv_noise_std, float *__restrict__ partial) {
+    __shared__ float red[kTok / 64][2 * kMaxE];
+    const long t = (long)blockIdx.x * kTok + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float p[kMaxE], q[kMaxE];
+#pragma unroll
+    for (int e = 0; e < kMaxE; ++e) p[e] = q[e] = 0.0f;
+    if (t < T) {
+        const float *l = logits + (size_t)t * E;
+        float lb = l[0];
+#pragma unroll
+        for (int e = 1; e < kMaxE; ++e)
+            if (e < E) lb = fmaxf(lb, l[e]);
+        float den = 0.0f;
+#pragma unroll
+        for (int e = 0; e < kMaxE; ++e)
+            if (e < E) { p[e] = expf(l[e] - lb); den += p[e]; }
+        const float r = 1.0f / den;
+#pragma unroll
+        for (int e = 0; e < kMaxE; ++e) p[e] *= r;
+#pragma unroll
+        for (int e = 0; e < kMaxE; ++e) {
+            if (e >= E) continue;
+            float other = -1.0f;
+#pragma unroll
+            for (int j = 0; j < kMaxE; ++j)
+                if (j != e && j < E) other = fmaxf(other, p[j]);
+            q[e] = 0.5f * erfcf(-(p[e] - other) * inv_noise_std * 0.70710678118654752f);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < kMaxE; ++e) {
+        if (e >= E) continue;
+        const float sp = wave_sum_f(p[e]), sq = wave_sum_f(q[e]);
+        if (lane == 0) { red[wave][e] = sp; red[wave][kMaxE + e] = sq; }
+    }
+    __syncthreads();
+    if (threadIdx.x < 2 * kMaxE) {
+        float s = 0.0f;
+        for (int w = 0; w < kTok / 64; ++w) s += red[w][threadIdx.x];
+        partial[(size_t)blockIdx.x * 2 * kMaxE + threadIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(64) void balance_final_kernel(const float *__restrict__ partial, long n_blocks, int E,
+                                                           const float *__restrict__ alpha, float *__restrict__ losses,
+                                                           float *__restrict__ sums) {
+    __shared__ double tot[2 * kMaxE];
+    const int i = threadIdx.x;                 // i < 16: (kind, expert) = (i / 8, i % 8)
+    if (i < 2 * kMaxE) {
+        double s = 0.0;
+        for (long b = 0; b < n_blocks; ++b) s += (double)partial[(size_t)b * 2 * kMaxE + i];
+        const int e = i % kMaxE;
+        tot[i] = e < E ? s * (double)alpha[e] : 0.0;
+        if (sums && e < E) sums[(i / kMaxE) * E + e] = (float)tot[i];
+    }
+    __syncthreads();
+    if (i < 2) {
+        double mean = 0.0, var = 0.0;
+        for (int e = 0; e < E; ++e) mean += tot[i * kMaxE + e];
+        mean /= (double)E;
+        for (int e = 0; e < E; ++e) { const double c = tot[i * kMaxE + e] - mean; var += c * c; }
+        losses[i] = (float)(var / (double)E / (mean * mean));
+    }
+}
+
 }  // namespace
 
 extern "C" size_t sa_moe_dispatch_workspace_bytes(long T, int E) {
@@ -196,4 +272,35 @@ extern "C" int sa_combine_rows(const float *src, const sa_rows *rows, const floa
     combine_kernel<<<dim3((unsigned)blocks), dim3(256), 0, sa::as_stream(stream)>>>(
         reinterpret_cast<const float4 *>(src), E / 4, sel, gate_or_null, reinterpret_cast<float4 *>(y));
     return sa::check_launch("sa_combine_rows");
+}
+
+extern "C" size_t sa_moe_balance_loss_workspace_bytes(long T, int E) {
+    if (T <= 0 || E < 2 || E > kMaxE) return 0;
+    return (size_t)((T + kTok - 1) / kTok) * 2 * kMaxE * sizeof(float);
+}
+
+extern "C" int sa_moe_balance_loss(const float *logits, long T, int E, const float *alpha, float noise_std,
+                                   float *losses, float *sums_or_null, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(T > 0, SA_ERR_INVALID, "sa_moe_balance_loss: T must be positive (the loss of no tokens is 0 / 0)");
+    SA_REQUIRE(E >= 2 && E <= kMaxE, SA_ERR_SHAPE, "sa_moe_balance_loss: 2 to 8 experts (got %d)", E);
+    SA_REQUIRE(noise_std > 0.0f && noise_std - noise_std == 0.0f, SA_ERR_INVALID,
+               "sa_moe_balance_loss: noise_std must be positive and finite");
+    SA_REQUIRE(logits && alpha && losses, SA_ERR_INVALID, "sa_moe_balance_loss: NULL buffer");
+    SA_REQUIRE(sa::aligned16(logits) && sa::aligned16(alpha) && sa::aligned16(losses) && sa::aligned16(sums_or_null) &&
+                   sa::aligned16(workspace),
+               SA_ERR_ALIGN, "sa_moe_balance_loss: pointers must be 16-byte aligned");
+    const size_t need = sa_moe_balance_loss_workspace_bytes(T, E);
+    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
+               "sa_moe_balance_loss: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    const long n_blocks = (T + kTok - 1) / kTok;
+    SA_REQUIRE(n_blocks < (1L << 31), SA_ERR_SHAPE, "sa_moe_balance_loss: T too large");
+    hipStream_t st = sa::as_stream(stream);
+    float *partial = static_cast<float *>(workspace);
+    balance_partial_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(logits, T, E, 1.0f / noise_std, partial);
+    int rc = sa::check_launch("sa_moe_balance_loss(partial sums)");
+    if (rc != SA_OK) return rc;
+    balance_final_kernel<<<dim3(1), dim3(64), 0, st>>>(partial, n_blocks, E, alpha, losses, sums_or_null);
+    return sa::check_launch("sa_moe_balance_loss(final)");
 }

@@ -546,3 +546,27 @@ def test_dwconv3x3_matches_oracle(sa, B, gh, gw, E):
     base = g.standard_normal((B, gh, gw, E)).astype(np.float32)
     got = host(sa.sa_dwconv3x3(dev(v), dev(w), None, out=dev(base), accumulate=True))
     assert_close(got, oracle.dwconv3x3(v, w) + base.astype(np.float64), 1e-5, 1e-5, "depthwise conv added to an output")
+
+
+# ------------------------------------------------ balancing loss (Eq. 4), forward ----
+
+@pytest.mark.parametrize("T,E,sigma", [(197, 2, 0.1), (12608, 2, 0.05), (3001, 4, 0.02), (1000, 8, 0.2), (1, 2, 1.0)])
+def test_moe_balance_loss_matches_oracle(sa, T, E, sigma):
+    logits = np.random.default_rng([83, T, E]).standard_normal((T, E)).astype(np.float32)
+    alpha = (np.arange(E, 0, -1) / np.arange(E, 0, -1).sum()).astype(np.float32)
+    ref_losses, ref_sums = oracle.moe_balance_loss(logits, alpha, sigma)
+    losses, sums = sa.sa_moe_balance_loss(dev(logits), dev(alpha), sigma)
+    assert_close(host(sums), ref_sums, 2e-5, 1e-6, "importance / load sums")
+    assert_close(host(losses), ref_losses, 2e-4, 1e-7, "L_IMP, L_LOAD")
+
+
+def test_moe_balance_loss_on_the_config_router(sa):
+    """Config 4's constructed router: 70 % of the tokens favour the Shift expert; with alpha = (0.7, 0.3)
+    (Mult : Shift latency 7 : 3) the weighted loads are nearly flat and L_LOAD is near 0."""
+    logits = wl.router_logits(wl.C4)
+    alpha = np.array([0.7, 0.3], dtype=np.float32)
+    ref_losses, ref_sums = oracle.moe_balance_loss(logits, alpha, 0.01)
+    losses, sums = sa.sa_moe_balance_loss(dev(logits), dev(alpha), 0.01)
+    assert_close(host(sums), ref_sums, 2e-5, 1e-6, "sums")
+    assert_close(host(losses), ref_losses, 2e-4, 1e-7, "losses")
+    assert ref_losses[1] < 1e-3
