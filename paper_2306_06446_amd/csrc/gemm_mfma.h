@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
     constexpr int EPI_BYTES = SLAB_BYTES + Store::kTableBytes;
     constexpr int LOADS = A_INSTR + NP * B_INSTR;       // direct loads per wavefront and stage
     constexpr int LDS_BYTES = NS * STAGE > EPI_BYTES ? NS * STAGE : EPI_BYTES;
-    static_assert(NS == 2 || NS == 3, "ring of two or three stages");
+    static_assert(NS >= 2 && NS <= 4, "ring of two to four stages");
     static_assert(LDS_BYTES * OCC <= 160 * 1024, "OCC workgroups of this tile do not fit the LDS of a CU");
     __shared__ __attribute__((aligned(1024))) uint8_t lds[LDS_BYTES];
 
@@ -268,13 +268,19 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
 #pragma unroll
     for (int q = 0; q < NS; ++q)
         if (q < n_stages) issue_stage(q, q * kStageBytes);
+    // Wait until all but the `later` most recently issued stages of this wavefront's loads have landed.
+    auto wait_all_but = [&](int later) {
+        if (NS >= 4 && later >= 3)
+            wait_loads_in_flight<(NS >= 4 ? 3 : 0) * LOADS>();
+        else if (NS >= 3 && later == 2)
+            wait_loads_in_flight<(NS >= 3 ? 2 : 0) * LOADS>();
+        else if (later == 1)
+            wait_loads_in_flight<LOADS>();
+        else
+            wait_loads_in_flight<0>();
+    };
     // this wavefront's loads of stage 0 have landed (later stages may still be in flight)
-    if (NS == 3 && n_stages > 2)
-        wait_loads_in_flight<2 * LOADS>();
-    else if (n_stages > 1)
-        wait_loads_in_flight<LOADS>();
-    else
-        wait_loads_in_flight<0>();
+    wait_all_but((n_stages < NS ? n_stages : NS) - 1);
     __syncthreads();                             // ... and everyone's
     read_frags(lds, 0, af[0], bf[0]);
     int buf = 0, prev = NS - 1;                  // ring slots of stage s and of stage s-1
@@ -286,11 +292,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
             if constexpr (kk + 1 < KK) {
                 read_frags(cur, kk + 1, af[(kk + 1) & 1], bf[(kk + 1) & 1]);
             } else if (s + 1 < n_stages) {
-                // stage s+1 has landed (this wavefront's part); with a ring of three, stage s+2 may be in flight
-                if (NS == 3 && s + 2 < n_stages)
-                    wait_loads_in_flight<LOADS>();
-                else
-                    wait_loads_in_flight<0>();
+                // stage s+1 has landed (this wavefront's part); stages s+2 .. s+NS-1 may still be in flight
+                wait_all_but((s + NS - 1 < n_stages ? s + NS - 1 : n_stages - 1) - (s + 1));
                 __syncthreads();                 // everyone's has, and everyone holds its last fragments of stage s
                 read_frags(lds + nxt * STAGE, 0, af[0], bf[0]);
             }

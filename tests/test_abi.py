@@ -96,3 +96,46 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     lib.sa_block_workspace_bytes.restype = ctypes.c_size_t
     assert lib.sa_block_workspace_bytes(null) == 0
     assert lib.sa_block_forward(null, null) == -1
+
+
+def test_argument_errors_of_the_layer_entry_points_without_a_gpu(lib):
+    null = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    f = ctypes.c_float(1.0)
+    T = ctypes.c_long(10)
+    z0 = ctypes.c_size_t(0)
+    # LayerNorm: E not a multiple of 4, too wide, no output, logits without weights, misaligned
+    ln = lib.sa_layernorm_quant
+    assert ln(fake, T, 66, fake, fake, f, f, fake, null, null, null, null, 0, null, null) == -2
+    assert ln(fake, T, 16384, fake, fake, f, f, fake, null, null, null, null, 0, null, null) == -6
+    assert ln(fake, T, 64, fake, fake, f, f, null, null, null, null, null, 0, null, null) == -1
+    assert ln(fake, T, 64, fake, fake, f, f, null, null, null, null, null, 2, fake, null) == -1
+    assert ln(fake, T, 64, fake, fake, f, f, null, null, null, fake, fake, 9, fake, null) == -2
+    assert ln(odd, T, 64, fake, fake, f, f, fake, null, null, null, null, 0, null, null) == -3
+    assert ln(null, ctypes.c_long(0), 64, null, null, f, f, null, null, null, null, null, 0, null, null) == 0
+    # fp32 shift Linear: parts out of range, N not divisible, residual with parts > 1, missing part pointer
+    lin = lib.sa_shift_linear_f32
+    assert lin(fake, fake, T, 64, 24, 0, f, null, 4, fake, fake, fake, null, z0, null) == -1
+    assert lin(fake, fake, T, 64, 20, 0, f, null, 3, fake, fake, fake, null, z0, null) == -2
+    assert lin(fake, fake, T, 64, 24, 0, f, fake, 2, fake, fake, null, null, z0, null) == -1
+    assert lin(fake, fake, T, 64, 24, 0, f, null, 2, fake, null, null, null, z0, null) == -1
+    assert lin(fake, fake, T, 64, 24, 1, f, null, 1, fake, null, null, null, z0, null) == -4
+    # weight conversion, {0,1} attention, depthwise convolution, balancing loss
+    assert lib.sa_shift_weights_from_float(fake, 4, 12, fake, null) == -2
+    assert lib.sa_shift_weights_from_float(null, 4, 16, fake, null) == -1
+    la = lib.sa_linear_attention_01
+    assert la(fake, fake, fake, fake, 1, 1, 4, 4, 64, 64, ctypes.c_float(0.0), fake, fake, 3, fake, ctypes.c_size_t(1 << 20), null) == -1
+    assert la(fake, fake, fake, fake, 1, 1, 4, 4, 65, 64, f, fake, fake, 3, fake, ctypes.c_size_t(1 << 20), null) == -2
+    assert la(fake, fake, fake, fake, 1, 1, 4, 4, 64, 64, f, fake, fake, 3, null, z0, null) == -4
+    assert lib.sa_dwconv3x3(fake, fake, null, fake, 0, 1, 4, 4, 6, null) == -2
+    assert lib.sa_dwconv3x3(fake, fake, null, fake, 0, 1, 4, 4, 8, null) == -1     # out == v
+    assert lib.sa_dwconv3x3(fake, fake, null, ctypes.c_void_p(0x2000), 0, 0, 4, 4, 8, null) == 0
+    bl = lib.sa_moe_balance_loss
+    assert bl(fake, T, 9, fake, f, fake, null, fake, ctypes.c_size_t(1 << 20), null) == -2
+    assert bl(fake, T, 2, fake, ctypes.c_float(0.0), fake, null, fake, ctypes.c_size_t(1 << 20), null) == -1
+    assert bl(fake, T, 2, fake, f, fake, null, null, z0, null) == -4
+    # stages flag of the experts
+    lib.sa_layer_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.sa_layer_workspace_bytes(null) == 0
+    assert lib.sa_layer_forward(null, null) == -1
