@@ -4,8 +4,9 @@
 // Dispatch is a stable partition of the token ids by expert, built without atomics so
 // that the lists are unique and reproducible: (1) every workgroup of 256 tokens takes
 // the decisions (raw-logit argmax, ties to the lowest index), the gate values and its
-// per-expert histogram; (2) one small workgroup turns the histograms into start offsets;
-// (3) every workgroup ranks its tokens with wavefront ballots / popcounts and writes them.
+// per-expert histogram; (2) one small workgroup turns the histograms into start offsets (for up
+// to 131072 tokens every workgroup of step 3 sums the few histograms itself instead, which saves
+// a launch); (3) every workgroup ranks its tokens with wavefront ballots / popcounts and writes them.
 #include "common.h"
 
 namespace {
@@ -13,6 +14,7 @@ namespace {
 using namespace sa;
 constexpr int kMaxE = 8;
 constexpr int kTok = 256;   // tokens per workgroup
+constexpr long kSelfScanBlocks = 512;   // up to this many workgroups (131072 tokens) the scatter pass sums the histograms itself
 
 __device__ inline uint64_t lanemask_lt(int lane) { return (lane == 0) ? 0ull : (~0ull >> (64 - lane)); }
 
@@ -49,35 +51,88 @@ __global__ __launch_bounds__(kTok) void route_kernel(const float *__restrict__ l
     }
 }
 
-// block_base[blk][e] = first position in perm of expert e's tokens of workgroup blk.
-__global__ __launch_bounds__(64) void offsets_kernel(const int32_t *__restrict__ block_counts,
-                                                     int32_t *__restrict__ block_base,
-                                                     int32_t *__restrict__ counts, long n_blocks, int E) {
-    __shared__ int32_t total[kMaxE];
-    const int e = threadIdx.x;
-    if (e < E) {
-        int s = 0;
-        for (long b = 0; b < n_blocks; ++b) s += block_counts[(size_t)b * E + e];
-        total[e] = s;
-        counts[e] = s;
-    }
-    __syncthreads();
-    if (e < E) {
-        int start = 0;
-        for (int i = 0; i < e; ++i) start += total[i];
-        for (long b = 0; b < n_blocks; ++b) {
-            block_base[(size_t)b * E + e] = start;
-            start += block_counts[(size_t)b * E + e];
+// block_base[blk][e] = first position in perm of expert e's tokens of workgroup blk: an exclusive scan
+// of the per-workgroup histograms, expert by expert, 256 workgroups' counts per pass of one workgroup.
+__global__ __launch_bounds__(256) void offsets_kernel(const int32_t *__restrict__ block_counts,
+                                                      int32_t *__restrict__ block_base,
+                                                      int32_t *__restrict__ counts, long n_blocks, int E) {
+    __shared__ int32_t wave_tot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int start = 0;                                     // position of the first token of (expert e, chunk)
+    for (int e = 0; e < E; ++e) {
+        const int first = start;
+        for (long b0 = 0; b0 < n_blocks; b0 += 256) {
+            const long b = b0 + tid;
+            const int c = b < n_blocks ? block_counts[(size_t)b * E + e] : 0;
+            int incl = c;                              // inclusive scan inside the wavefront
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int up = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += up;
+            }
+            __syncthreads();                           // wave_tot of the previous pass has been read
+            if (lane == 63) wave_tot[wave] = incl;
+            __syncthreads();
+            int before = 0, all = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                if (w < wave) before += wave_tot[w];
+                all += wave_tot[w];
+            }
+            if (b < n_blocks) block_base[(size_t)b * E + e] = start + before + incl - c;
+            start += all;
         }
+        if (tid == 0) counts[e] = start - first;
     }
 }
 
+// block_base == nullptr: every workgroup sums the histograms itself (few workgroups: cheaper than a launch of
+// the scan in between) - base[e] = all tokens of lower experts + expert e's tokens of lower workgroups - and
+// workgroup 0 also writes counts.
 __global__ __launch_bounds__(kTok) void scatter_kernel(const int32_t *__restrict__ expert_of, long T, int E,
                                                        const int32_t *__restrict__ block_base,
+                                                       const int32_t *__restrict__ block_counts, int32_t *__restrict__ counts,
                                                        int32_t *__restrict__ perm) {
     __shared__ int32_t wave_cnt[kTok / 64][kMaxE];
+    __shared__ int32_t red[kTok / 64][2 * kMaxE];
+    __shared__ int32_t base_s[kMaxE];
     const long t = (long)blockIdx.x * kTok + threadIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (block_base == nullptr) {
+        int below[kMaxE], all[kMaxE];                  // this thread's share of the two sums per expert
+#pragma unroll
+        for (int e = 0; e < kMaxE; ++e) below[e] = all[e] = 0;
+        for (long b = threadIdx.x; b < (long)gridDim.x; b += kTok) {
+#pragma unroll
+            for (int e = 0; e < kMaxE; ++e) {
+                if (e >= E) continue;
+                const int c = block_counts[(size_t)b * E + e];
+                all[e] += c;
+                below[e] += b < (long)blockIdx.x ? c : 0;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < kMaxE; ++e) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                below[e] += __shfl_xor(below[e], off, 64);
+                all[e] += __shfl_xor(all[e], off, 64);
+            }
+            if (lane == 0) { red[wave][e] = below[e]; red[wave][kMaxE + e] = all[e]; }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int start = 0;
+            for (int e = 0; e < E; ++e) {
+                int bl = 0, al = 0;
+                for (int w = 0; w < kTok / 64; ++w) { bl += red[w][e]; al += red[w][kMaxE + e]; }
+                base_s[e] = start + bl;
+                if (blockIdx.x == 0) counts[e] = al;
+                start += al;
+            }
+        }
+        __syncthreads();
+    }
     const int mine = (t < T) ? expert_of[t] : -1;
     int rank = 0;
     for (int e = 0; e < E; ++e) {
@@ -89,7 +144,8 @@ __global__ __launch_bounds__(kTok) void scatter_kernel(const int32_t *__restrict
     if (mine >= 0) {
         int before = 0;
         for (int w = 0; w < wave; ++w) before += wave_cnt[w][mine];
-        perm[block_base[(size_t)blockIdx.x * E + mine] + before + rank] = (int32_t)t;
+        const int base = block_base ? block_base[(size_t)blockIdx.x * E + mine] : base_s[mine];
+        perm[base + before + rank] = (int32_t)t;
     }
 }
 
@@ -229,10 +285,14 @@ extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm
     route_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(logits, T, E, expert_of, gate, block_counts);
     int rc = sa::check_launch("sa_moe_dispatch(route)");
     if (rc != SA_OK) return rc;
-    offsets_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, block_base, counts, n_blocks, E);
+    if (n_blocks <= kSelfScanBlocks) {
+        scatter_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(expert_of, T, E, nullptr, block_counts, counts, perm);
+        return sa::check_launch("sa_moe_dispatch(scatter)");
+    }
+    offsets_kernel<<<dim3(1), dim3(256), 0, st>>>(block_counts, block_base, counts, n_blocks, E);
     rc = sa::check_launch("sa_moe_dispatch(offsets)");
     if (rc != SA_OK) return rc;
-    scatter_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(expert_of, T, E, block_base, perm);
+    scatter_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(expert_of, T, E, block_base, block_counts, counts, perm);
     return sa::check_launch("sa_moe_dispatch(scatter)");
 }
 
