@@ -51,6 +51,14 @@ __device__ inline uint32_t requant_index(int32_t acc, float rq_finite) {
     return __builtin_bit_cast(uint32_t, t + 12583040.0f) & 0xFFu;
 }
 
+// requant_code as the byte of the int8 code, for a float that may be anything: clamp + magic add (three vector
+// operations) and one select for NaN (a median with a NaN operand is not 0).
+__device__ inline uint32_t requant_byte(float t) {
+    const float c = __builtin_amdgcn_fmed3f(t, -127.0f, 127.0f);
+    const uint32_t idx = __builtin_bit_cast(uint32_t, c + 12583040.0f) & 0xFFu;     // code + 128
+    return (t != t) ? 0u : (idx ^ 0x80u);
+}
+
 // NaN -> 0 (every product is NaN -> code 0, as 0 * acc), +-Inf -> +-FLT_MAX (same clamped codes; 0 * acc = 0 -> code 0,
 // where Inf * 0 = NaN -> code 0 as well).
 inline float requant_scale_finite(float s) {

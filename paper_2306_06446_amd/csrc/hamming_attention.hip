@@ -102,48 +102,82 @@ struct TableEntry {
     float p;
 };
 
-// Row sums meet, then every output form leaves in whole 16- / 8- / 4-byte pieces of a row.
+// Row sums meet, then every output form leaves in whole 16-byte pieces of a row.  The fp32 rows go out
+// straight from the registers (after the transpose a quad-aligned group of lanes covers 128 contiguous
+// bytes of a row).  The int8 and fp16 forms are narrower than that: they are collected per wavefront in
+// LDS (`stage_q`, `stage_h`: the V planes, free by now), 16 rows at a time, and leave as 16 bytes per lane,
+// so that a store covers a head's whole 64- or 128-byte row piece instead of 4- and 8-byte crumbs.
 template <int DV>
 __device__ inline void write_outputs(v16f (&acc)[DV / 32], float den, float *den_s, float *__restrict__ out,
                                      int8_t *__restrict__ xq, _Float16 *__restrict__ xh, float act_inv_scale, int b,
-                                     int h, int H, int Nq, int chunk, int wave, int lane) {
+                                     int h, int H, int Nq, int chunk, int wave, int lane, uint8_t *stage_q,
+                                     uint8_t *stage_h) {
     constexpr int JT = DV / 32;
     const int i_loc = lane & 31, kg = lane >> 5;
     // row sums: the two half-wavefronts hold different keys of the same 32 queries
     den += __shfl_xor(den, 32);
     if (lane < 32) den_s[wave * 32 + lane] = den;
-    __syncthreads();
     // A lane holds one column of four consecutive rows per register quartet; after a 4 x 4
-    // transpose inside each quad of lanes it holds four consecutive columns of one row, and every
-    // output form leaves in whole 16- / 8- / 4-byte pieces of a row.
+    // transpose inside each quad of lanes it holds four consecutive columns of one row.
     const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
     const int q4 = lane & 3;
+    uint8_t *my_q = stage_q + wave * 16 * DV;
+    uint8_t *my_h = stage_h + wave * 16 * DV * 2;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int row = 8 * g + 4 * kg + q4;                  // the row this lane holds after the transpose
-        const int qo = q_tile0 + row;
-        const float inv = 1.0f / den_s[wave * 32 + row];
-        const size_t at = (((size_t)b * Nq + min(qo, Nq - 1)) * H + h) * DV + (i_loc & ~3);
+    for (int half = 0; half < 2; ++half) {
+        __syncthreads();                                      // row sums are there; the staging rows are free
 #pragma unroll
-        for (int jt = 0; jt < JT; ++jt) {
-            float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
-            transpose_in_quad(x, q4);
-            if (qo < Nq) {
+        for (int gg = 0; gg < 2; ++gg) {
+            const int g = 2 * half + gg;
+            const int row16 = 8 * gg + 4 * kg + q4;               // row inside this half
+            const int row = 16 * half + row16;                    // the row this lane holds after the transpose
+            const int qo = q_tile0 + row;
+            const float inv = 1.0f / den_s[wave * 32 + row];
+            const size_t at = (((size_t)b * Nq + min(qo, Nq - 1)) * H + h) * DV + (i_loc & ~3);
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) {
+                float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
+                transpose_in_quad(x, q4);
                 const float4 val = make_float4(x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv);
-                *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
+                if (qo < Nq) *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
                 // what the MLP reads: the int8 codes of the activation quantiser, and the fp16 rounding
+                const int col = jt * 32 + (i_loc & ~3);
                 if (xq) {
-                    const uint32_t c0 = (uint8_t)sa::requant_code(val.x * act_inv_scale);
-                    const uint32_t c1 = (uint8_t)sa::requant_code(val.y * act_inv_scale);
-                    const uint32_t c2b = (uint8_t)sa::requant_code(val.z * act_inv_scale);
-                    const uint32_t c3 = (uint8_t)sa::requant_code(val.w * act_inv_scale);
-                    *reinterpret_cast<uint32_t *>(xq + at + jt * 32) = c0 | (c1 << 8) | (c2b << 16) | (c3 << 24);
+                    const uint32_t c0 = sa::requant_byte(val.x * act_inv_scale);
+                    const uint32_t c1 = sa::requant_byte(val.y * act_inv_scale);
+                    const uint32_t c2b = sa::requant_byte(val.z * act_inv_scale);
+                    const uint32_t c3 = sa::requant_byte(val.w * act_inv_scale);
+                    *reinterpret_cast<uint32_t *>(my_q + row16 * DV + col) = c0 | (c1 << 8) | (c2b << 16) | (c3 << 24);
                 }
                 if (xh) {
                     v4h hv;
                     hv[0] = (_Float16)val.x; hv[1] = (_Float16)val.y; hv[2] = (_Float16)val.z; hv[3] = (_Float16)val.w;
-                    *reinterpret_cast<v4h *>(xh + at + jt * 32) = hv;
+                    *reinterpret_cast<v4h *>(my_h + (row16 * DV + col) * 2) = hv;
                 }
+            }
+        }
+        if (xq == nullptr && xh == nullptr) continue;
+        __syncthreads();
+        if (xq) {
+            constexpr int CPR = DV / 16;                          // 16-byte pieces per row
+#pragma unroll
+            for (int c = lane; c < 16 * CPR; c += 64) {
+                const int r = c / CPR, cc = c % CPR;
+                const int qo = q_tile0 + 16 * half + r;
+                if (qo < Nq)
+                    *reinterpret_cast<uint4 *>(xq + (((size_t)b * Nq + qo) * H + h) * DV + cc * 16) =
+                        *reinterpret_cast<const uint4 *>(my_q + r * DV + cc * 16);
+            }
+        }
+        if (xh) {
+            constexpr int CPR = DV / 8;
+#pragma unroll
+            for (int c = lane; c < 16 * CPR; c += 64) {
+                const int r = c / CPR, cc = c % CPR;
+                const int qo = q_tile0 + 16 * half + r;
+                if (qo < Nq)
+                    *reinterpret_cast<uint4 *>(xh + (((size_t)b * Nq + qo) * H + h) * DV + cc * 8) =
+                        *reinterpret_cast<const uint4 *>(my_h + (r * DV + cc * 8) * 2);
             }
         }
     }
@@ -289,7 +323,8 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
         if (n_full < n) step(n_full, n, std::true_type{});
     }
 
-    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane);
+    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane,
+                      reinterpret_cast<uint8_t *>(vth_s), reinterpret_cast<uint8_t *>(vtl_s));
 }
 
 // ---- the same attention with the scores on the matrix cores as well ------------------------------
@@ -488,7 +523,8 @@ __global__ __launch_bounds__(kMaxWaves *kWave, (DV <= 64 && W <= 2) ? 4 : 2) voi
         if (n_full < n) step(n_full, n, std::true_type{});
     }
 
-    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane);
+    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane,
+                      reinterpret_cast<uint8_t *>(vth_s), reinterpret_cast<uint8_t *>(vtl_s));
 }
 
 // Optional dump of the integer scores, one thread per (query, key) pair.
