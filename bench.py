@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--layer", action="store_true",
                     help="time the complete block of Eq. 2 (sa_layer_forward: LayerNorms, the four attention Linears "
                          "as shift layers, residuals, router) on tokens of the chosen configuration's shape")
+    ap.add_argument("--sign-hash", action="store_true",
+                    help="with --layer: the sign-hash variant (no projection, nbits = head width), whose code bits are "
+                         "taken in the epilogue of the fused Q/K/V projection")
     ap.add_argument("--zero-one", action="store_true",
                     help="time the {0,1}-code normalised linear attention with the depthwise convolution on V "
                          "(sa_linear_attention_01 + sa_dwconv3x3) at the chosen configuration's attention shape (c2, c5)")
@@ -426,6 +429,9 @@ def bench_zero_one(args, sa, wl, torch, np, cfg):
 def bench_layer(args, sa, wl, torch, np, cfg):
     """The complete block of Eq. 2 (sa_layer_forward) and each of its kernels through the stage entry points."""
     assert cfg.E, "--layer needs a configuration with an MLP (c1, c4, c5)"
+    if args.sign_hash:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, nbits=cfg.E // cfg.H, name=cfg.name + "-sign-hash")
     T, E, H, hid = cfg.T, cfg.E, cfg.H, cfg.hid
     moe = cfg.shift_frac is not None
     lp, p = wl.layer_params(cfg), wl.mlp_params(cfg)
@@ -443,7 +449,8 @@ def bench_layer(args, sa, wl, torch, np, cfg):
                   moe=int(moe), shift_variant=var, eps=lp.eps, ln_inv_scale=lp.ln_inv_scale, qkv_scale=lp.qkv_scale,
                   attn_scale=scale, act_inv_scale=p.act_inv_scale, o_scale=lp.o_scale, requant_scale=p.requant_scale,
                   out_scale=p.out_scale, gamma1=dev(lp.gamma1), beta1=dev(lp.beta1), gamma2=dev(lp.gamma2),
-                  beta2=dev(lp.beta2), wqkv=wqkv, wo=wo, proj=dev(wl.proj(cfg)), w1=w1, w2=w2, lut=dev(p.lut))
+                  beta2=dev(lp.beta2), wqkv=wqkv, wo=wo, proj=None if args.sign_hash else dev(wl.proj(cfg)), w1=w1, w2=w2,
+                  lut=dev(p.lut))
     if moe:
         shared.update(wg=dev(lp.wg), bg=dev(lp.bg), mw1=dev(p.mw1), mw2=dev(p.mw2))
     x_host = wl.layer_input(cfg)
@@ -479,10 +486,16 @@ def bench_layer(args, sa, wl, torch, np, cfg):
 
     add("ln1_quant", lambda: sa.sa_layernorm_quant(x, shared["gamma1"], shared["beta1"], lp.eps, lp.ln_inv_scale,
                                                    want_ln=False, q=z8), T * E * 5, 8 * T * E, "alu_fp32")
-    add("qkv_linear", lambda: sa.sa_shift_linear_f32(z8, wqkv, lp.qkv_scale, parts=3, variant=var, ys=(q, k, v), workspace=lin_ws),
-        T * E + 3 * E * E // 2 + 3 * T * E * 4, 2 * T * E * 3 * E, "mfma_i8")
-    add("binarize_qk", lambda: sa.sa_binarize_pair(q4, k4, shared["proj"], cfg.nbits, q_codes=qc, k_codes=kc),
-        2 * (rows * d * 4 + code_b) + d * cfg.nbits * 4, 4 * rows * cfg.nbits * d, "mfma_bf16x3")
+    if args.sign_hash and var != 0:
+        add("qkv_linear_codes", lambda: sa.sa_shift_linear_qkv_codes(z8, wqkv, B, N, H, lp.qkv_scale, variant=var, workspace=lin_ws, q_codes=qc,
+                                                                     k_codes=kc, v=v),
+            T * E + 3 * E * E // 2 + T * E * 4 + 2 * code_b, 2 * T * E * 3 * E, "mfma_i8")
+    else:
+        add("qkv_linear", lambda: sa.sa_shift_linear_f32(z8, wqkv, lp.qkv_scale, parts=3, variant=var, ys=(q, k, v), workspace=lin_ws),
+            T * E + 3 * E * E // 2 + 3 * T * E * 4, 2 * T * E * 3 * E, "mfma_i8")
+        add("binarize_qk", lambda: sa.sa_binarize_pair(q4, k4, shared["proj"], cfg.nbits, q_codes=qc, k_codes=kc),
+            2 * (rows * d * 4 + code_b) + (d * cfg.nbits * 4 if shared["proj"] is not None else 0),
+            4 * rows * cfg.nbits * d if shared["proj"] is not None else 2 * rows * d, "mfma_bf16x3")
     o = torch.empty((B, N, H, d), dtype=torch.float32, device="cuda")
     if cfg.attention == "linear":
         kv = torch.empty((B, H, cfg.nbits, d), dtype=torch.float32, device="cuda")
@@ -565,7 +578,7 @@ def bench_layer(args, sa, wl, torch, np, cfg):
         small = wl.scaled_down(cfg, B=min(bs, cfg.B))
         xs = x_host[: small.T]
         t0 = time.perf_counter()
-        oracle.layer_forward(small, xs, lp, p, wl.proj(cfg), scale)
+        oracle.layer_forward(small, xs, lp, p, None if args.sign_hash else wl.proj(cfg), scale)
         dt = time.perf_counter() - t0
         cpu = {"value": round(small.T / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": "%d of %d batch items (%d tokens), one pass of oracle.layer_forward" % (small.B, cfg.B, small.T)}

@@ -205,6 +205,21 @@ int sa_shift_linear_f32(const int8_t *x, const uint8_t *w4, long M, int K, int N
                         float *y2, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The fused Q/K/V projection of the sign-hash variant (Sec. 4.1 with vanilla
+ * sign quantisation of Q and K, nbits = head width): the shift Linear of
+ * sa_shift_linear_f32 over the stacked [3E, E] weight, but Q and K never leave
+ * as floats: their code bits are the signs of the accumulators,
+ *   bit j of token n, head h = [acc[n, h * d + j] >= 0]     (= [scale * acc >= 0], scale > 0)
+ * packed as sa_binarize would pack them ([B,H,N,d/64]), and only V is written
+ * as fp32 [B*N, E] = fma(float(acc), scale, 0).  x int8 [B*N, E]; d = E / H in
+ * {64, 128}; E % 128 == 0; matrix-core variants only.  Bit-identical to
+ * sa_shift_linear_f32 followed by sa_binarize_pair without a projection.
+ */
+int sa_shift_linear_qkv_codes(const int8_t *x, const uint8_t *wqkv, int B, int N, int H, int E, int variant,
+                              float scale, uint64_t *q_codes, uint64_t *k_codes, float *v, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
  * Top-1 routing (Sec. 4.2: p = softmax(logits), G(x) = p_i * 1{p_i >= p_j}).
  * Expert 0 = Mult, expert 1 = Shift.  The decision compares raw logits; ties
  * go to the lowest index.  2 <= E <= 8.

@@ -23,7 +23,7 @@ EXPORTS = [
     "sa_additive_attention", "sa_linear_attention_01_workspace_bytes", "sa_linear_attention_01", "sa_dwconv3x3",
     "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear", "sa_shift_linear_f32", "sa_layernorm_quant",
-    "sa_shift_weights_from_float",
+    "sa_shift_weights_from_float", "sa_shift_linear_qkv_codes",
     "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_moe_balance_loss_workspace_bytes", "sa_moe_balance_loss", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
@@ -286,6 +286,25 @@ def sa_shift_linear_f32(x, w4, scale, residual=None, parts=1, variant=SA_VARIANT
                                    _ptr(y[0]), _ptr(y[1]), _ptr(y[2]), _ptr(workspace), _z(workspace.numel()),
                                    _stream()))
     return tuple(ys)
+
+
+def sa_shift_linear_qkv_codes(x, wqkv, B, N, H, scale, variant=SA_VARIANT_MFMA, workspace=None, q_codes=None,
+                              k_codes=None, v=None):
+    """Fused Q/K/V projection with the sign hash in its epilogue: returns (q_codes, k_codes, v)."""
+    lib = load_library()
+    M, E = x.shape
+    d = E // H
+    if q_codes is None:
+        q_codes = torch.empty((B, H, N, d // 64), dtype=torch.int64, device=x.device)
+    if k_codes is None:
+        k_codes = torch.empty((B, H, N, d // 64), dtype=torch.int64, device=x.device)
+    if v is None:
+        v = torch.empty((M, E), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = _workspace(lib.sa_shift_linear_workspace_bytes(_l(M), E, 3 * E, variant), x.device)
+    _check(lib.sa_shift_linear_qkv_codes(_ptr(x), _ptr(wqkv), B, N, H, E, variant, _f(scale), _ptr(q_codes),
+                                         _ptr(k_codes), _ptr(v), _ptr(workspace), _z(workspace.numel()), _stream()))
+    return q_codes, k_codes, v
 
 
 def sa_layernorm_quant(x, gamma, beta, eps, inv_scale=1.0, want_ln=True, want_q=False, want_half=False,

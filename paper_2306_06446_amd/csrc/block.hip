@@ -292,11 +292,22 @@ extern "C" int sa_layer_forward(const sa_layer_desc *d, void *stream) {
     rc = sa_layernorm_quant(d->x, T, E, d->gamma1, d->beta1, d->eps, d->ln_inv_scale, nullptr, codes8, nullptr, nullptr,
                             nullptr, 0, nullptr, stream);
     if (rc != SA_OK) return rc;
-    rc = sa_shift_linear_f32(codes8, d->wqkv, T, E, 3 * E, d->shift_variant, d->qkv_scale, nullptr, 3, q, k, v,
-                             ws + L.lin_ws, L.lin_ws_bytes, stream);
-    if (rc != SA_OK) return rc;
-    rc = sa_binarize_pair(q, k, d->B, d->N, d->H, dv, d->proj, d->nbits, qc, kc, stream);
-    if (rc != SA_OK) return rc;
+    // Sign hash (no projection): the code bits are the signs of the Q and K accumulators, taken in the epilogue of
+    // the projection, so Q and K never exist as floats.  Otherwise Q, K, V leave as fp32 and Q, K are hashed.
+    const bool fused_hash = d->proj == nullptr && d->nbits == dv && (dv == 64 || dv == 128) && E % 128 == 0 &&
+                            d->shift_variant != SA_VARIANT_VALU && d->qkv_scale > 0.0f &&
+                            d->qkv_scale - d->qkv_scale == 0.0f;
+    if (fused_hash) {
+        rc = sa_shift_linear_qkv_codes(codes8, d->wqkv, d->B, d->N, d->H, E, d->shift_variant, d->qkv_scale, qc, kc, v,
+                                       ws + L.lin_ws, L.lin_ws_bytes, stream);
+        if (rc != SA_OK) return rc;
+    } else {
+        rc = sa_shift_linear_f32(codes8, d->wqkv, T, E, 3 * E, d->shift_variant, d->qkv_scale, nullptr, 3, q, k, v,
+                                 ws + L.lin_ws, L.lin_ws_bytes, stream);
+        if (rc != SA_OK) return rc;
+        rc = sa_binarize_pair(q, k, d->B, d->N, d->H, dv, d->proj, d->nbits, qc, kc, stream);
+        if (rc != SA_OK) return rc;
+    }
     if (d->attention == 0) {
         rc = sa_additive_attention(qc, kc, v, o, d->B, d->H, d->N, d->N, d->nbits, dv, d->attn_scale,
                                    reinterpret_cast<float *>(ws + L.kv), 3, ws + L.attn_ws, L.attn_ws_bytes, stream);

@@ -14,6 +14,7 @@ enum EpiMode : int {
     kEpiGeluHalf,      // hh[m, n] = half(gelu(acc))                              fp16
     kEpiScatterF32,    // yf[rows[m], n] = gate[rows[m]] * acc
     kEpiLinearF32,     // parts[n / part_width][m, n % part_width] = fma(float(acc), lin_scale, residual[m, n])
+    kEpiQkvCodes,      // column blocks 0 and 1 leave as sign codes (bit = acc >= 0) per head, block 2 as kEpiLinearF32
 };
 
 struct Epilogue {
@@ -32,6 +33,8 @@ struct Epilogue {
     int part_width = 0;
     const float *residual = nullptr;                 // kEpiLinearF32: [rows, N] or null
     float lin_scale = 1.0f;
+    uint64_t *codes[2] = {nullptr, nullptr};         // kEpiQkvCodes: [B, H, tokens, head_dim / 64] each
+    int head_dim = 0, tokens = 0, heads = 0;         // tokens per batch element
 };
 
 __device__ inline int8_t requant_code(float t) {

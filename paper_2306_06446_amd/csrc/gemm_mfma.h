@@ -98,6 +98,9 @@ __device__ inline void load_to_lds_16(const void *src, uint32_t lds_base) {
 //   void *out : [rows, N] elements;  const void *table;  const float *gate : null, or a factor per
 //       destination row that multiplies fp32 outputs (kScatter && kBytes == 4 only);  bool accumulate :
 //       (same case) the product is added to what the destination holds, as fma(gate, value, old)
+//   static constexpr bool kSignCodes  : tiles left of column code_cols leave as packed sign bits instead
+//       (bit = acc >= 0, 64 columns = one word): uint64_t *codes[2] (column block 0 / 1 of width part_width,
+//       laid out [batch, head, token, word]), int head_dim (64 or 128), tokens (per batch element), heads
 //   static constexpr bool kLinear     : fp32 outputs leave as fma(value, scale, residual[m, n]) into
 //       column blocks: float *parts[3], int part_width (a multiple of 4), const float *residual, float scale
 // Wait until at most N of this wavefront's vector-memory loads are still in flight (loads
@@ -312,6 +315,41 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
         });
         prev = buf;
         buf = nxt;
+    }
+
+    // ---- sign codes: a wavefront's 64 columns are one code word of a head; one ballot per accumulator
+    //      register gives 32 sign bits of two rows, and lanes 0..15 write the words of the 32 rows of a tile.
+    if constexpr (Store::kSignCodes) {
+        if (n0 < store.code_cols) {               // uniform per workgroup
+            static_assert(NJ == 2, "a wavefront must own 64 columns");
+            const int col0 = n0 + wn;
+            const int part = col0 / store.part_width;
+            const int cin = col0 - part * store.part_width;
+            const int head = cin / store.head_dim, w = (cin % store.head_dim) / 64, W = store.head_dim / 64;
+            uint64_t *dst = part == 0 ? store.codes[0] : store.codes[1];
+            static_for<MI>([&](auto i_c) {
+                constexpr int i = decltype(i_c)::value;
+                uint64_t mine[2] = {0, 0};
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint64_t lo = __ballot(acc[i][0][r] >= 0), hi = __ballot(acc[i][1][r] >= 0);
+                    const uint64_t w0 = (lo & 0xFFFFFFFFull) | (hi << 32);              // rows of lanes 0..31
+                    const uint64_t w1 = (lo >> 32) | (hi & 0xFFFFFFFF00000000ull);      // rows of lanes 32..63
+                    if (lane == r) { mine[0] = w0; mine[1] = w1; }
+                }
+                if (lane < 16) {
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        const long m = m0 + wm + i * 32 + 8 * (lane >> 2) + 4 * half + (lane & 3);
+                        if (m < n_rows) {
+                            const long b = m / store.tokens, n = m % store.tokens;
+                            dst[((size_t)(b * store.heads + head) * store.tokens + n) * W + w] = mine[half];
+                        }
+                    }
+                }
+            });
+            return;
+        }
     }
 
     // ---- epilogue.  Every output leaves through LDS so that a lane stores 16 contiguous bytes of

@@ -39,6 +39,7 @@ struct MultStore {
     static constexpr int kTableBytes = 0;
     static constexpr bool kScatter = (MODE == kEpiScatterF32);
     static constexpr bool kLinear = false;
+    static constexpr bool kSignCodes = false;
     void *out;                      // compact fp32 rows | fp16 hidden rows | scattered fp32 rows
     const void *table = nullptr;
     const float *gate;

@@ -171,7 +171,8 @@ struct ShiftStore {
     static constexpr int kBytes = (MODE == kEpiRequantLut) ? 1 : 4;
     static constexpr int kTableBytes = (MODE == kEpiRequantLut) ? 256 : 0;
     static constexpr bool kScatter = (MODE == kEpiScatterI32);
-    static constexpr bool kLinear = (MODE == kEpiLinearF32);
+    static constexpr bool kLinear = (MODE == kEpiLinearF32 || MODE == kEpiQkvCodes);
+    static constexpr bool kSignCodes = (MODE == kEpiQkvCodes);
     Epilogue e;
     void *out;             // int32 rows | int8 hidden rows | scattered fp32 rows
     const void *table;     // the 256-entry activation table
@@ -181,21 +182,28 @@ struct ShiftStore {
     int part_width;
     const float *residual;
     float scale;
+    uint64_t *codes[2];    // kEpiQkvCodes: sign codes of column blocks 0 and 1
+    int code_cols, head_dim, tokens, heads;
     explicit ShiftStore(const Epilogue &epi)     // epi.rq is made finite here: convert() relies on it
         : e(with_finite_scale(epi)),
           out(MODE == kEpiInt32 ? (void *)epi.y : MODE == kEpiRequantLut ? (void *)epi.h
-              : MODE == kEpiLinearF32 ? (void *)epi.parts[0] : (void *)epi.yf),
+              : MODE == kEpiLinearF32 ? (void *)epi.parts[0] : MODE == kEpiQkvCodes ? (void *)epi.parts[2] : (void *)epi.yf),
           table(epi.lut),
           gate(MODE == kEpiScatterI32 ? epi.gate : nullptr),
           accumulate(MODE == kEpiScatterI32 && epi.accumulate),
           parts{epi.parts[0], epi.parts[1], epi.parts[2]},
           part_width(epi.part_width > 0 ? epi.part_width : 4),
           residual(epi.residual),
-          scale(epi.lin_scale) {}
+          scale(epi.lin_scale),
+          codes{epi.codes[0], epi.codes[1]},
+          code_cols(MODE == kEpiQkvCodes ? 2 * epi.part_width : 0),
+          head_dim(epi.head_dim > 0 ? epi.head_dim : 64),
+          tokens(epi.tokens > 0 ? epi.tokens : 1),
+          heads(epi.heads) {}
     __device__ inline uint32_t convert(int32_t acc, int n, const uint8_t *lds_table) const {
         if (MODE == kEpiInt32) return (uint32_t)(acc + (e.bias ? e.bias[n] : 0));
         if (MODE == kEpiRequantLut) return lds_table[requant_index(acc, e.rq)];
-        if (MODE == kEpiLinearF32) return __builtin_bit_cast(uint32_t, (float)acc);   // scaled at the store
+        if (MODE == kEpiLinearF32 || MODE == kEpiQkvCodes) return __builtin_bit_cast(uint32_t, (float)acc);   // scaled at the store
         return __builtin_bit_cast(uint32_t, e.out_scale * (float)acc);
     }
 };
@@ -416,6 +424,42 @@ extern "C" int sa_shift_linear_f32(const int8_t *x, const uint8_t *w4, long M, i
     epi.lin_scale = scale;
     sa::RowSel sel{nullptr, nullptr, 0, M};
     return launch_shift<sa::kEpiLinearF32>(variant, x, w4, sel, false, K, N, epi, workspace, sa::as_stream(stream));
+}
+
+extern "C" int sa_shift_linear_qkv_codes(const int8_t *x, const uint8_t *wqkv, int B, int N, int H, int E, int variant,
+                                         float scale, uint64_t *q_codes, uint64_t *k_codes, float *v, void *workspace,
+                                         size_t workspace_bytes, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(B >= 0 && N >= 0 && H > 0 && E > 0, SA_ERR_INVALID, "sa_shift_linear_qkv_codes: bad size");
+    SA_REQUIRE(variant >= 1 && variant <= 3, SA_ERR_UNSUPPORTED,
+               "sa_shift_linear_qkv_codes: matrix-core variants only (1, 2 or 3; got %d)", variant);
+    SA_REQUIRE(E % H == 0 && (E / H == 64 || E / H == 128), SA_ERR_UNSUPPORTED,
+               "sa_shift_linear_qkv_codes: head width E / H must be 64 or 128 (E = %d, H = %d)", E, H);
+    SA_REQUIRE(E % 128 == 0, SA_ERR_UNSUPPORTED, "sa_shift_linear_qkv_codes: E (%d) must be a multiple of 128", E);
+    SA_REQUIRE(scale > 0.0f && scale - scale == 0.0f, SA_ERR_INVALID,
+               "sa_shift_linear_qkv_codes: the scale must be positive and finite (the sign of scale * acc is taken from acc)");
+    const long M = (long)B * N;
+    SA_REQUIRE(M < 65535L * kValuRows, SA_ERR_SHAPE, "sa_shift_linear_qkv_codes: too many rows for one call");
+    if (M == 0) return SA_OK;
+    SA_REQUIRE(x && wqkv && q_codes && k_codes && v, SA_ERR_INVALID, "sa_shift_linear_qkv_codes: NULL buffer");
+    SA_REQUIRE(sa::aligned16(x) && sa::aligned16(wqkv) && sa::aligned16(q_codes) && sa::aligned16(k_codes) &&
+                   sa::aligned16(v) && sa::aligned16(workspace),
+               SA_ERR_ALIGN, "sa_shift_linear_qkv_codes: pointers must be 16-byte aligned");
+    if (variant == SA_VARIANT_AUTO) variant = SA_VARIANT_MFMA;
+    const size_t need = sa_shift_linear_workspace_bytes(M, E, 3 * E, variant);
+    SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
+               "sa_shift_linear_qkv_codes: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    sa::Epilogue epi;
+    epi.parts[0] = epi.parts[1] = epi.parts[2] = v;      // only column block 2 is written as fp32
+    epi.part_width = E;
+    epi.lin_scale = scale;
+    epi.codes[0] = q_codes;
+    epi.codes[1] = k_codes;
+    epi.head_dim = E / H;
+    epi.tokens = N;
+    epi.heads = H;
+    sa::RowSel sel{nullptr, nullptr, 0, M};
+    return launch_shift<sa::kEpiQkvCodes>(variant, x, wqkv, sel, false, E, 3 * E, epi, workspace, sa::as_stream(stream));
 }
 
 extern "C" int sa_quantize_act(const float *x, long n, float inv_scale, int8_t *q, void *stream) {

@@ -193,15 +193,20 @@ def chain_entry_points(sa, cfg, kw):
     return x1_copy, x1
 
 
+import dataclasses
+
 LAYER_CASES = [
-    wl.C1,
-    wl.scaled_down(wl.C4, B=2),
-    wl.scaled_down(wl.C5, B=1, N=1100),
+    (wl.C1, True),
+    (wl.scaled_down(wl.C4, B=2), True),
+    (wl.scaled_down(wl.C5, B=1, N=1100), True),
+    # the sign-hash variant (no projection, nbits = head width): the hash runs in the projection's epilogue
+    (dataclasses.replace(wl.scaled_down(wl.C4, B=2), nbits=64, name="c4-sign-hash"), False),
+    (dataclasses.replace(wl.scaled_down(wl.C5, B=1, N=700), nbits=64, name="c5-sign-hash"), False),
 ]
 
 
-@pytest.mark.parametrize("cfg", LAYER_CASES, ids=lambda c: c.name)
-def test_layer_forward_matches_oracle(sa, cfg):
+@pytest.mark.parametrize("cfg,use_proj", LAYER_CASES, ids=lambda c: getattr(c, "name", ""))
+def test_layer_forward_matches_oracle(sa, cfg, use_proj):
     """End to end against the oracle.  Four int8 quantisers sit in the path (after both LayerNorms, after
     the attention, inside the Shift expert) and one hash; an fp32 input that differs from the oracle's fp64
     value in its last bits lands on the other side of a rounding boundary now and then, and a flipped code of
@@ -212,7 +217,7 @@ def test_layer_forward_matches_oracle(sa, cfg):
     x = wl.layer_input(cfg)
     lp = wl.layer_params(cfg)
     p = wl.mlp_params(cfg)
-    proj = wl.proj(cfg)
+    proj = wl.proj(cfg) if use_proj else None
     scale = wl.attention_scale(cfg)
     r = oracle.layer_forward(cfg, x, lp, p, proj, scale)
     kw = layer_kwargs(sa, cfg, x, lp, p, proj, scale)
@@ -248,3 +253,27 @@ def test_shift_weights_from_float_bit_exact(sa):
     # the packed weights drive the shift layers like any others
     x = wl.int8_activations(3, 70, 384)
     assert np.array_equal(host(sa.sa_shift_linear(dev(x), dev(got))), oracle.shift_linear(x, ref))
+
+
+# --------------------------- fused Q/K/V projection with the sign hash in its epilogue ---
+
+@pytest.mark.parametrize("variant", [1, 3])
+@pytest.mark.parametrize("B,N,H,E", [(2, 197, 12, 768), (3, 50, 2, 256), (1, 300, 3, 384), (1, 1, 2, 128)])
+def test_qkv_projection_with_sign_codes_bit_exact(sa, variant, B, N, H, E):
+    M, d = B * N, E // H
+    x = wl.int8_activations(3, M, E, extra=H)
+    x[0, :] = 0                                                  # accumulators of 0: bit 1
+    w4 = wl.shift_weights(3, 5, 3 * E, E)
+    scale = float(np.float32(2.5e-5))
+    acc = oracle.shift_linear(x, w4)
+    qkv = oracle.dequant_residual(acc, scale)
+    q_ref = oracle.binarize(qkv[:, :E].reshape(B, N, H, d), None, d)
+    k_ref = oracle.binarize(qkv[:, E:2 * E].reshape(B, N, H, d), None, d)
+    d_w = dev(w4)
+    if variant == 3:
+        d_w = sa.sa_shift_planes_prepare(d_w)
+    qc, kc, v = sa.sa_shift_linear_qkv_codes(dev(x), d_w, B, N, H, scale, variant=variant)
+    assert np.array_equal(host(qc).view(np.uint64), q_ref)
+    assert np.array_equal(host(kc).view(np.uint64), k_ref)
+    assert np.array_equal(host(v), qkv[:, 2 * E:])
+    assert np.all(host(qc).view(np.uint64)[0, :, 0] == np.uint64(2**64 - 1))
