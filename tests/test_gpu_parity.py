@@ -571,3 +571,40 @@ def test_moe_balance_loss_on_the_config_router(sa):
     assert_close(host(sums), ref_sums, 2e-5, 1e-6, "sums")
     assert_close(host(losses), ref_losses, 2e-4, 1e-7, "losses")
     assert ref_losses[1] < 1e-3
+
+
+def test_block_forward_replays_from_a_captured_graph(sa):
+    """The block enqueues kernels and events only (its side stream is forked from and joined into the
+    caller's stream, buffers are cleared by kernels), so a caller may capture it.  Every replay, with eager
+    work and synchronisations in between, must reproduce the eager result bit for bit."""
+    cfg = wl.scaled_down(wl.C4, B=3)
+    q, k, v, pr, scale, p, logits = _block_inputs(cfg)
+    kw = dict(B=cfg.B, N=cfg.N, H=cfg.H, d=cfg.d, nbits=cfg.nbits, dv=cfg.dv, attention=1, hid=cfg.hid, moe=True,
+              attn_scale=scale, q=dev(q), k=dev(k), v=dev(v), proj=dev(pr), act_inv_scale=p.act_inv_scale,
+              requant_scale=p.requant_scale, out_scale=p.out_scale, w1=dev(p.w1), w2=dev(p.w2), lut=dev(p.lut),
+              logits=dev(logits), mw1=dev(p.mw1), mw2=dev(p.mw2))
+    blk = sa.binding.Block(**kw)
+    o, y = blk.forward()
+    torch.cuda.synchronize()
+    o_ref, y_ref = o.clone(), y.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        blk.forward()
+        torch.cuda.synchronize()
+        graph.capture_begin()
+        blk.forward()
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        o.zero_()
+        y.zero_()
+        if rep % 2:
+            blk.forward()                          # eager work between replays
+            o.zero_()
+            y.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_ref) and torch.equal(y, y_ref), "replay %d" % rep
