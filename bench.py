@@ -507,8 +507,9 @@ def bench_layer(args, sa, wl, torch, np, cfg):
             code_b + v_b + kv_b, 2 * rows * cfg.nbits * d, "mfma_bf16x3")
         add("quantize", lambda: sa.sa_quantize_act(o.view(T, E), p.act_inv_scale, q=z8), T * E * 5, 2 * T * E, "alu_fp32")
     else:
-        add("hamming", lambda: sa.sa_hamming_attention_fused(qc, kc, v4, scale, cfg.nbits, p.act_inv_scale, out=o, xq=z8, want_xh=False),
-            2 * code_b + 2 * v_b + T * E, 2 * B * H * N * N * d, "mfma_bf16x3")
+        add("hamming", lambda: sa.sa_hamming_attention_fused(qc, kc, v4, scale, cfg.nbits, p.act_inv_scale, xq=z8, want_xh=False,
+                                                             want_out=False),
+            2 * code_b + v_b + T * E, 2 * B * H * N * N * d, "mfma_bf16x3")
     add("o_linear", lambda: sa.sa_shift_linear_f32(z8, wo, lp.o_scale, residual=x, variant=var, ys=(x1,), workspace=lin_ws),
         T * E + E * E // 2 + 2 * T * E * 4, 2 * T * E * E, "mfma_i8")
     xh = torch.empty((T, E), dtype=torch.float16, device="cuda") if moe else None

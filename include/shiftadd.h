@@ -142,7 +142,8 @@ int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const
 /* The same, with the attention output also written in the two forms the MLP of the block
  * reads (Eq. 2 feeds the attention output to the MLP): xq_or_null int8 [B*Nq, H*dv], the
  * codes sa_quantize_act(out, act_inv_scale) would give, and xh_or_null fp16 [B*Nq, H*dv],
- * out rounded to nearest.  Either may be NULL.
+ * out rounded to nearest.  Either may be NULL, and so may `out` when one of them is given
+ * (a consumer that reads only the quantised form saves the fp32 write).
  * variant: SA_VARIANT_VALU computes the scores by XOR + popcount on the vector ALU;
  * SA_VARIANT_MFMA as the dot product of the +-1 sign vectors on the matrix cores (the same
  * integers, nbits <= 256); SA_VARIANT_AUTO (what sa_hamming_attention uses) takes the

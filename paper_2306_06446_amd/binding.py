@@ -216,13 +216,13 @@ def sa_hamming_attention(q_codes, k_codes, v, scale, nbits, want_scores=False, o
 
 
 def sa_hamming_attention_fused(q_codes, k_codes, v, scale, nbits, act_inv_scale, out=None, xq=None, xh=None,
-                               want_xq=True, want_xh=True, variant=SA_VARIANT_AUTO):
+                               want_xq=True, want_xh=True, variant=SA_VARIANT_AUTO, want_out=True):
     """Hamming attention that also leaves its output as int8 codes (xq) and in fp16 (xh), both [B*Nq, H*dv]."""
     B, H, Nq, W = q_codes.shape
     Nk = k_codes.shape[2]
     dv = v.shape[3]
     dev = v.device
-    if out is None:
+    if out is None and want_out:
         out = torch.empty((B, Nq, H, dv), dtype=torch.float32, device=dev)
     if xq is None and want_xq:
         xq = torch.empty((B * Nq, H * dv), dtype=torch.int8, device=dev)

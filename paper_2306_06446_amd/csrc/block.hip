@@ -313,7 +313,8 @@ extern "C" int sa_layer_forward(const sa_layer_desc *d, void *stream) {
                                    reinterpret_cast<float *>(ws + L.kv), 3, ws + L.attn_ws, L.attn_ws_bytes, stream);
         if (rc == SA_OK) rc = sa_quantize_act(o, T * E, d->act_inv_scale, codes8, stream);
     } else {
-        rc = sa_hamming_attention_fused(qc, kc, v, o, d->B, d->H, d->N, d->N, d->nbits, dv, d->attn_scale, nullptr,
+        // only the int8 form of the attention output is read (by the output projection): no fp32 write
+        rc = sa_hamming_attention_fused(qc, kc, v, nullptr, d->B, d->H, d->N, d->N, d->nbits, dv, d->attn_scale, nullptr,
                                          codes8, nullptr, d->act_inv_scale, SA_VARIANT_AUTO, stream);
     }
     if (rc != SA_OK) return rc;

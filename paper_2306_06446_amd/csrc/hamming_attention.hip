@@ -139,7 +139,7 @@ __device__ inline void write_outputs(v16f (&acc)[DV / 32], float den, float *den
                 float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
                 transpose_in_quad(x, q4);
                 const float4 val = make_float4(x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv);
-                if (qo < Nq) *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
+                if (out && qo < Nq) *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
                 // what the MLP reads: the int8 codes of the activation quantiser, and the fp16 rounding
                 const int col = jt * 32 + (i_loc & ~3);
                 if (xq) {
@@ -621,7 +621,8 @@ extern "C" int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_
     SA_REQUIRE((long)B * H < (1L << 20), SA_ERR_SHAPE, "sa_hamming_attention: B*H too large");
     if ((long)B * H == 0 || Nq == 0) return SA_OK;
     SA_REQUIRE(Nk > 0, SA_ERR_SHAPE, "sa_hamming_attention: softmax over zero keys is undefined");
-    SA_REQUIRE(q_codes && k_codes && v && out, SA_ERR_INVALID, "sa_hamming_attention: NULL buffer");
+    SA_REQUIRE(q_codes && k_codes && v, SA_ERR_INVALID, "sa_hamming_attention: NULL buffer");
+    SA_REQUIRE(out || xq_or_null || xh_or_null, SA_ERR_INVALID, "sa_hamming_attention: no output requested");
     SA_REQUIRE(sa::aligned16(q_codes) && sa::aligned16(k_codes) && sa::aligned16(v) && sa::aligned16(out) &&
                    sa::aligned16(scores_or_null) && sa::aligned16(xq_or_null) && sa::aligned16(xh_or_null),
                SA_ERR_ALIGN, "sa_hamming_attention: pointers must be 16-byte aligned");

@@ -172,7 +172,7 @@ def chain_entry_points(sa, cfg, kw):
         oq = sa.sa_quantize_act(o.view(T, E), kw["act_inv_scale"])
     else:
         _, oq, _ = sa.sa_hamming_attention_fused(qc, kc, v4, kw["attn_scale"], cfg.nbits, kw["act_inv_scale"],
-                                                 want_xh=False)
+                                                 want_xh=False, want_out=False)
         oq = oq.view(T, E)
     (x1,) = sa.sa_shift_linear_f32(oq, kw["wo"], kw["o_scale"], residual=kw["x"], variant=var)
     x1_copy = x1.clone()

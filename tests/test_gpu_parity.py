@@ -282,6 +282,10 @@ def test_fused_attention_outputs_are_the_quantiser_and_the_half_rounding_of_out(
     # same kernel arithmetic on the same fp32 values: the library's own quantiser must agree exactly
     assert torch.equal(xq, sa.sa_quantize_act(out.view(cfg.T, cfg.E), p.act_inv_scale))
     assert torch.equal(xh, out.view(cfg.T, cfg.E).to(torch.float16))
+    # the fp32 output is optional when a narrower form is requested
+    none, xq2, _ = sa.sa_hamming_attention_fused(qc, kc, dev(v), scale, cfg.nbits, p.act_inv_scale, want_out=False,
+                                                 want_xh=False)
+    assert none is None and torch.equal(xq2, xq)
     # and against the oracle end to end: codes differ by at most one step, and rarely
     o_ref = oracle.hamming_attention(oracle.binarize(q, pr, cfg.nbits), oracle.binarize(k, pr, cfg.nbits), v,
                                      cfg.nbits, scale)
