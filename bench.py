@@ -685,11 +685,11 @@ def cpu_baseline(cfg, sample_batch):
     p = wl.mlp_params(small) if small.E else None
     logits = wl.router_logits(small) if (small.E and small.shift_frac is not None) else None
     oracle.build()
-    t0 = time.perf_counter()
+    t0, c0 = time.perf_counter(), time.process_time()
     oracle.block_forward(small, q, k, v, pr, scale, logits, p)
-    dt = time.perf_counter() - t0
+    dt, cpu_s = time.perf_counter() - t0, time.process_time() - c0
     return {"value": round(small.T / dt, 2), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%s with B=%d, N=%d (%d tokens), one pass, %.2f s" % (cfg.name, sb, n, small.T, dt)}
+            "sample": "%s with B=%d, N=%d (%d tokens), one pass, %.2f s wall, %.1f s of CPU time" % (cfg.name, sb, n, small.T, dt, cpu_s)}
 
 
 if __name__ == "__main__":
