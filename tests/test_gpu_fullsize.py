@@ -9,7 +9,6 @@ import dataclasses
 
 import numpy as np
 import pytest
-import torch
 
 import oracle
 from helpers import ATTN_ATOL, ATTN_RTOL, assert_close, dev, host

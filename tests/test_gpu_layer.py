@@ -1,6 +1,8 @@
 """GPU parity of the rest of the block of Eq. 2: LayerNorm with its fused outputs, shift Linears
 with fp32 outputs (Q/K/V in column blocks, output projection with residual), the accumulating
 expert epilogues, and the composed layer.  Every stage runs on inputs the CPU oracle produced."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -192,8 +194,6 @@ def chain_entry_points(sa, cfg, kw):
                         stages=3 | acc)
     return x1_copy, x1
 
-
-import dataclasses
 
 LAYER_CASES = [
     (wl.C1, True),
