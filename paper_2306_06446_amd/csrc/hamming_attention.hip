@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
 // keys as long as the V operand uses the same one: here element e of step t is key
 // 16 t + 8 (e / 4) + 4 (lane / 32) + e % 4 of the tile).
 template <int DV, int W, bool ROWREF>
-__global__ __launch_bounds__(kMaxWaves *kWave, (DV <= 64 && W <= 2) ? 4 : 2) void hamming_mm_kernel(
+__global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mm_kernel(
     const uint64_t *__restrict__ q_codes, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
     float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2, int8_t *__restrict__ xq,
     _Float16 *__restrict__ xh, float act_inv_scale) {
