@@ -36,8 +36,8 @@ PEAK_TFLOPS = {                  # dense peaks of MI355X
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="c3 times the two shift linear layers alone, in both variants")
     ap.add_argument("--rotate", type=int, default=0,
@@ -195,6 +195,22 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / n_steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
 
+    # ---- the same steps once more with a HIP event after each (median / min of single steps), cold (rotating
+    #      buffer sets, larger than the last-level cache together) and hot (one set, cache-resident inputs)
+    def step_times(pick):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)]
+        evs[0].record()
+        for i in range(n_steps):
+            blocks[pick(i)][0].forward()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        us = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_steps))
+        return {"median": round(us[len(us) // 2], 2), "min": round(us[0], 2)}
+
+    step_us = None
+    if not args.kernels_only:
+        step_us = {"cold": step_times(lambda i: i % n_sets), "hot": step_times(lambda i: 0)}
+
     # ---- per-kernel durations, HIP events on the launch stream, same buffers, same rotation
     counts = None
     if moe:
@@ -266,6 +282,7 @@ def main():
                    "mlp": ("moe %.0f%% shift / %.0f%% fp16 mult" % (100 * cfg.shift_frac, 100 - 100 * cfg.shift_frac))
                    if moe else ("shift" if cfg.E else "none"),
                    "input_sets_rotated": n_sets, "shift_variant": args.shift_variant},
+        "step_us": step_us,
         "block_hbm_roofline_frac": round(block_hbm_frac, 4),
         "block_algorithmic_bytes": block_bytes,
         "block_us_sum_of_kernels_modularized": modularized_us,
