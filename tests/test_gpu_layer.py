@@ -277,3 +277,27 @@ def test_qkv_projection_with_sign_codes_bit_exact(sa, variant, B, N, H, E):
     assert np.array_equal(host(kc).view(np.uint64), k_ref)
     assert np.array_equal(host(v), qkv[:, 2 * E:])
     assert np.all(host(qc).view(np.uint64)[0, :, 0] == np.uint64(2**64 - 1))
+
+
+# ------------------------------------------------------------------ degenerate sizes ---
+
+def test_empty_and_degenerate_inputs_of_the_newer_entry_points(sa):
+    z = torch.zeros
+    # no tokens: nothing is launched, nothing is written
+    ln, q, _, _ = sa.sa_layernorm_quant(z((0, 64), device="cuda"), z(64, device="cuda"), z(64, device="cuda"), 1e-6,
+                                        want_q=True)
+    assert ln.shape == (0, 64) and q.shape == (0, 64)
+    (y,) = sa.sa_shift_linear_f32(z((0, 64), dtype=torch.int8, device="cuda"), dev(wl.shift_weights(3, 4, 8, 64)), 1.0)
+    assert y.shape == (0, 8)
+    # no keys: K^T V, the counts and the normaliser are zero, and so is the output (0 / eps)
+    qc = dev(wl.random_codes(7, (1, 2, 9), 64))
+    kc = torch.zeros((1, 2, 0, 1), dtype=torch.int64, device="cuda")
+    v = z((1, 0, 2, 32), device="cuda")
+    out, kv, ksum = sa.sa_linear_attention_01(qc, kc, v, 1.0, 64)
+    assert float(kv.abs().max()) == 0.0 and int(ksum.abs().max()) == 0 and float(out.abs().max()) == 0.0
+    # a single token and a 1 x 1 grid
+    x = wl.float_activations(5, 1, 64)
+    w = np.random.default_rng(91).standard_normal((64, 3, 3)).astype(np.float32)
+    got = host(sa.sa_dwconv3x3(dev(x.reshape(1, 1, 1, 64)), dev(w)))
+    assert_close(got, oracle.dwconv3x3(x.reshape(1, 1, 1, 64), w), 1e-6, 1e-6, "1 x 1 grid")
+    assert np.allclose(got.ravel(), x.ravel() * w[:, 1, 1])
