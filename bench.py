@@ -40,6 +40,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="c3 times the two shift linear layers alone, in both variants")
+    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
+                    help="HIP streams the K steps are enqueued on in turn (each step is one whole pass on one stream, on "
+                         "input sets of that stream's own): with 2, the attention kernels of one step overlap the expert "
+                         "GEMMs of the previous one, as two concurrent requests would; 1 = strictly one step after another; "
+                         "0 = 2, except for config 1, whose 197 tokens are launch-bound and gain nothing from it")
     ap.add_argument("--rotate", type=int, default=0,
                     help="input/workspace sets cycled through (0 = enough to exceed the 256 MiB last-level cache)")
     ap.add_argument("--shift-variant", type=int, default=3, choices=[0, 1, 2, 3],
@@ -135,6 +140,8 @@ def main():
     if args.config == "c3":
         return bench_shift_linear(args, sa, wl, torch, np)
     cfg = {"c1": wl.C1, "c2": wl.C2, "c4": wl.C4, "c5": wl.C5}[args.config]
+    if args.streams == 0:
+        args.streams = 1 if args.config == "c1" else 2
     if args.layer:
         return bench_layer(args, sa, wl, torch, np, cfg)
     if args.zero_one:
@@ -162,6 +169,7 @@ def main():
             shared.update(mw1=dev(p.mw1), mw2=dev(p.mw2))
     per_set_bytes = (q.nbytes + k.nbytes + v.nbytes) + 2 * cfg.T * max(cfg.E, cfg.H * cfg.dv) * 4
     n_sets = args.rotate or max(1, min(8, math.ceil(600e6 / per_set_bytes)))
+    n_sets = (n_sets + args.streams - 1) // args.streams * args.streams      # every set stays on one stream
     blocks = []
     for _ in range(n_sets):
         kw = dict(B=cfg.B, N=cfg.N, H=cfg.H, d=cfg.d, nbits=cfg.nbits, dv=cfg.dv,
@@ -184,12 +192,11 @@ def main():
 
     # ---- the timed region: W warm-up steps, then exactly K steps
     n_warm, n_steps = (0, 1) if args.kernels_only else (args.warmup, args.steps)
-    for i in range(n_warm):
-        blocks[i % n_sets][0].forward()
+    run_steps = make_step_runner(torch, args.streams, n_sets, lambda i: blocks[i][0].forward())
+    run_steps(n_warm)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(n_steps):
-        blocks[i % n_sets][0].forward()
+    run_steps(n_steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / n_steps
@@ -281,7 +288,7 @@ def main():
                    "E": cfg.E, "hid": cfg.hid, "attention": cfg.attention,
                    "mlp": ("moe %.0f%% shift / %.0f%% fp16 mult" % (100 * cfg.shift_frac, 100 - 100 * cfg.shift_frac))
                    if moe else ("shift" if cfg.E else "none"),
-                   "input_sets_rotated": n_sets, "shift_variant": args.shift_variant},
+                   "input_sets_rotated": n_sets, "shift_variant": args.shift_variant, "streams": args.streams},
         "step_us": step_us,
         "block_hbm_roofline_frac": round(block_hbm_frac, 4),
         "block_algorithmic_bytes": block_bytes,
@@ -289,6 +296,25 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "kernels": report,
     }
     print(json.dumps(out))
+
+
+def make_step_runner(torch, n_streams, n_sets, forward_set):
+    """run(k): enqueue k steps, step i on stream i % n_streams and on input set i % n_sets (n_sets is a multiple of
+    n_streams, so a set is only ever used on one stream and its steps stay ordered).  The caller synchronises."""
+    if n_streams == 1:
+        def run(k):
+            for i in range(k):
+                forward_set(i % n_sets)
+        return run
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+
+    def run(k):
+        for s in streams:
+            s.wait_stream(torch.cuda.current_stream())
+        for i in range(k):
+            with torch.cuda.stream(streams[i % n_streams]):
+                forward_set(i % n_sets)
+    return run
 
 
 def bench_shift_linear(args, sa, wl, torch, np):
@@ -472,13 +498,13 @@ def bench_layer(args, sa, wl, torch, np, cfg):
         shared.update(wg=dev(lp.wg), bg=dev(lp.bg), mw1=dev(p.mw1), mw2=dev(p.mw2))
     x_host = wl.layer_input(cfg)
     n_sets = args.rotate or max(2, min(8, math.ceil(600e6 / (10 * x_host.nbytes))))
+    n_sets = (n_sets + args.streams - 1) // args.streams * args.streams
     layers = [sa.Layer(x=dev(x_host), **shared) for _ in range(n_sets)]
-    for i in range(args.warmup):
-        layers[i % n_sets].forward()
+    run_steps = make_step_runner(torch, args.streams, n_sets, lambda i: layers[i].forward())
+    run_steps(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        layers[i % n_sets].forward()
+    run_steps(args.steps)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -607,7 +633,7 @@ def bench_layer(args, sa, wl, torch, np, cfg):
            "vs_baseline": None, "dtype": "f32+u64 codes+i8/i32 shift+f16 mult", "data": "synthetic",
            "config": {"workload": cfg.name.replace("block", "layer"), "B": cfg.B, "N": cfg.N, "H": H, "nbits": cfg.nbits, "E": E,
                       "hid": hid, "attention": cfg.attention, "mlp": "moe" if moe else "shift", "input_sets_rotated": n_sets,
-                      "shift_variant": var},
+                      "shift_variant": var, "streams": args.streams},
            "layer_hbm_roofline_frac": round(layer_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
            "layer_algorithmic_bytes": layer_bytes, "roofline": roofline, "cpu_baseline": cpu, "kernels": report}
     print(json.dumps(out))

@@ -612,3 +612,35 @@ def test_block_forward_replays_from_a_captured_graph(sa):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(o, o_ref) and torch.equal(y, y_ref), "replay %d" % rep
+
+
+def test_block_forward_on_two_streams_in_turn_is_bit_identical(sa):
+    """Successive blocks enqueued on two streams in turn (what bench.py does by default) overlap on the GPU and
+    share the library's side stream and events; every block must still produce what it produces alone."""
+    cfg = wl.scaled_down(wl.C4, B=8)
+    q, k, v, pr, scale, p, logits = _block_inputs(cfg)
+    g = np.random.default_rng(77)
+    blocks, refs = [], []
+    for i in range(4):
+        qi = (q + np.float32(0.01 * i) * g.standard_normal(q.shape, dtype=np.float32)).astype(np.float32)
+        kw = dict(B=cfg.B, N=cfg.N, H=cfg.H, d=cfg.d, nbits=cfg.nbits, dv=cfg.dv, attention=1, hid=cfg.hid, moe=True,
+                  attn_scale=scale, q=dev(qi), k=dev(k), v=dev(v), proj=dev(pr), act_inv_scale=p.act_inv_scale,
+                  requant_scale=p.requant_scale, out_scale=p.out_scale, w1=dev(p.w1), w2=dev(p.w2), lut=dev(p.lut),
+                  logits=dev(logits), mw1=dev(p.mw1), mw2=dev(p.mw2))
+        blk = sa.binding.Block(**kw)
+        o, y = blk.forward()
+        torch.cuda.synchronize()
+        blocks.append(blk)
+        refs.append((o.clone(), y.clone()))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        for blk in blocks:
+            blk.o.zero_()
+            blk.y.zero_()
+        torch.cuda.synchronize()
+        for i in range(16):
+            with torch.cuda.stream(streams[i % 2]):
+                blocks[i % 4].forward()
+        torch.cuda.synchronize()
+        for blk, (o_ref, y_ref) in zip(blocks, refs):
+            assert torch.equal(blk.o, o_ref) and torch.equal(blk.y, y_ref), "rep %d" % rep
