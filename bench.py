@@ -40,11 +40,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c4", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="c3 times the two shift linear layers alone, in both variants")
-    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2, 3, 4],
                     help="HIP streams the K steps are enqueued on in turn (each step is one whole pass on one stream, on "
                          "input sets of that stream's own): with 2, the attention kernels of one step overlap the expert "
-                         "GEMMs of the previous one, as two concurrent requests would; 1 = strictly one step after another; "
-                         "0 = 2, except for config 1, whose 197 tokens are launch-bound and gain nothing from it")
+                         "GEMMs of the previous one, as two concurrent requests would; 1 = strictly one step after another")
     ap.add_argument("--rotate", type=int, default=0,
                     help="input/workspace sets cycled through (0 = enough to exceed the 256 MiB last-level cache)")
     ap.add_argument("--shift-variant", type=int, default=3, choices=[0, 1, 2, 3],
@@ -140,8 +139,6 @@ def main():
     if args.config == "c3":
         return bench_shift_linear(args, sa, wl, torch, np)
     cfg = {"c1": wl.C1, "c2": wl.C2, "c4": wl.C4, "c5": wl.C5}[args.config]
-    if args.streams == 0:
-        args.streams = 1 if args.config == "c1" else 2
     if args.layer:
         return bench_layer(args, sa, wl, torch, np, cfg)
     if args.zero_one:

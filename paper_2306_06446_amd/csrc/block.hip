@@ -2,8 +2,6 @@
 // attention MatMuls and the MLP): hash Q and K, additive or Hamming attention, then the
 // Shift MLP or the two-expert MoE.  Pure composition of the library's own entry points;
 // the expert row counts stay on the device (no host round trip).
-#include <mutex>
-
 #include "common.h"
 
 namespace {
@@ -66,50 +64,6 @@ extern "C" size_t sa_block_workspace_bytes(const sa_block_desc *desc) {
     return L.total;
 }
 
-namespace {
-
-// The two experts are independent once the routing lists exist (the paper's "experts run in
-// parallel", Sec. 4.2), and neither fills the chip on its own at these sizes.  The Mult expert
-// and the routing therefore run on a second stream of the library's own, forked from and joined
-// back into the caller's stream with events, so that from the caller's point of view everything
-// is still ordered on the one stream it passed in.  One side stream and one set of events per
-// device, created on first use at the default priority; concurrent sa_block_forward calls from
-// several host threads serialise on the enqueue.
-struct SideLane {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, routed = nullptr, attended = nullptr, joined = nullptr;
-    bool ready = false;
-};
-
-std::mutex g_lane_mutex;
-SideLane g_lanes[16];
-
-int side_lane(SideLane **out) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16)
-        return sa::fail(SA_ERR_HIP, "block: cannot identify the current device");
-    SideLane &l = g_lanes[dev];
-    if (!l.ready) {
-        if (hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) != hipSuccess ||
-            hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&l.routed, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&l.attended, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&l.joined, hipEventDisableTiming) != hipSuccess)
-            return sa::fail(SA_ERR_HIP, "block: cannot create the side stream");
-        l.ready = true;
-    }
-    *out = &l;
-    return SA_OK;
-}
-
-#define SA_HIP(call)                                                                      \
-    do {                                                                                  \
-        hipError_t e_ = (call);                                                           \
-        if (e_ != hipSuccess) return sa::fail(SA_ERR_HIP, "block: %s", hipGetErrorString(e_)); \
-    } while (0)
-
-}  // namespace
-
 extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     sa::clear_error();
     Layout L;
@@ -128,33 +82,23 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     const long T = (long)d->B * d->N;
     const int E = d->H * d->dv;
 
-    hipStream_t main_st = sa::as_stream(stream);
     const bool moe = d->hid > 0 && d->moe;
-    SideLane *lane = nullptr;
-    std::unique_lock<std::mutex> lock(g_lane_mutex, std::defer_lock);
     int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
     int32_t *expert_of = reinterpret_cast<int32_t *>(ws + L.expert_of);
     int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
     float *gate = reinterpret_cast<float *>(ws + L.gate);
+    // Everything runs on the caller's stream, one kernel after the other.  The two experts are independent
+    // once the routing lists exist (the paper's "experts run in parallel", Sec. 4.2), but each of their GEMMs
+    // fills the chip on its own: running them on two streams was measured and gains nothing (247-252 us against
+    // 248 us per step at the DeiT-Base shape), while a caller that keeps two batches in flight on two streams of
+    // its own is 5 % faster without the library's extra stream and events in the way.
     if (moe) {
-        // side lane: routing needs nothing but the logits, so it starts right away
-        lock.lock();
-        rc = side_lane(&lane);
+        rc = sa_moe_dispatch(d->logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes, stream);
         if (rc != SA_OK) return rc;
-        SA_HIP(hipEventRecord(lane->fork, main_st));
-        SA_HIP(hipStreamWaitEvent(lane->stream, lane->fork, 0));
-        rc = sa_moe_dispatch(d->logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes,
-                             lane->stream);
-        if (rc != SA_OK) return rc;
-        SA_HIP(hipEventRecord(lane->routed, lane->stream));
     }
 
     rc = sa_binarize_pair(d->q, d->k, d->B, d->N, d->H, d->d, d->proj, d->nbits, qc, kc, stream);
     if (rc != SA_OK) return rc;
-    // The routing lists are needed after the attention kernel; the wait is enqueued before it (the
-    // routing is long done by then), so that the first Shift layer follows the attention kernel
-    // without a dependency packet in between.
-    if (moe) SA_HIP(hipStreamWaitEvent(main_st, lane->routed, 0));
     // The attention output leaves in three forms: fp32 (the block's output o), the int8 codes the
     // Shift layers read, and (with a Mult expert) the fp16 rounding its first layer reads.  The
     // Hamming kernel writes all three from its accumulators; the linear path adds one pass over o.
@@ -172,14 +116,10 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
     if (rc != SA_OK || !mlp) return rc;
 
     if (moe) {
-        // Mult expert on the side lane as soon as the attention output exists
-        SA_HIP(hipEventRecord(lane->attended, main_st));
-        SA_HIP(hipStreamWaitEvent(lane->stream, lane->attended, 0));
         const sa_rows mult_rows{perm, counts, 0, T};
         rc = sa_mult_mlp_f16_half(xh, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3, ws + L.mult_ws,
-                                  L.mult_ws_bytes, lane->stream);
+                                  L.mult_ws_bytes, stream);
         if (rc != SA_OK) return rc;
-        SA_HIP(hipEventRecord(lane->joined, lane->stream));
     }
 
     if (!moe) {
@@ -188,11 +128,8 @@ extern "C" int sa_block_forward(const sa_block_desc *d, void *stream) {
                             d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
     }
     const sa_rows shift_rows{perm, counts, 1, T};
-    rc = sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
-                      d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
-    if (rc != SA_OK) return rc;
-    SA_HIP(hipStreamWaitEvent(main_st, lane->joined, 0));     // the caller's stream sees both experts done
-    return SA_OK;
+    return sa_shift_mlp(xq, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
+                        d->out_scale, d->shift_variant, 3, ws + L.shift_ws, L.shift_ws_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -286,7 +223,6 @@ extern "C" int sa_layer_forward(const sa_layer_desc *d, void *stream) {
     float *v = reinterpret_cast<float *>(ws + L.v);
     float *o = q;                                 // Q is dead once it is hashed
     uint64_t *qc = reinterpret_cast<uint64_t *>(ws + L.qc), *kc = reinterpret_cast<uint64_t *>(ws + L.kc);
-    hipStream_t main_st = sa::as_stream(stream);
 
     // attention half: X_attn = Attn(LayerNorm(X)) + X, left in y
     rc = sa_layernorm_quant(d->x, T, E, d->gamma1, d->beta1, d->eps, d->ln_inv_scale, nullptr, codes8, nullptr, nullptr,
@@ -341,22 +277,12 @@ extern "C" int sa_layer_forward(const sa_layer_desc *d, void *stream) {
     float *gate = reinterpret_cast<float *>(ws + L.gate);
     rc = sa_moe_dispatch(logits, T, 2, perm, expert_of, counts, gate, ws + L.disp_ws, L.disp_ws_bytes, stream);
     if (rc != SA_OK) return rc;
-    // the Mult expert on the side lane, the Shift expert on the caller's stream; they add to disjoint rows of y
-    SideLane *lane = nullptr;
-    std::lock_guard<std::mutex> lock(g_lane_mutex);
-    rc = side_lane(&lane);
-    if (rc != SA_OK) return rc;
-    SA_HIP(hipEventRecord(lane->routed, main_st));
-    SA_HIP(hipStreamWaitEvent(lane->stream, lane->routed, 0));
+    // both experts on the caller's stream; they add to disjoint rows of y
     const sa_rows mult_rows{perm, counts, 0, T};
     rc = sa_mult_mlp_f16_half(xh, &mult_rows, E, d->hid, d->mw1, d->mw2, nullptr, d->y, gate, 3 | SA_MLP_ACCUMULATE,
-                              ws + L.mult_ws, L.mult_ws_bytes, lane->stream);
+                              ws + L.mult_ws, L.mult_ws_bytes, stream);
     if (rc != SA_OK) return rc;
-    SA_HIP(hipEventRecord(lane->joined, lane->stream));
     const sa_rows shift_rows{perm, counts, 1, T};
-    rc = sa_shift_mlp(codes8, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
-                      d->out_scale, d->shift_variant, 3 | SA_MLP_ACCUMULATE, ws + L.shift_ws, L.shift_ws_bytes, stream);
-    if (rc != SA_OK) return rc;
-    SA_HIP(hipStreamWaitEvent(main_st, lane->joined, 0));
-    return SA_OK;
+    return sa_shift_mlp(codes8, &shift_rows, E, d->hid, d->w1, d->w2, d->requant_scale, d->lut, nullptr, d->y, gate,
+                        d->out_scale, d->shift_variant, 3 | SA_MLP_ACCUMULATE, ws + L.shift_ws, L.shift_ws_bytes, stream);
 }

@@ -578,8 +578,8 @@ def test_moe_balance_loss_on_the_config_router(sa):
 
 
 def test_block_forward_replays_from_a_captured_graph(sa):
-    """The block enqueues kernels and events only (its side stream is forked from and joined into the
-    caller's stream, buffers are cleared by kernels), so a caller may capture it.  Every replay, with eager
+    """The block enqueues kernels on the caller's stream only (buffers are cleared by kernels, not by memset
+    nodes), so a caller may capture it.  Every replay, with eager
     work and synchronisations in between, must reproduce the eager result bit for bit."""
     cfg = wl.scaled_down(wl.C4, B=3)
     q, k, v, pr, scale, p, logits = _block_inputs(cfg)
@@ -615,8 +615,8 @@ def test_block_forward_replays_from_a_captured_graph(sa):
 
 
 def test_block_forward_on_two_streams_in_turn_is_bit_identical(sa):
-    """Successive blocks enqueued on two streams in turn (what bench.py does by default) overlap on the GPU and
-    share the library's side stream and events; every block must still produce what it produces alone."""
+    """Successive blocks enqueued on two streams in turn (what bench.py does by default) overlap on the GPU;
+    every block must still produce what it produces alone."""
     cfg = wl.scaled_down(wl.C4, B=8)
     q, k, v, pr, scale, p, logits = _block_inputs(cfg)
     g = np.random.default_rng(77)
