@@ -44,6 +44,9 @@ def parse():
                     help="HIP streams the K steps are enqueued on in turn (each step is one whole pass on one stream, on "
                          "input sets of that stream's own): with 2, the attention kernels of one step overlap the expert "
                          "GEMMs of the previous one, as two concurrent requests would; 1 = strictly one step after another")
+    ap.add_argument("--settle-ms", type=float, default=250.0,
+                    help="untimed steps are run for this long before the W warm-up steps: the device takes on the order "
+                         "of 100 ms of load to reach its steady clocks, longer than a small W covers (0 = off)")
     ap.add_argument("--rotate", type=int, default=0,
                     help="input/workspace sets cycled through (0 = enough to exceed the 256 MiB last-level cache)")
     ap.add_argument("--shift-variant", type=int, default=3, choices=[0, 1, 2, 3],
@@ -190,6 +193,8 @@ def main():
     # ---- the timed region: W warm-up steps, then exactly K steps
     n_warm, n_steps = (0, 1) if args.kernels_only else (args.warmup, args.steps)
     run_steps = make_step_runner(torch, args.streams, n_sets, lambda i: blocks[i][0].forward())
+    if not args.kernels_only:
+        settle(torch, run_steps, args.settle_ms)
     run_steps(n_warm)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -285,7 +290,8 @@ def main():
                    "E": cfg.E, "hid": cfg.hid, "attention": cfg.attention,
                    "mlp": ("moe %.0f%% shift / %.0f%% fp16 mult" % (100 * cfg.shift_frac, 100 - 100 * cfg.shift_frac))
                    if moe else ("shift" if cfg.E else "none"),
-                   "input_sets_rotated": n_sets, "shift_variant": args.shift_variant, "streams": args.streams},
+                   "input_sets_rotated": n_sets, "shift_variant": args.shift_variant, "streams": args.streams,
+                   "settle_ms": args.settle_ms},
         "step_us": step_us,
         "block_hbm_roofline_frac": round(block_hbm_frac, 4),
         "block_algorithmic_bytes": block_bytes,
@@ -312,6 +318,15 @@ def make_step_runner(torch, n_streams, n_sets, forward_set):
             with torch.cuda.stream(streams[i % n_streams]):
                 forward_set(i % n_sets)
     return run
+
+
+def settle(torch, run_steps, ms):
+    """Runs untimed steps for about `ms` of wall-clock time, so that the W warm-up steps and the timed region start at
+    steady clocks whatever W is."""
+    t_end = time.perf_counter() + ms * 1e-3
+    while ms > 0 and time.perf_counter() < t_end:
+        run_steps(8)
+        torch.cuda.synchronize()
 
 
 def bench_shift_linear(args, sa, wl, torch, np):
@@ -498,6 +513,7 @@ def bench_layer(args, sa, wl, torch, np, cfg):
     n_sets = (n_sets + args.streams - 1) // args.streams * args.streams
     layers = [sa.Layer(x=dev(x_host), **shared) for _ in range(n_sets)]
     run_steps = make_step_runner(torch, args.streams, n_sets, lambda i: layers[i].forward())
+    settle(torch, run_steps, args.settle_ms)
     run_steps(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -630,7 +646,7 @@ def bench_layer(args, sa, wl, torch, np, cfg):
            "vs_baseline": None, "dtype": "f32+u64 codes+i8/i32 shift+f16 mult", "data": "synthetic",
            "config": {"workload": cfg.name.replace("block", "layer"), "B": cfg.B, "N": cfg.N, "H": H, "nbits": cfg.nbits, "E": E,
                       "hid": hid, "attention": cfg.attention, "mlp": "moe" if moe else "shift", "input_sets_rotated": n_sets,
-                      "shift_variant": var, "streams": args.streams},
+                      "shift_variant": var, "streams": args.streams, "settle_ms": args.settle_ms},
            "layer_hbm_roofline_frac": round(layer_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
            "layer_algorithmic_bytes": layer_bytes, "roofline": roofline, "cpu_baseline": cpu, "kernels": report}
     print(json.dumps(out))
