@@ -54,7 +54,8 @@ struct Tensors {
     uint64_t *codes0, *codes1;
 };
 
-template <int D>
+// RND steps of the chain per round trip of loads.
+template <int D, int RND>
 __device__ inline void settle_entry(uint64_t e, const Tensors &ts, const float *__restrict__ proj, const RowMap &map,
                                     int nbits) {
     const long row = (long)(e & 0xffffffffu);
@@ -66,19 +67,19 @@ __device__ inline void settle_entry(uint64_t e, const Tensors &ts, const float *
     const float *xr = x + (size_t)row * D;
     const float *pc = proj + col;
     float acc = 0.0f;
-    // 32 steps of the chain per round trip: loads first, then the fmas in their defined order
+    // loads first, then the fmas in their defined order
 #pragma unroll 1
-    for (int k0 = 0; k0 < D; k0 += 32) {
-        float xv[32], rv[32];
+    for (int k0 = 0; k0 < D; k0 += RND) {
+        float xv[RND], rv[RND];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < RND / 4; ++q) {
             const float4 t4 = *reinterpret_cast<const float4 *>(xr + k0 + 4 * q);
             xv[4 * q] = t4.x; xv[4 * q + 1] = t4.y; xv[4 * q + 2] = t4.z; xv[4 * q + 3] = t4.w;
         }
 #pragma unroll
-        for (int k = 0; k < 32; ++k) rv[k] = pc[(size_t)(k0 + k) * nbits];
+        for (int k = 0; k < RND; ++k) rv[k] = pc[(size_t)(k0 + k) * nbits];
 #pragma unroll
-        for (int k = 0; k < 32; ++k) acc = __builtin_fmaf(xv[k], rv[k], acc);
+        for (int k = 0; k < RND; ++k) acc = __builtin_fmaf(xv[k], rv[k], acc);
     }
     const bool exact = acc >= 0.0f;
     if (exact != prov)
@@ -93,7 +94,7 @@ __device__ __attribute__((noinline)) void work_off_list(const uint64_t *list, in
     const int lane = threadIdx.x & 63;
     __builtin_amdgcn_s_waitcnt(0x0F70);      // the words these bits live in have been stored
     for (int t0 = 0; t0 < cnt; t0 += 64)
-        if (t0 + lane < cnt) settle_entry<D>(list[t0 + lane], ts, proj, map, nbits);
+        if (t0 + lane < cnt) settle_entry<D, 32>(list[t0 + lane], ts, proj, map, nbits);
 }
 
 // D: head dim; G: hash columns handled by one workgroup (blockIdx.y selects the group).
@@ -225,14 +226,20 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
             for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) {
+            // all fragments of the step first, then the three products term by term, so that successive
+            // MFMAs go to different accumulators and none waits for the one before it
+            v8bf rh[JT], rl[JT];
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
-                const v8bf rh = __builtin_bit_cast(v8bf, frag[((s * JT + jt) * 2 + 0) * 64 + lane]);
-                const v8bf rl = __builtin_bit_cast(v8bf, frag[((s * JT + jt) * 2 + 1) * 64 + lane]);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xh[s], acc[jt], 0, 0, 0);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl, xh[s], acc[jt], 0, 0, 0);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh, xl[s], acc[jt], 0, 0, 0);
+                rh[jt] = __builtin_bit_cast(v8bf, frag[((s * JT + jt) * 2 + 0) * 64 + lane]);
+                rl[jt] = __builtin_bit_cast(v8bf, frag[((s * JT + jt) * 2 + 1) * 64 + lane]);
             }
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh[jt], xh[s], acc[jt], 0, 0, 0);
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rl[jt], xh[s], acc[jt], 0, 0, 0);
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rh[jt], xl[s], acc[jt], 0, 0, 0);
             // keep the steps apart: hoisting every fragment read of the tile to the top costs
             // 128 registers and one wavefront of occupancy
             __builtin_amdgcn_sched_barrier(0);
@@ -316,19 +323,20 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
         }   // column groups
     }
 
-    // The four wavefronts' leftovers are worked off together by wavefront 0: the cost of a pass is
-    // its uncoalesced loads, so one full pass beats four nearly empty ones.
+    // The four wavefronts' leftovers are pooled and worked off 64 entries per pass, pass p by wavefront
+    // p % 4: the cost of a pass is the latency of its uncoalesced loads, so full passes side by side
+    // beat both four nearly empty ones and a queue of full ones on one wavefront.
     __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's words have been stored
     if (lane == 0) cnt_s[wave] = cnt;
     __syncthreads();
-    if (wave == 0) {
+    {
         const int n0 = cnt_s[0], n1 = n0 + cnt_s[1], n2 = n1 + cnt_s[2], n3 = n2 + cnt_s[3];
-        for (int t0 = 0; t0 < n3; t0 += 64) {
+        for (int t0 = wave * 64; t0 < n3; t0 += 256) {
             const int t = t0 + lane;
             if (t < n3) {
                 const int w = (t >= n0) + (t >= n1) + (t >= n2);
                 const int base = w == 0 ? 0 : (w == 1 ? n0 : (w == 2 ? n1 : n2));
-                settle_entry<D>(list_s[w][t - base], ts, proj, map, nbits);
+                settle_entry<D, (D <= 64 ? D : 32)>(list_s[w][t - base], ts, proj, map, nbits);   // the tile loop's registers are free now
             }
         }
     }
