@@ -4,11 +4,14 @@
 // For almost every (row, bit) that sign is decided long before rounding matters, so the kernel
 //   1. computes z~ = x . r^_j on the bf16 matrix cores, r^_j = r_j / |r_j|, with a three-product
 //      split (x = xh + xl, r^ = rh + rl, z~ = xh rh + xh rl + xl rh: ~2^-15 relative accuracy),
-//   2. keeps sign(z~) wherever |z~| > 2^-12 * |x| (|x| |r^_j| is the Cauchy-Schwarz bound of
-//      sum |x_k r^_kj|; the chain's own error is at most 64 * 2^-24 of that sum, the split's and
-//      the normalisation's about 2^-15, so the margin is more than an order of magnitude), and
-//   3. re-runs the defining chain, one (row, bit) per lane, for the rest (about 0.2 % of the bits
-//      on Gaussian data; every bit if the data is degenerate) and flips the stored bit if needed.
+//   2. keeps sign(z~) wherever |z~| > 2^-13 * |x| (|x| |r^_j| is the Cauchy-Schwarz bound of
+//      sum |x_k r^_kj|; the split drops at most 3 * 2^-18 of that sum, the fp32 accumulation of the
+//      pre-pass and of the defining chain at most (d + 2) * 2^-24 of it each: 2^-15.4 |x| together
+//      at d = 64, so the margin is a factor of five over the worst case), and
+//   3. re-runs the defining chain, one (row, bit) per lane, for the rest (about 0.08 % of the bits
+//      on Gaussian data at d = 64; every bit if the data is degenerate) and flips the stored bit if
+//      needed.  These re-runs are the expensive part (80 uncoalesced loads per bit): a quarter of
+//      the kernel's time at a margin of 2^-12, hence the tighter one.
 // NaN / Inf / denormal-range sums fail the test in step 2 and take step 3, which is the definition.
 //
 // Tiles are 32 consecutive rows of the flattened [B*N*H, d] input (one contiguous 32*d*4-byte
@@ -28,7 +31,7 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kListCap = 192;                 // unsettled bits parked per wavefront
-constexpr float kKeepFactor = 6.26e-8f;       // (2^-12)^2 * 1.05: keep = sqrt(kKeepFactor * |x|^2)
+constexpr float kKeepFactor = 1.565e-8f;      // (2^-13)^2 * 1.05: keep = sqrt(kKeepFactor * |x|^2)
 constexpr float kKeepFloor = 1e-37f;          // keep >= ~3e-19: below that the relative error model does not hold
 
 struct RowMap {
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
 #pragma unroll
         for (int k = 0; k < HALF; ++k) nx2 += xv[k] * xv[k];
         nx2 += __shfl_xor(nx2, 32);                                // |x_row|^2, row = r0 + i_loc
-        // keep sign(z~) where |z~| > keep = 2^-12 |x| (floored); a non-finite |x|^2 keeps nothing
+        // keep sign(z~) where |z~| > keep = 2^-13 |x| (floored); a non-finite |x|^2 keeps nothing
         const float keep = nx2 < __builtin_inff() ? __builtin_sqrtf(__builtin_fmaxf(kKeepFactor * nx2, kKeepFloor))
                                                   : __builtin_inff();
 
