@@ -32,7 +32,7 @@ using sa::kWave;
 
 constexpr int kMaxWaves = 8;       // 32-query tiles per workgroup
 constexpr int kKeyChunk = 128;     // keys staged in LDS at a time
-constexpr int kStageBatch = 4;     // V staging tasks whose loads a thread keeps in flight together
+constexpr int kStageBatch = 2;     // V staging tasks (8 loads each) whose loads a thread keeps in flight together
 constexpr int kVtStride = kKeyChunk + 8;   // bf16 elements per transposed V row: 272 bytes, so that the
                                            // 16-byte reads of 16 consecutive columns hit 16 bank groups
 
@@ -95,6 +95,65 @@ __device__ inline void split_bf16_pair(float a, float b, uint32_t &upper, uint32
     r[0] -= __builtin_bit_cast(float, upper << 16);
     r[1] -= __builtin_bit_cast(float, upper & 0xFFFF0000u);
     lower = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2bf));
+}
+
+// A chunk of V rows -> the two transposed bf16 planes in LDS (keys n .. n_pad-1 are zero in both planes: their
+// numerators add nothing).  One task = eight consecutive keys of one column: the loads of a wavefront cover
+// whole rows of the head (coalesced), and the eight values of a task leave as 16 bytes per plane, at offsets
+// whose bank groups differ from lane to lane.  (Two keys x four columns per task, the shape a float4 load
+// suggests, puts 16 lanes of a 4-byte write on two banks.)  The loads of PT tasks are issued together.
+template <int DV, int STRIDE, int PT>
+struct VStage {
+    static_assert(STRIDE % 4 == 0, "8-byte pieces of a transposed row must be aligned");
+    float x[PT][8];
+    // tasks first, first + n_threads, ... (PT of them) of the chunk at key j0
+    __device__ inline void load(const float *__restrict__ v, int b, int H, int h, int Nk, int j0, int n, int n_pad, int first,
+                                int n_threads) {
+        const int n_tasks = (n_pad / 8) * DV;
+        const size_t row = (size_t)H * DV;
+#pragma unroll
+        for (int u = 0; u < PT; ++u) {
+            const int t = first + u * n_threads;
+            const int col = t % DV, j = 8 * (t / DV);
+            const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + col;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[u][e] = (t < n_tasks && j + e < n) ? vp[e * row] : 0.0f;
+        }
+    }
+    __device__ inline void store(int n_pad, uint16_t *vth_s, uint16_t *vtl_s, int first, int n_threads) const {
+        const int n_tasks = (n_pad / 8) * DV;
+#pragma unroll
+        for (int u = 0; u < PT; ++u) {
+            const int t = first + u * n_threads;
+            if (t >= n_tasks) continue;
+            const int col = t % DV, j = 8 * (t / DV);
+            uint32_t up[4], lo[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) split_bf16_pair(x[u][2 * e2], x[u][2 * e2 + 1], up[e2], lo[e2]);
+            const int off = col * STRIDE + j;
+            if constexpr (STRIDE % 8 == 0) {
+                *reinterpret_cast<uint4 *>(vth_s + off) = make_uint4(up[0], up[1], up[2], up[3]);
+                *reinterpret_cast<uint4 *>(vtl_s + off) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            } else {
+                *reinterpret_cast<uint2 *>(vth_s + off) = make_uint2(up[0], up[1]);
+                *reinterpret_cast<uint2 *>(vth_s + off + 4) = make_uint2(up[2], up[3]);
+                *reinterpret_cast<uint2 *>(vtl_s + off) = make_uint2(lo[0], lo[1]);
+                *reinterpret_cast<uint2 *>(vtl_s + off + 4) = make_uint2(lo[2], lo[3]);
+            }
+        }
+    }
+};
+
+// The whole chunk, loads and stores back to back (kStageBatch tasks per round trip).
+template <int DV, int STRIDE>
+__device__ inline void stage_v(const float *__restrict__ v, int b, int H, int h, int Nk, int j0, int n, int n_pad,
+                               uint16_t *vth_s, uint16_t *vtl_s, int tid, int n_threads) {
+    const int n_tasks = (n_pad / 8) * DV;
+    for (int base = 0; base < n_tasks; base += n_threads * kStageBatch) {
+        VStage<DV, STRIDE, kStageBatch> st;
+        st.load(v, b, H, h, Nk, j0, n, n_pad, base + tid, n_threads);
+        st.store(n_pad, vth_s, vtl_s, base + tid, n_threads);
+    }
 }
 
 struct TableEntry {
@@ -285,38 +344,7 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
         const int n_pad = (n + 15) & ~15;
         __syncthreads();                           // the previous chunk has been consumed (and the table is there)
         for (int t = tid; t < n_pad * W; t += n_threads) kc_s[t] = (t < n * W) ? kc_g[(size_t)j0 * W + t] : 0ull;
-        // V: one task = two consecutive keys x four columns -> four dwords into each transposed plane
-        // (consecutive threads take consecutive float4s of a row: coalesced reads).  The loads of
-        // kStageBatch tasks are issued together, so a chunk costs a few memory round trips, not one
-        // per task.  Keys past the last one are zero in both planes: their numerators add nothing.
-        const int n_tasks = (n_pad / 2) * (DV / 4);
-        for (int base = 0; base < n_tasks; base += n_threads * kStageBatch) {
-            float4 v0[kStageBatch], v1[kStageBatch];
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int t = base + u * n_threads + tid;
-                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
-                v0[u] = v1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c4 * 4;
-                if (t < n_tasks && j < n) v0[u] = *reinterpret_cast<const float4 *>(vp);
-                if (t < n_tasks && j + 1 < n) v1[u] = *reinterpret_cast<const float4 *>(vp + (size_t)H * DV);
-            }
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int t = base + u * n_threads + tid;
-                if (t >= n_tasks) continue;
-                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
-                const float a0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, a1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    uint32_t up, lo;
-                    split_bf16_pair(a0[c], a1[c], up, lo);
-                    const int off = (c4 * 4 + c) * kVtStride + j;      // even: 4-byte aligned
-                    *reinterpret_cast<uint32_t *>(vth_s + off) = up;
-                    *reinterpret_cast<uint32_t *>(vtl_s + off) = lo;
-                }
-            }
-        }
+        stage_v<DV, kVtStride>(v, b, H, h, Nk, j0, n, n_pad, vth_s, vtl_s, tid, n_threads);
         __syncthreads();
         const int n_full = n & ~15;                // whole steps first, then at most one masked step
         for (int k0 = 0; k0 < n_full; k0 += 16) step(k0, n, std::false_type{});
@@ -489,34 +517,7 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mm_kernel(
             }
         }
         // V: as in the kernel above, padded to whole 32-key steps
-        const int n_tasks = (n_pad / 2) * (DV / 4);
-        for (int base = 0; base < n_tasks; base += n_threads * kStageBatch) {
-            float4 v0[kStageBatch], v1[kStageBatch];
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int t = base + u * n_threads + tid;
-                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
-                v0[u] = v1[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                const float *vp = v + (((size_t)b * Nk + j0 + j) * H + h) * DV + c4 * 4;
-                if (t < n_tasks && j < n) v0[u] = *reinterpret_cast<const float4 *>(vp);
-                if (t < n_tasks && j + 1 < n) v1[u] = *reinterpret_cast<const float4 *>(vp + (size_t)H * DV);
-            }
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int t = base + u * n_threads + tid;
-                if (t >= n_tasks) continue;
-                const int c4 = t % (DV / 4), j = 2 * (t / (DV / 4));
-                const float a0[4] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w}, a1[4] = {v1[u].x, v1[u].y, v1[u].z, v1[u].w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    uint32_t up, lo;
-                    split_bf16_pair(a0[c], a1[c], up, lo);
-                    const int off = (c4 * 4 + c) * kVtStride8 + j;      // even: 4-byte aligned
-                    *reinterpret_cast<uint32_t *>(vth_s + off) = up;
-                    *reinterpret_cast<uint32_t *>(vtl_s + off) = lo;
-                }
-            }
-        }
+        stage_v<DV, kVtStride8>(v, b, H, h, Nk, j0, n, n_pad, vth_s, vtl_s, tid, n_threads);
         __syncthreads();
         const int n_full = n & ~31;                // whole steps first, then at most one masked step
         for (int k0 = 0; k0 < n_full; k0 += 32) step(k0, n, std::false_type{});
