@@ -257,6 +257,24 @@ def test_shift_linear_on_prepared_planes(sa, M, K, N):
     assert np.array_equal(got, oracle.shift_linear(x, w4))
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_shift_linear_random_shapes(sa, seed):
+    """Ragged M and N around the tile edges of all three int8 tilings (row tiles of 128 and 256, column tiles of
+    128, stages of 64 and 128 bytes), weights decoded per call and prepared planes."""
+    g = np.random.default_rng([77, seed])
+    M = int(g.choice([1, 63, 127, 129, 255, 257, 511, 700, 1025])) + int(g.integers(0, 3))
+    K = 64 * int(g.choice([1, 2, 3, 5, 8, 12, 32, 33, 48]))
+    N = int(g.choice([1, 31, 127, 128, 129, 200, 383, 640, 1300]))
+    neg = g.integers(0, 2, size=(N, K), dtype=np.uint8)
+    e = g.integers(0, 8, size=(N, K), dtype=np.uint8)
+    w4 = wl.pack_w4(neg, e)
+    x = g.integers(-127, 128, size=(M, K), dtype=np.int8)
+    ref = oracle.shift_linear(x, w4)
+    assert np.array_equal(host(sa.sa_shift_linear(dev(x), dev(w4), variant=1)), ref), (M, K, N)
+    planes = sa.sa_shift_planes_prepare(dev(w4))
+    assert np.array_equal(host(sa.sa_shift_linear(dev(x), planes, variant=3)), ref), (M, K, N)
+
+
 def test_shift_linear_auto_falls_back_when_k_not_multiple_of_64(sa):
     M, K, N = 40, 96, 33
     w4 = wl.shift_weights(3, 5, N, K)
