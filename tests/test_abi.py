@@ -139,3 +139,13 @@ def test_argument_errors_of_the_layer_entry_points_without_a_gpu(lib):
     lib.sa_layer_workspace_bytes.restype = ctypes.c_size_t
     assert lib.sa_layer_workspace_bytes(null) == 0
     assert lib.sa_layer_forward(null, null) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The bench measures one GPU: asked for more, it exits with a message and code 2 before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in (r.stdout + r.stderr)
