@@ -3,17 +3,22 @@
 //     C[m, n] = sum_p sum_k A[m, k] * B_p[n, k]
 //
 // Workgroup tile BM x BN, four wavefronts in a 2 x 2 grid, each owning (BM/2) x (BN/2) as
-// 32x32 MFMA tiles.  K advances 64 bytes per stage through a double-buffered LDS tile that
-// is filled by direct global->LDS loads (no register staging): while stage s is multiplied
-// out of one buffer, the loads of stage s+1 are in flight into the other; one barrier per
-// stage, and the LDS fragment reads run one half-stage ahead of the MFMAs that consume them.  A direct load writes 1 KiB of consecutive LDS per wavefront instruction, so LDS
-// rows cannot be padded; instead the 16-byte chunks of a row are XOR-swizzled with the row
-// number (the lane chooses which global chunk it fetches), which makes the 16-byte fragment
-// reads of any 16 consecutive rows hit 16 different bank groups.
+// 32x32 MFMA tiles.  K advances SB bytes (64 or 128) per stage through a ring of NS (2 to 4) LDS
+// stage buffers that is filled by direct global->LDS loads (no register staging): while stage s
+// is multiplied out of one buffer, the loads of the following stages are in flight into the
+// others; one barrier per stage; the LDS fragment reads run one 32-byte step ahead of the MFMAs
+// that consume them, and the loads of a stage are spread between the MFMAs of LS steps.  A direct
+// load writes 1 KiB of consecutive LDS per wavefront instruction, so LDS rows cannot be padded;
+// instead the 16-byte chunks of a row are XOR-swizzled with the row number (the lane chooses
+// which global chunk it fetches), which makes the 16-byte fragment reads of any 16 consecutive
+// rows hit 16 different bank groups.
 //
-// The loads are issued from inline assembly: the kernel orders them by hand (one vmcnt(0)
-// and one barrier per stage), and the compiler must not serialise the reads of the current
-// buffer behind the loads in flight into the other one.
+// The loads are issued from inline assembly: the kernel orders them by hand (one vmcnt wait and
+// one barrier per stage), and the compiler must not serialise the reads of the current buffer
+// behind the loads in flight into the other ones.  The K loop is written out in five pieces
+// (first stage, steady state, the stage after which no load is left to issue, the stages that
+// only drain, the last stage) so that the steady state holds no branch around a load and no
+// branch join in front of its MFMAs.
 //
 // Outputs leave through LDS, 64 rows per pass, so that every lane stores 16 bytes of one row
 // (a scattered destination row index and its gate are then fetched once per 16 bytes).
@@ -204,31 +209,25 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // fragment read offsets (bytes inside a tile) for the 32-byte steps of a stage
+    // fragment read offsets (bytes inside a tile) for the 32-byte steps of a stage.  The swizzle of a row depends
+    // on the row number modulo 16 only, so tile i of a wavefront reads at the offset of its tile 0 plus 32 rows * i.
     const int fr = lane & 31, fg = lane >> 5;
-    int a_rd[MI][KK], b_rd[NJ][KK];
+    int a_rd[KK], b_rd[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int r = wm + i * 32 + fr;
-            a_rd[i][kk] = r * kStageBytes + swizzle<kChunksPerRow>(r, 2 * kk + fg) * 16;
-        }
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            const int r = wn + j * 32 + fr;
-            b_rd[j][kk] = r * kStageBytes + swizzle<kChunksPerRow>(r, 2 * kk + fg) * 16;
-        }
+        a_rd[kk] = (wm + fr) * kStageBytes + swizzle<kChunksPerRow>(wm + fr, 2 * kk + fg) * 16;
+        b_rd[kk] = (wn + fr) * kStageBytes + swizzle<kChunksPerRow>(wn + fr, 2 * kk + fg) * 16;
     }
 
     auto read_frags = [&](const uint8_t *A, int kk, uint4 (&af)[MI], uint4 (&bf)[NP][NJ]) {
         const uint8_t *B = A + A_BYTES;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const uint4 *>(A + a_rd[i][kk]);
+        for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const uint4 *>(A + a_rd[kk] + i * 32 * kStageBytes);
 #pragma unroll
         for (int p = 0; p < NP; ++p)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) bf[p][j] = *reinterpret_cast<const uint4 *>(B + p * B_BYTES + b_rd[j][kk]);
+            for (int j = 0; j < NJ; ++j)
+                bf[p][j] = *reinterpret_cast<const uint4 *>(B + p * B_BYTES + b_rd[kk] + j * 32 * kStageBytes);
     };
     // One 32-byte step of MFMAs.  When phase >= 0, the direct loads [phase * LPS, (phase+1) * LPS)
     // of the stage at byte kbyte are issued into ring slot `slot`, evenly spaced between the MFMAs:
@@ -236,8 +235,9 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
     // (about 1 KiB per 16 cycles and CU) and leaves its matrix core idle meanwhile.
     constexpr int MFMAS = NP * MI * NJ;
     constexpr int LPS = (LOADS + LS - 1) / LS;          // loads per step
-    auto multiply = [&](const uint4 (&af)[MI], const uint4 (&bf)[NP][NJ], auto phase_c, bool more, int slot, int kbyte) {
+    auto multiply = [&](const uint4 (&af)[MI], const uint4 (&bf)[NP][NJ], auto phase_c, auto more_c, bool more, int slot, int kbyte) {
         constexpr int phase = decltype(phase_c)::value;
+        constexpr int MORE = decltype(more_c)::value;      // 1: always, 0: never, -1: `more` decides
         static_for<MFMAS>([&](auto m_c) {
             constexpr int m = decltype(m_c)::value;             // MFMAs issued before this one
             constexpr int p = m / (MI * NJ), i = m / NJ % MI, j = m % NJ;
@@ -249,8 +249,12 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<q1 - q0>([&](auto d_c) {
                         constexpr int q = phase * LPS + q0 + decltype(d_c)::value;
-                        if constexpr (q < LOADS)
-                            if (more) issue_load(q, slot, kbyte);
+                        if constexpr (q < LOADS && MORE != 0) {
+                            if constexpr (MORE == 1)
+                                issue_load(q, slot, kbyte);
+                            else if (more)
+                                issue_load(q, slot, kbyte);
+                        }
                     });
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -287,34 +291,59 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
     __syncthreads();                             // ... and everyone's
     read_frags(lds, 0, af[0], bf[0]);
     int buf = 0, prev = NS - 1;                  // ring slots of stage s and of stage s-1
-    for (int s = 0; s < n_stages; ++s) {
+    // One stage.  What depends on the position in the K loop is passed as a compile-time constant where the caller
+    // knows it (1 = yes, 0 = no, -1 = decide at run time), so that the steady state has no branch around a load and
+    // no branch join in front of the MFMAs (at a join the compiler must assume the longer of the two wait lists):
+    //   next : there is a stage s+1 (hand-over barrier and its first fragment reads)
+    //   m0   : stage s+NS exists (its first share of loads goes into the slot this stage leaves)
+    //   m1   : stage s-1+NS exists and s >= 1 (its further shares go into the slot of stage s-1)
+    auto stage = [&](int s, auto next_c, auto m0_c, auto m1_c) {
+        constexpr int NEXT = decltype(next_c)::value, M0 = decltype(m0_c)::value, M1 = decltype(m1_c)::value;
+        const bool next = NEXT < 0 ? s + 1 < n_stages : NEXT != 0;
+        const bool m0 = M0 < 0 ? s + NS < n_stages : M0 != 0;
+        const bool m1 = M1 < 0 ? (s >= 1 && s - 1 + NS < n_stages) : M1 != 0;
         const uint8_t *cur = lds + buf * STAGE;
         const int nxt = buf + 1 == NS ? 0 : buf + 1;
         static_for<KK>([&](auto kk_c) {
             constexpr int kk = decltype(kk_c)::value;
             if constexpr (kk + 1 < KK) {
                 read_frags(cur, kk + 1, af[(kk + 1) & 1], bf[(kk + 1) & 1]);
-            } else if (s + 1 < n_stages) {
+            } else if (next) {
                 // stage s+1 has landed (this wavefront's part); stages s+2 .. s+NS-1 may still be in flight
-                wait_all_but((s + NS - 1 < n_stages ? s + NS - 1 : n_stages - 1) - (s + 1));
+                if constexpr (M0 == 1)
+                    wait_all_but(NS - 2);
+                else
+                    wait_all_but((s + NS - 1 < n_stages ? s + NS - 1 : n_stages - 1) - (s + 1));
                 __syncthreads();                 // everyone's has, and everyone holds its last fragments of stage s
                 read_frags(lds + nxt * STAGE, 0, af[0], bf[0]);
             }
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (kk == KK - 1) {
                 // first share of stage s+NS, into the slot this stage has just left
-                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, 0>{}, s + NS < n_stages, buf, (s + NS) * kStageBytes);
+                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, 0>{}, m0_c, m0, buf, (s + NS) * kStageBytes);
             } else if constexpr (kk + 1 < LS) {
                 // further shares of stage s-1+NS, into the slot of stage s-1
-                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, kk + 1>{}, s >= 1 && s - 1 + NS < n_stages, prev,
-                         (s - 1 + NS) * kStageBytes);
+                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, kk + 1>{}, m1_c, m1, prev, (s - 1 + NS) * kStageBytes);
             } else {
-                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, -1>{}, false, 0, 0);
+                multiply(af[kk & 1], bf[kk & 1], std::integral_constant<int, -1>{}, std::integral_constant<int, 0>{}, false, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
         prev = buf;
         buf = nxt;
+    };
+    using Yes = std::integral_constant<int, 1>;
+    using No = std::integral_constant<int, 0>;
+    using Ask = std::integral_constant<int, -1>;
+    if (n_stages > NS + 1) {
+        int s = 0;
+        stage(s++, Yes{}, Yes{}, No{});
+        for (; s < n_stages - NS; ++s) stage(s, Yes{}, Yes{}, Yes{});
+        stage(s++, Yes{}, No{}, Yes{});
+        for (; s < n_stages - 1; ++s) stage(s, Yes{}, No{}, No{});
+        stage(s, No{}, No{}, No{});
+    } else {
+        for (int s = 0; s < n_stages; ++s) stage(s, Ask{}, Ask{}, Ask{});
     }
 
     // ---- sign codes: a wavefront's 64 columns are one code word of a head; one ballot per accumulator
@@ -463,11 +492,11 @@ int launch_gemm_tile(const GemmArgs &g, const Store &store, hipStream_t st, cons
 
 // Tile choice, from timings of the expert layers of the DeiT-Base block on one MI355X:
 //  * long rows (>= 2 KiB) in whole 128-byte lines: 128-byte stages pay (every request is a
-//    whole cache line); int8 takes the 256 x 128 tile, one workgroup per CU; fp16, whose
-//    steps hold half as many MFMAs, takes 64 x 128 with a ring of three, two per CU;
-//  * short rows leave only a few stages per tile, so prologue and epilogue must hide behind
-//    another resident workgroup: int8 takes 64-byte stages (two or three workgroups per CU),
-//    fp16 128 x 64 tiles with 128-byte stages (two per CU).
+//    whole cache line); int8 takes the 256 x 128 tile, one workgroup per CU; fp16 takes
+//    128 x 128 with a ring of three, one per CU (64 x 128, two per CU, when there are few rows);
+//  * short rows leave only a few stages per tile: int8 takes 64-byte stages so that two or
+//    three workgroups per CU hide each other's prologue and epilogue; fp16 takes 192 x 128 tiles
+//    with 128-byte stages, one per CU (128 x 64, two per CU, when there are few rows).
 // Narrow (1- and 2-byte) output rows must be whole 16-byte chunks; operand rows must be a
 // multiple of 64 bytes long.
 template <class T, class Store>
@@ -484,8 +513,13 @@ int launch_gemm(const GemmArgs &g, const Store &store, hipStream_t st, const cha
         if (blocks256 >= 512) return launch_gemm_tile<T, 256, 128, 64, 2, 1, 2, Store>(g, store, st, what);
         return launch_gemm_tile<T, 128, 128, 64, 2, 1, 3, Store>(g, store, st, what);
     } else {
-        if (lines && long_rows) return launch_gemm_tile<T, 64, 128, 128, 3, 2, 2, Store>(g, store, st, what);
-        if (lines) return launch_gemm_tile<T, 128, 64, 128, 2, 2, 2, Store>(g, store, st, what);
+        const bool many_rows = g.sel.max_rows >= 2048;
+        if (lines && long_rows)
+            return many_rows ? launch_gemm_tile<T, 128, 128, 128, 3, 2, 1, Store>(g, store, st, what)
+                             : launch_gemm_tile<T, 64, 128, 128, 3, 2, 2, Store>(g, store, st, what);
+        if (lines)
+            return many_rows ? launch_gemm_tile<T, 192, 128, 128, 2, 2, 1, Store>(g, store, st, what)
+                             : launch_gemm_tile<T, 128, 64, 128, 2, 2, 2, Store>(g, store, st, what);
         return launch_gemm_tile<T, 128, 128, 64, 3, 1, 2, Store>(g, store, st, what);
     }
 }

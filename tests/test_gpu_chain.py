@@ -1,0 +1,256 @@
+"""Chained-stage GPU parity: every stage of the block is fed what the GPU's own previous stage produced.
+
+The end-to-end comparisons (test_block_forward_matches_oracle, test_layer_forward_matches_oracle) can only be
+statistical, because an int8 quantiser sits between the float stages: a float that differs from the oracle's in
+its last bits now and then lands on the other side of a rounding boundary.  Here nothing is excused: the
+oracle's stage k+1 runs on the GPU's output of stage k, so the two sides see the same integers and the GPU's
+stage k+1 must agree element by element (bit-exact where it is integer work).  At the full benchmark sizes the
+oracle recomputes whole sampled batch elements (they are independent in every stage) or sampled token rows.
+
+Also here: the integer Hamming scores the attention kernels actually use (Eq. 1 on codes), recovered from the
+softmax weights themselves.
+"""
+import dataclasses
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import ATTN_ATOL, ATTN_RTOL, assert_close, dev, host
+from paper_2306_06446_amd import workloads as wl
+from test_gpu_layer import check_codes, layer_kwargs
+from test_gpu_parity import _block_inputs, run_block
+
+pytestmark = pytest.mark.gpu
+
+SHIFT_RTOL, SHIFT_ATOL = 3e-6, 1e-7      # gate (1e-6 relative) and three fp32 roundings on an exact integer
+MULT_RTOL, MULT_ATOL = 2e-3, 1e-3        # fp16 operands, hidden activation rounded to fp16
+
+
+def sampled_tokens(cfg, batches, per_batch):
+    g = np.random.default_rng([17, cfg.cfg_id])
+    toks = []
+    for b in batches:
+        n = np.arange(cfg.N) if per_batch >= cfg.N else np.sort(g.choice(cfg.N, size=per_batch, replace=False))
+        toks.append(b * cfg.N + n)
+    return np.concatenate(toks)
+
+
+# ------------------------------------------------------------------------------------- the block ---
+
+BLOCK_CASES = [
+    (wl.C1, [0], 197, False),
+    (wl.scaled_down(wl.C4, B=2), [0, 1], 197, False),
+    (wl.scaled_down(wl.C5, B=1, N=1100), [0], 1100, False),
+    (wl.C4, [0, 17, 63], 197, True),           # full size, whole sampled batch elements
+    (wl.C5, [5], 1536, True),                  # full size, sampled token rows of one batch element
+]
+
+
+@pytest.mark.parametrize("cfg,batches,per_batch,prepared", BLOCK_CASES,
+                         ids=lambda c: getattr(c, "name", None) if isinstance(c, wl.BlockConfig) else None)
+def test_block_mlp_on_the_gpus_own_attention_output(sa, cfg, batches, per_batch, prepared):
+    """GPU O -> oracle MLP / MoE stage -> must equal the GPU's y element by element."""
+    inputs = _block_inputs(cfg)
+    q, k, v, pr, scale, p, logits = inputs
+    o, y = run_block(sa, cfg, inputs, prepared=prepared)
+    tokens = sampled_tokens(cfg, batches, per_batch)
+    x = o.reshape(cfg.T, cfg.E)[tokens]
+    y_ref = oracle.mlp_stage(x, None if logits is None else logits[tokens], p)
+    got = y[tokens].astype(np.float64)
+    if logits is None:
+        assert_close(got, y_ref, SHIFT_RTOL, SHIFT_ATOL, "Shift MLP on the GPU's attention output")
+    else:
+        shift = logits[tokens, 1] > logits[tokens, 0]
+        assert 0 < shift.sum() < len(tokens)
+        assert_close(got[shift], y_ref[shift], SHIFT_RTOL, SHIFT_ATOL, "Shift expert rows")
+        assert_close(got[~shift], y_ref[~shift], MULT_RTOL, MULT_ATOL, "Mult expert rows")
+    # extra, for the record: how the same rows compare with the pure-oracle chain (the statistical test's quantity)
+    b0 = batches[0]
+    sub = dataclasses.replace(cfg, B=1)
+    o_ref, y_pure = oracle.block_forward(sub, q[b0:b0 + 1], k[b0:b0 + 1], v[b0:b0 + 1], pr, scale,
+                                         None if logits is None else logits[b0 * cfg.N:(b0 + 1) * cfg.N], p)
+    assert_close(o[b0], o_ref[0], ATTN_RTOL, ATTN_ATOL, "attention output, batch %d" % b0)
+    rows = slice(b0 * cfg.N, (b0 + 1) * cfg.N)
+    rms = float(np.sqrt(np.mean(np.square(y_pure))))
+    tight = np.abs(y[rows] - y_pure) <= 2e-3 * np.abs(y_pure) + 1e-3 * rms
+    print("block %s batch %d: %.5f of the outputs agree tightly with the pure-oracle chain" % (cfg.name, b0, tight.mean()))
+
+
+# ------------------------------------------------------------------------------------- the layer ---
+
+def run_layer_stages(sa, cfg, kw):
+    """The layer as the chain of its stage entry points, keeping every intermediate (device tensors)."""
+    T, E, H = cfg.T, cfg.E, cfg.H
+    var = kw["shift_variant"]
+    r = {}
+    _, r["z1q"], _, _ = sa.sa_layernorm_quant(kw["x"], kw["gamma1"], kw["beta1"], kw["eps"], kw["ln_inv_scale"],
+                                              want_ln=False, want_q=True)
+    r["q"], r["k"], r["v"] = sa.sa_shift_linear_f32(r["z1q"], kw["wqkv"], kw["qkv_scale"], parts=3, variant=var)
+    q4, k4, v4 = (r[n].view(cfg.B, cfg.N, H, E // H) for n in ("q", "k", "v"))
+    r["qc"], r["kc"] = sa.sa_binarize_pair(q4, k4, kw["proj"], cfg.nbits)
+    if cfg.attention == "linear":
+        o, _ = sa.sa_additive_attention(r["qc"], r["kc"], v4, kw["attn_scale"], cfg.nbits)
+        r["o"] = o.view(T, E)
+        r["oq"] = sa.sa_quantize_act(r["o"], kw["act_inv_scale"])
+    else:
+        o, oq, _ = sa.sa_hamming_attention_fused(r["qc"], r["kc"], v4, kw["attn_scale"], cfg.nbits, kw["act_inv_scale"],
+                                                 want_xh=False, want_out=True)
+        r["o"], r["oq"] = o.view(T, E), oq.view(T, E)
+    (x1,) = sa.sa_shift_linear_f32(r["oq"], kw["wo"], kw["o_scale"], residual=kw["x"], variant=var)
+    r["x1"] = x1.clone()
+    moe = bool(kw["moe"])
+    _, r["z2q"], r["xh"], r["logits"] = sa.sa_layernorm_quant(x1, kw["gamma2"], kw["beta2"], kw["eps"], kw["ln_inv_scale"],
+                                                              want_ln=False, want_q=True, want_half=moe, wg=kw.get("wg"),
+                                                              bg=kw.get("bg"))
+    acc = sa.binding.SA_MLP_ACCUMULATE
+    if not moe:
+        sa.sa_shift_mlp(r["z2q"], kw["w1"], kw["w2"], kw["requant_scale"], kw["lut"], want_y2=False, y=x1,
+                        out_scale=kw["out_scale"], variant=var, stages=3 | acc)
+    else:
+        r["perm"], r["expert_of"], r["counts"], r["gate"] = sa.sa_moe_dispatch(r["logits"])
+        sa.sa_mult_mlp_f16_half(r["xh"], kw["mw1"], kw["mw2"], rows=r["perm"], counts=r["counts"], expert=0, max_rows=T,
+                                want_out=False, y=x1, gate=r["gate"], stages=3 | acc)
+        sa.sa_shift_mlp(r["z2q"], kw["w1"], kw["w2"], kw["requant_scale"], kw["lut"], rows=r["perm"], counts=r["counts"],
+                        expert=1, max_rows=T, want_y2=False, y=x1, gate=r["gate"], out_scale=kw["out_scale"], variant=var,
+                        stages=3 | acc)
+    r["y"] = x1
+    torch.cuda.synchronize()
+    return r
+
+
+LAYER_CASES = [
+    (wl.scaled_down(wl.C4, B=2), [0, 1], 197, False),
+    (wl.scaled_down(wl.C5, B=1, N=1100), [0], 1100, False),
+    (wl.C1, [0], 197, False),
+    (wl.C4, [0, 41], 197, True),
+    (wl.C5, [3], 1024, True),
+]
+
+
+@pytest.mark.parametrize("cfg,batches,per_batch,prepared", LAYER_CASES,
+                         ids=lambda c: getattr(c, "name", None) if isinstance(c, wl.BlockConfig) else None)
+def test_layer_stage_by_stage_on_the_gpus_own_intermediates(sa, cfg, batches, per_batch, prepared):
+    x = wl.layer_input(cfg)
+    lp, p, proj, scale = wl.layer_params(cfg), wl.mlp_params(cfg), wl.proj(cfg), wl.attention_scale(cfg)
+    kw = layer_kwargs(sa, cfg, x, lp, p, proj, scale, prepared=prepared)
+    g = {n: (host(t) if t is not None else None) for n, t in run_layer_stages(sa, cfg, kw).items()}
+    y_layer = host(sa.binding.Layer(**kw).forward())
+    assert np.array_equal(y_layer, g["y"]), "sa_layer_forward differs from the chain of its entry points"
+    B, N, H, E, d = cfg.B, cfg.N, cfg.H, cfg.E, cfg.E // cfg.H
+    moe = lp.wg is not None
+    if moe:
+        # routing of all T tokens from the GPU's own logits: indices and counts exact
+        perm_r, eo_r, cnt_r, gate_r = oracle.moe_dispatch(g["logits"])
+        assert np.array_equal(g["perm"], perm_r) and np.array_equal(g["expert_of"], eo_r)
+        assert np.array_equal(g["counts"], cnt_r)
+        assert_close(g["gate"], gate_r, 1e-6, 0.0, "gate")
+    for b in batches:
+        rows = np.arange(b * N, (b + 1) * N)
+        # LayerNorm 1 -> int8 codes
+        check_codes(g["z1q"][rows], oracle.layernorm(x[rows], lp.gamma1, lp.beta1, lp.eps), lp.ln_inv_scale, 1e-4)
+        # Q, K, V: shift Linears on the GPU's codes, one fused multiply-add each: bit-exact
+        for name, w in (("q", lp.wq), ("k", lp.wk), ("v", lp.wv)):
+            ref = oracle.dequant_residual(oracle.shift_linear(g["z1q"][rows], w), lp.qkv_scale)
+            assert np.array_equal(g[name][rows], ref), "%s projection, batch %d" % (name, b)
+        # hash of the GPU's Q and K: bit-exact
+        q4, k4, v4 = (g[n][rows].reshape(1, N, H, d) for n in ("q", "k", "v"))
+        qc, kc = g["qc"].view(np.uint64)[b:b + 1], g["kc"].view(np.uint64)[b:b + 1]
+        assert np.array_equal(qc, oracle.binarize(q4, proj, cfg.nbits)), "Q codes, batch %d" % b
+        assert np.array_equal(kc, oracle.binarize(k4, proj, cfg.nbits)), "K codes, batch %d" % b
+        # attention on the GPU's codes and V
+        if cfg.attention == "linear":
+            o_ref, _ = oracle.additive_attention(qc, kc, v4, cfg.nbits, scale)
+        else:
+            o_ref = oracle.hamming_attention(qc, kc, v4, cfg.nbits, scale)
+        assert_close(g["o"][rows], o_ref.reshape(N, E), ATTN_RTOL, ATTN_ATOL, "attention output, batch %d" % b)
+        # its int8 form is the quantiser applied to the GPU's own fp32 output: bit-exact
+        assert np.array_equal(g["oq"][rows], oracle.quantize_act(g["o"][rows], p.act_inv_scale))
+        # output projection + residual: bit-exact
+        ref = oracle.dequant_residual(oracle.shift_linear(g["oq"][rows], lp.wo), lp.o_scale, x[rows])
+        assert np.array_equal(g["x1"][rows], ref), "output projection, batch %d" % b
+        # LayerNorm 2 on the GPU's X_attn: codes, fp16 rows, router logits
+        ln2 = oracle.layernorm(g["x1"][rows], lp.gamma2, lp.beta2, lp.eps)
+        check_codes(g["z2q"][rows], ln2, lp.ln_inv_scale, 1e-4)
+        if moe:
+            assert_close(g["xh"][rows].astype(np.float64), ln2, 1e-3, 1e-6, "fp16 rows")
+            assert_close(g["logits"][rows], oracle.router_logits(ln2, lp.wg, lp.bg), 1e-5, 2e-5, "router logits")
+        # experts on the GPU's codes / fp16 rows, added to the GPU's X_attn rows with the GPU's gate
+        sub = rows if per_batch >= N else b * N + np.sort(np.random.default_rng([19, b]).choice(N, per_batch, replace=False))
+        x1 = g["x1"][sub].astype(np.float64)
+        out_scale = np.float64(np.float32(p.out_scale))
+        if not moe:
+            y_ref = x1 + out_scale * oracle.shift_mlp(g["z2q"][sub], p.w1, p.w2, p.requant_scale, p.lut)
+            assert_close(g["y"][sub], y_ref, SHIFT_RTOL, 1e-6, "Shift MLP + residual, batch %d" % b)
+        else:
+            shift = g["expert_of"][sub] == 1
+            gate = g["gate"][sub].astype(np.float64)[:, None]
+            s_rows, m_rows = sub[shift], sub[~shift]
+            y_s = x1[shift] + gate[shift] * out_scale * oracle.shift_mlp(g["z2q"][s_rows], p.w1, p.w2, p.requant_scale, p.lut)
+            y_m = x1[~shift] + gate[~shift] * oracle.mult_mlp(g["xh"][m_rows].astype(np.float32), None, p.mw1, p.mw2)
+            assert_close(g["y"][s_rows], y_s, SHIFT_RTOL, 1e-6, "Shift expert + residual, batch %d" % b)
+            assert_close(g["y"][m_rows], y_m, MULT_RTOL, MULT_ATOL, "Mult expert + residual, batch %d" % b)
+
+
+# ------------------------------------------------ the scores the attention kernels actually use ---
+
+def one_hot_values(B, Nk, H, dv, first):
+    """V whose key row first + c is the unit vector e_c (c < dv), every other key row zero: output column c of a
+    query is then the softmax weight of key first + c, normalised by the sum over ALL keys."""
+    v = np.zeros((B, Nk, H, dv), dtype=np.float32)
+    for c in range(min(dv, Nk - first)):
+        v[:, first + c, :, c] = 1.0
+    return v
+
+
+def near_codes(seed, shape, nbits, max_flips):
+    """Codes within a few bit flips of one base code per (batch, head): small score differences, so that even a
+    sharp softmax keeps every weight far above the underflow threshold."""
+    g = np.random.default_rng([23, seed])
+    B, H, N = shape
+    W = nbits // 64
+    base = g.integers(0, 2**64, size=(B, H, 1, W), dtype=np.uint64)
+    codes = np.repeat(base, N, axis=2)
+    for b in range(B):
+        for h in range(H):
+            for n in range(N):
+                for bit in g.choice(nbits, size=int(g.integers(0, max_flips + 1)), replace=False):
+                    codes[b, h, n, bit // 64] ^= np.uint64(1) << np.uint64(bit % 64)
+    return codes
+
+
+@pytest.mark.parametrize("variant", [0, 1], ids=["popcount", "matrix-core"])
+@pytest.mark.parametrize("B,H,Nq,Nk,nbits,dv,scale,near", [
+    (2, 3, 70, 100, 128, 128, None, False),     # one ragged key chunk, c4 code width
+    (1, 2, 40, 200, 64, 128, None, False),      # two key chunks, ragged tail (two passes over the keys)
+    (1, 2, 300, 128, 128, 128, None, False),    # two query chunks
+    (1, 1, 33, 60, 256, 64, None, False),       # 256-bit codes
+    (1, 2, 50, 90, 128, 128, 3.0, True),        # sharp softmax: the row-reference path
+    (1, 2, 50, 150, 128, 128, -0.2, True),      # negative scale: the row-reference path, two key chunks
+])
+def test_scores_inside_the_attention_kernels_are_the_hamming_similarities(sa, variant, B, H, Nq, Nk, nbits, dv, scale, near):
+    """S[i,j] = nbits - 2 popcount(q_i xor k_j) as the kernels use it: with unit-vector value rows the output IS the
+    softmax weights, so S[i,j] - S[i,0] = ln(w[i,j] / w[i,0]) / scale must round to the oracle's integer."""
+    if near:
+        qc, kc = near_codes(1, (B, H, Nq), nbits, 4), near_codes(1, (B, H, Nk), nbits, 4)
+    else:
+        qc, kc = wl.random_codes(31, (B, H, Nq), nbits), wl.random_codes(32, (B, H, Nk), nbits)
+    if scale is None:
+        scale = float(np.float32(1.0 / math.sqrt(nbits)))
+    s_ref = oracle.hamming_scores(qc, kc, nbits).astype(np.int64)                  # [B,H,Nq,Nk]
+    w = np.zeros((B, H, Nq, Nk))
+    for first in range(0, Nk, dv):
+        v = one_hot_values(B, Nk, H, dv, first)
+        o, _, _ = sa.sa_hamming_attention_fused(dev(qc), dev(kc), dev(v), scale, nbits, 1.0, want_xq=False, want_xh=False,
+                                                variant=variant)
+        n = min(dv, Nk - first)
+        w[:, :, :, first:first + n] = host(o).astype(np.float64).transpose(0, 2, 1, 3)[..., :n]
+    assert np.allclose(w.sum(axis=-1), 1.0, rtol=0, atol=2e-5)
+    assert w.min() > 1e-30, "a softmax weight underflowed: the case is not decisive"
+    s32 = np.float64(np.float32(scale))
+    diff = np.log(w / w[..., :1]) / s32
+    want = s_ref - s_ref[..., :1]
+    assert np.abs(diff - want).max() < 0.05, "largest deviation from an integer score difference: %g" % np.abs(diff - want).max()
+    assert np.array_equal(np.rint(diff).astype(np.int64), want)
