@@ -229,6 +229,7 @@ int sa_shift_linear_qkv_codes(const int8_t *x, const uint8_t *wqkv, int B, int N
  *   expert_of [T] chosen expert per token
  *   counts [E]    tokens per expert (device memory, like the others)
  *   gate [T]      softmax probability of the chosen expert, fp32
+ * Up to 32768 tokens the call is one launch and needs no workspace (the query returns 0).
  */
 size_t sa_moe_dispatch_workspace_bytes(long T, int E);
 int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,

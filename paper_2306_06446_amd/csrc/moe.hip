@@ -2,11 +2,15 @@
 // the Shift expert (Sec. 4.2: p = softmax(router logits), G(x) = p_i * 1{p_i >= p_j}).
 //
 // Dispatch is a stable partition of the token ids by expert, built without atomics so
-// that the lists are unique and reproducible: (1) every workgroup of 256 tokens takes
-// the decisions (raw-logit argmax, ties to the lowest index), the gate values and its
-// per-expert histogram; (2) one small workgroup turns the histograms into start offsets (for up
-// to 131072 tokens every workgroup of step 3 sums the few histograms itself instead, which saves
-// a launch); (3) every workgroup ranks its tokens with wavefront ballots / popcounts and writes them.
+// that the lists are unique and reproducible.  Up to 32768 tokens it is ONE launch: every
+// workgroup of 1024 tokens takes the decisions of ALL tokens from the logits (raw-logit argmax,
+// ties to the lowest index; the logits of 12608 tokens are 100 KB, read from the L2), which
+// gives it the totals per expert and the counts of the workgroups before it, then ranks its own
+// tokens with wavefront ballots / popcounts and writes them.  Longer inputs take three steps
+// through a scratch buffer: (1) decisions, gate values and a per-expert histogram per workgroup;
+// (2) one small workgroup turns the histograms into start offsets (up to 131072 tokens every
+// workgroup of step 3 sums the few histograms itself instead, which saves that launch);
+// (3) ranking and writing as above.
 #include "common.h"
 
 namespace {
@@ -15,6 +19,7 @@ using namespace sa;
 constexpr int kMaxE = 8;
 constexpr int kTok = 256;   // tokens per workgroup
 constexpr long kSelfScanBlocks = 512;   // up to this many workgroups (131072 tokens) the scatter pass sums the histograms itself
+constexpr long kOneLaunchTokens = 32768; // up to this many tokens one launch does everything (every workgroup reads all logits)
 
 __device__ inline uint64_t lanemask_lt(int lane) { return (lane == 0) ? 0ull : (~0ull >> (64 - lane)); }
 
@@ -48,6 +53,121 @@ __global__ __launch_bounds__(kTok) void route_kernel(const float *__restrict__ l
         int s = 0;
         for (int w = 0; w < kTok / 64; ++w) s += wave_cnt[w][threadIdx.x];
         block_counts[(size_t)blockIdx.x * E + threadIdx.x] = s;
+    }
+}
+
+// The index of the largest logit of token t (the first one among equals).
+__device__ inline int top1(const float *__restrict__ l, int E) {
+    int best = 0;
+    float lb = l[0];
+    for (int e = 1; e < E; ++e) {
+        const float le = l[e];
+        if (le > lb) { lb = le; best = e; }
+    }
+    return best;
+}
+
+// One launch for the whole dispatch: workgroup b owns tokens [1024 b, 1024 b + 1024).  Pass 1 over all T tokens
+// (thread i takes tokens i, i + 1024, ...; the loads of a thread are independent and issued together): per expert, how
+// many tokens it gets in all and how many of them lie in workgroups before b.  Pass 2: the workgroup's own tokens,
+// ranked by ballot / popcount behind those counts.
+constexpr int kOneTok = 1024;            // tokens (and threads) per workgroup of the one-launch kernel
+
+template <int E_FIXED>
+__global__ __launch_bounds__(kOneTok) void route_scatter_kernel(const float *__restrict__ logits, long T, int E_runtime,
+                                                                int32_t *__restrict__ expert_of, float *__restrict__ gate,
+                                                                int32_t *__restrict__ counts, int32_t *__restrict__ perm) {
+    const int E = E_FIXED > 0 ? E_FIXED : E_runtime;
+    constexpr int kWaves = kOneTok / 64;
+    __shared__ int32_t wave_cnt[kWaves][kMaxE];
+    __shared__ int32_t red[kWaves][2 * kMaxE];
+    __shared__ int32_t base_s[kMaxE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long first = (long)blockIdx.x * kOneTok;              // tokens before `first` belong to earlier workgroups
+    int below[kMaxE], all[kMaxE];
+#pragma unroll
+    for (int e = 0; e < kMaxE; ++e) below[e] = all[e] = 0;
+    if (E_FIXED == 2) {
+        const float2 *l2 = reinterpret_cast<const float2 *>(logits);
+        constexpr int kBatch = 8;                               // independent loads in flight per thread
+        for (long t0 = tid; t0 < T; t0 += (long)kBatch * kOneTok) {
+            float2 l[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const long t = t0 + (long)i * kOneTok;
+                l[i] = t < T ? l2[t] : make_float2(0.0f, 0.0f);
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const long t = t0 + (long)i * kOneTok;
+                const int one = (t < T && l[i].y > l[i].x) ? 1 : 0;     // expert 1 only if strictly larger
+                all[1] += one;
+                below[1] += t < first ? one : 0;
+            }
+        }
+        const int mine_all = T > tid ? (int)((T - tid + kOneTok - 1) / kOneTok) : 0;    // tokens this thread looked at
+        const long fb = first - tid;
+        const int mine_below = fb > 0 ? (int)((fb + kOneTok - 1) / kOneTok) : 0;          // ... and those before `first`
+        all[0] = mine_all - all[1];
+        below[0] = mine_below - below[1];
+    } else {
+        for (long t = tid; t < T; t += kOneTok) {
+            const int best = top1(logits + (size_t)t * E, E);
+#pragma unroll
+            for (int e = 0; e < kMaxE; ++e) {
+                all[e] += best == e ? 1 : 0;
+                below[e] += (best == e && t < first) ? 1 : 0;
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < kMaxE; ++e) {
+        if (e >= E) continue;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            below[e] += __shfl_xor(below[e], off, 64);
+            all[e] += __shfl_xor(all[e], off, 64);
+        }
+        if (lane == 0) { red[wave][e] = below[e]; red[wave][kMaxE + e] = all[e]; }
+    }
+    __syncthreads();
+    if (tid < E) {
+        int bl = 0, al = 0;
+        for (int w = 0; w < kWaves; ++w) { bl += red[w][tid]; al += red[w][kMaxE + tid]; }
+        red[0][tid] = bl;                       // (row 0 of red has been read by this thread only)
+        red[0][kMaxE + tid] = al;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int start = 0;
+        for (int e = 0; e < E; ++e) {
+            base_s[e] = start + red[0][e];
+            if (blockIdx.x == 0) counts[e] = red[0][kMaxE + e];
+            start += red[0][kMaxE + e];
+        }
+    }
+    const long t = first + tid;
+    int mine = -1;
+    if (t < T) {
+        const float *l = logits + (size_t)t * E;
+        mine = top1(l, E);
+        const float lb = l[mine];
+        float den = 0.0f;
+        for (int e = 0; e < E; ++e) den += __expf(l[e] - lb);
+        expert_of[t] = mine;
+        gate[t] = 1.0f / den;
+    }
+    int rank = 0;
+    for (int e = 0; e < E; ++e) {
+        const uint64_t m = __ballot(mine == e);
+        if (mine == e) rank = __builtin_popcountll(m & lanemask_lt(lane));
+        if (lane == 0) wave_cnt[wave][e] = __builtin_popcountll(m);
+    }
+    __syncthreads();
+    if (mine >= 0) {
+        int before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_cnt[w][mine];
+        perm[base_s[mine] + before + rank] = (int32_t)t;
     }
 }
 
@@ -254,33 +374,27 @@ __global__ __launch_bounds__(64) void balance_final_kernel(const float *__restri
     }
 }
 
-}  // namespace
-
-extern "C" size_t sa_moe_dispatch_workspace_bytes(long T, int E) {
-    if (T <= 0 || E <= 0) return 0;
+// Scratch of the three-step path: per-workgroup histograms, then their exclusive scan (none up to kOneLaunchTokens).
+size_t dispatch_scratch_bytes(long T, int E) {
+    if (T <= kOneLaunchTokens || E <= 0) return 0;
     const size_t n_blocks = (size_t)((T + kTok - 1) / kTok);
     return (2 * n_blocks * E * sizeof(int32_t) + 255) / 256 * 256;
 }
 
-extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
-                               int32_t *counts, float *gate, void *workspace, size_t workspace_bytes,
-                               void *stream) {
-    sa::clear_error();
-    SA_REQUIRE(T >= 0, SA_ERR_INVALID, "sa_moe_dispatch: T < 0");
-    SA_REQUIRE(E >= 2 && E <= kMaxE, SA_ERR_SHAPE, "sa_moe_dispatch: E must be in [2, %d] (got %d)", kMaxE, E);
-    SA_REQUIRE(T < (1L << 31), SA_ERR_SHAPE, "sa_moe_dispatch: T >= 2^31");
-    SA_REQUIRE(counts != nullptr, SA_ERR_INVALID, "sa_moe_dispatch: counts is NULL");
-    SA_REQUIRE(sa::aligned16(logits) && sa::aligned16(perm) && sa::aligned16(expert_of) &&
-                   sa::aligned16(counts) && sa::aligned16(gate) && sa::aligned16(workspace),
-               SA_ERR_ALIGN, "sa_moe_dispatch: pointers must be 16-byte aligned");
-    hipStream_t st = sa::as_stream(stream);
-    if (T == 0) return sa::launch_zero(counts, ((size_t)E * 4 + 3) / 4 * 4, st);
-    SA_REQUIRE(logits && perm && expert_of && gate, SA_ERR_INVALID, "sa_moe_dispatch: NULL buffer");
-    const size_t need = sa_moe_dispatch_workspace_bytes(T, E);
-    SA_REQUIRE(workspace != nullptr && workspace_bytes >= need, SA_ERR_WORKSPACE,
-               "sa_moe_dispatch: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+// Everything of sa_moe_dispatch after the checks that both entry points share; `scratch` holds
+// dispatch_scratch_bytes(T, E) bytes (not read before it is written; may be null when that is 0).
+int dispatch_launch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of, int32_t *counts, float *gate,
+                    void *scratch, hipStream_t st) {
+    if (T <= kOneLaunchTokens) {
+        const unsigned blocks = (unsigned)((T + kOneTok - 1) / kOneTok);
+        if (E == 2)
+            route_scatter_kernel<2><<<dim3(blocks), dim3(kOneTok), 0, st>>>(logits, T, E, expert_of, gate, counts, perm);
+        else
+            route_scatter_kernel<0><<<dim3(blocks), dim3(kOneTok), 0, st>>>(logits, T, E, expert_of, gate, counts, perm);
+        return sa::check_launch("sa_moe_dispatch(one launch)");
+    }
     const long n_blocks = (T + kTok - 1) / kTok;
-    int32_t *block_counts = static_cast<int32_t *>(workspace);
+    int32_t *block_counts = static_cast<int32_t *>(scratch);
     int32_t *block_base = block_counts + (size_t)n_blocks * E;
     route_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(logits, T, E, expert_of, gate, block_counts);
     int rc = sa::check_launch("sa_moe_dispatch(route)");
@@ -294,6 +408,39 @@ extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm
     if (rc != SA_OK) return rc;
     scatter_kernel<<<dim3((unsigned)n_blocks), dim3(kTok), 0, st>>>(expert_of, T, E, block_base, block_counts, counts, perm);
     return sa::check_launch("sa_moe_dispatch(scatter)");
+}
+
+// Argument checks of both dispatch entry points (everything but the scratch memory).
+int dispatch_check(const char *who, const float *logits, long T, int E, int32_t *perm, int32_t *expert_of, int32_t *counts,
+                   float *gate) {
+    SA_REQUIRE(T >= 0, SA_ERR_INVALID, "%s: T < 0", who);
+    SA_REQUIRE(E >= 2 && E <= kMaxE, SA_ERR_SHAPE, "%s: E must be in [2, %d] (got %d)", who, kMaxE, E);
+    SA_REQUIRE(T < (1L << 31), SA_ERR_SHAPE, "%s: T >= 2^31", who);
+    SA_REQUIRE(counts != nullptr, SA_ERR_INVALID, "%s: counts is NULL", who);
+    SA_REQUIRE(sa::aligned16(logits) && sa::aligned16(perm) && sa::aligned16(expert_of) && sa::aligned16(counts) &&
+                   sa::aligned16(gate),
+               SA_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+    SA_REQUIRE(T == 0 || (logits && perm && expert_of && gate), SA_ERR_INVALID, "%s: NULL buffer", who);
+    return SA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t sa_moe_dispatch_workspace_bytes(long T, int E) { return dispatch_scratch_bytes(T, E); }
+
+extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
+                               int32_t *counts, float *gate, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+    sa::clear_error();
+    int rc = dispatch_check("sa_moe_dispatch", logits, T, E, perm, expert_of, counts, gate);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(sa::aligned16(workspace), SA_ERR_ALIGN, "sa_moe_dispatch: the workspace must be 16-byte aligned");
+    hipStream_t st = sa::as_stream(stream);
+    if (T == 0) return sa::launch_zero(counts, ((size_t)E * 4 + 3) / 4 * 4, st);
+    const size_t need = dispatch_scratch_bytes(T, E);
+    SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
+               "sa_moe_dispatch: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    return dispatch_launch(logits, T, E, perm, expert_of, counts, gate, workspace, st);
 }
 
 extern "C" int sa_gather_rows(const void *src, size_t row_bytes, const sa_rows *rows, void *dst, void *stream) {

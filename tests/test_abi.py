@@ -91,6 +91,11 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     # dispatch: E out of range, missing workspace
     T = ctypes.c_long(100)
     assert lib.sa_moe_dispatch(fake, T, 1, fake, fake, fake, fake, null, ctypes.c_size_t(0), null) == -2
+    # (up to 32768 tokens the dispatch is one launch without scratch; longer inputs need the workspace)
+    lib.sa_moe_dispatch_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.sa_moe_dispatch_workspace_bytes(T, 2) == 0
+    T = ctypes.c_long(100000)
+    assert lib.sa_moe_dispatch_workspace_bytes(T, 2) >= 2 * 391 * 2 * 4
     assert lib.sa_moe_dispatch(fake, T, 2, fake, fake, fake, fake, null, ctypes.c_size_t(0), null) == -4
     # block: NULL descriptor
     lib.sa_block_workspace_bytes.restype = ctypes.c_size_t

@@ -352,6 +352,7 @@ def test_requant_lut_bit_exact(sa):
 
 @pytest.mark.parametrize("T,E,tie_every", [(197, 2, 0), (12608, 2, 0), (1000, 2, 7), (3001, 4, 5),
                                            (1, 2, 0), (256, 2, 1), (1023, 8, 3), (1025, 3, 0),
+                                           (32768, 2, 3), (32769, 2, 0), (40000, 4, 9),        # either side of the one-launch limit
                                            (131072, 2, 11), (131073, 2, 0), (200001, 8, 5)])   # the last two: the separate scan kernel
 def test_moe_dispatch_bit_exact(sa, T, E, tie_every):
     g = np.random.default_rng([31, T, E])
