@@ -235,6 +235,19 @@ size_t sa_moe_dispatch_workspace_bytes(long T, int E);
 int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
                     int32_t *counts, float *gate, void *workspace, size_t workspace_bytes,
                     void *stream);
+/*
+ * sa_moe_dispatch for callers that cannot allocate device memory and so have no workspace
+ * to pass: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and kernels; the scratch of the long-input path is an
+ * array built into the library (256 KiB per GPU, held until the process ends) instead of
+ * a workspace.  The call allocates nothing.  T <= sa_moe_dispatch_static_max_tokens()
+ * (1048576), SA_ERR_UNSUPPORTED beyond.  All calls on one GPU share that array: two calls
+ * that overlap in time on the same GPU (different streams) race; calls on one stream, or
+ * on different GPUs, do not.
+ */
+long sa_moe_dispatch_static_max_tokens(void);
+int sa_moe_dispatch_static(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
+                           int32_t *counts, float *gate, void *stream);
 
 /*
  * Forward value of the latency-aware load-balancing loss (Eq. 4):

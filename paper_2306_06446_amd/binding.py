@@ -24,7 +24,8 @@ EXPORTS = [
     "sa_hamming_attention", "sa_hamming_attention_fused", "sa_shift_planes_bytes", "sa_shift_planes_prepare",
     "sa_shift_linear_workspace_bytes", "sa_shift_linear", "sa_shift_linear_f32", "sa_layernorm_quant",
     "sa_shift_weights_from_float", "sa_shift_linear_qkv_codes",
-    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_moe_balance_loss_workspace_bytes", "sa_moe_balance_loss", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
+    "sa_moe_dispatch_workspace_bytes", "sa_moe_dispatch", "sa_moe_dispatch_static_max_tokens", "sa_moe_dispatch_static",
+    "sa_moe_balance_loss_workspace_bytes", "sa_moe_balance_loss", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
     "sa_block_forward", "sa_layer_workspace_bytes", "sa_layer_forward",
@@ -76,6 +77,7 @@ def load_library():
                 "g.build()'` first; there is no fallback path" % LIB_PATH)
         lib = ctypes.CDLL(LIB_PATH)
         lib.sa_last_error.restype = ctypes.c_char_p
+        lib.sa_moe_dispatch_static_max_tokens.restype = ctypes.c_long
         for name in ("sa_moe_balance_loss_workspace_bytes", "sa_additive_attention_workspace_bytes", "sa_linear_attention_01_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
                      "sa_shift_linear_workspace_bytes", "sa_shift_planes_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
@@ -343,6 +345,21 @@ def sa_moe_dispatch(logits, out=None, workspace=None):
         ws = _workspace(lib.sa_moe_dispatch_workspace_bytes(_l(T), E), dev)
     _check(lib.sa_moe_dispatch(_ptr(logits), _l(T), E, _ptr(perm), _ptr(expert_of), _ptr(counts),
                                _ptr(gate), _ptr(ws), _z(ws.numel()), _stream()))
+    return perm, expert_of, counts, gate
+
+
+def sa_moe_dispatch_static(logits, out=None):
+    """sa_moe_dispatch without a workspace: the library's built-in scratch array is used (nothing is allocated by the call;
+    the four output tensors are the caller's, made here only when `out` is not given)."""
+    lib = load_library()
+    T, E = logits.shape
+    dev = logits.device
+    if out is None:
+        out = (torch.empty(T, dtype=torch.int32, device=dev), torch.empty(T, dtype=torch.int32, device=dev),
+               torch.empty(max(E, 4), dtype=torch.int32, device=dev)[:E], torch.empty(T, dtype=torch.float32, device=dev))
+    perm, expert_of, counts, gate = out
+    _check(lib.sa_moe_dispatch_static(_ptr(logits), _l(T), E, _ptr(perm), _ptr(expert_of), _ptr(counts), _ptr(gate),
+                                      _stream()))
     return perm, expert_of, counts, gate
 
 

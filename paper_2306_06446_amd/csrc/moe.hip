@@ -11,6 +11,8 @@
 // (2) one small workgroup turns the histograms into start offsets (up to 131072 tokens every
 // workgroup of step 3 sums the few histograms itself instead, which saves that launch);
 // (3) ranking and writing as above.
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -441,6 +443,60 @@ extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm
     SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
                "sa_moe_dispatch: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     return dispatch_launch(logits, T, E, perm, expert_of, counts, gate, workspace, st);
+}
+
+// ---- the dispatch for callers that cannot allocate -------------------------------------------------
+// Its scratch (the histograms and their scan of the three-step path) is this array instead of a workspace:
+// 2 * 4096 workgroups * 8 experts * 4 bytes = 256 KiB, enough for kStaticTokens tokens.  Every GPU the library
+// runs on holds its own copy at its own address until the process ends; in host code the name `scratch` is only
+// a handle for hipGetSymbolAddress, the kernels get the address that call returns for the current device.
+constexpr long kStaticTokens = 1L << 20;
+static __device__ __align__(256) int32_t scratch[2 * (kStaticTokens / 256) * 8];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, asked for once per device
+
+int static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return sa::fail(SA_ERR_HIP, "sa_moe_dispatch_static: hipGetDevice: %s", hipGetErrorString(e));
+    SA_REQUIRE(dev >= 0 && dev < kMaxDevices, SA_ERR_UNSUPPORTED, "sa_moe_dispatch_static: device %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr)
+            return sa::fail(SA_ERR_HIP, "sa_moe_dispatch_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SA_OK;
+}
+
+}  // namespace
+
+extern "C" long sa_moe_dispatch_static_max_tokens(void) { return kStaticTokens; }
+
+extern "C" int sa_moe_dispatch_static(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
+                                      int32_t *counts, float *gate, void *stream) {
+    sa::clear_error();
+    int rc = dispatch_check("sa_moe_dispatch_static", logits, T, E, perm, expert_of, counts, gate);
+    if (rc != SA_OK) return rc;
+    SA_REQUIRE(T <= kStaticTokens, SA_ERR_UNSUPPORTED,
+               "sa_moe_dispatch_static: %ld tokens exceed the %ld the built-in scratch holds; use sa_moe_dispatch with a workspace",
+               T, kStaticTokens);
+    static_assert(sizeof(scratch) >= 2 * ((kStaticTokens + kTok - 1) / kTok) * kMaxE * sizeof(int32_t), "scratch too small");
+    hipStream_t st = sa::as_stream(stream);
+    if (T == 0) return sa::launch_zero(counts, ((size_t)E * 4 + 3) / 4 * 4, st);
+    void *ws = nullptr;
+    if (dispatch_scratch_bytes(T, E) != 0) {
+        rc = static_scratch(&ws);
+        if (rc != SA_OK) return rc;
+    }
+    return dispatch_launch(logits, T, E, perm, expert_of, counts, gate, ws, st);
 }
 
 extern "C" int sa_gather_rows(const void *src, size_t row_bytes, const sa_rows *rows, void *dst, void *stream) {
