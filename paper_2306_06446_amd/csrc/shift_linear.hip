@@ -161,6 +161,26 @@ __global__ __launch_bounds__(256) void decode_w4_kernel(const uint4 *__restrict_
     plane_b[2 * i + 1] = make_uint4(ob[4], ob[5], ob[6], ob[7]);
 }
 
+// The same for the two weight matrices of an MLP in one launch (threads past the first matrix's chunks take the second's).
+__global__ __launch_bounds__(256) void decode_w4_pair_kernel(const uint4 *__restrict__ w4_0, long n0, uint4 *__restrict__ a0,
+                                                             uint4 *__restrict__ b0, const uint4 *__restrict__ w4_1, long n1,
+                                                             uint4 *__restrict__ a1, uint4 *__restrict__ b1) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool second = i >= n0;
+    if (second) i -= n0;
+    if (second && i >= n1) return;
+    const uint4 wv = second ? w4_1[i] : w4_0[i];
+    const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
+    uint32_t oa[8], ob[8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) decode8(wd[q], oa + 2 * q, ob + 2 * q);
+    uint4 *pa = second ? a1 : a0, *pb = second ? b1 : b0;
+    pa[2 * i] = make_uint4(oa[0], oa[1], oa[2], oa[3]);
+    pa[2 * i + 1] = make_uint4(oa[4], oa[5], oa[6], oa[7]);
+    pb[2 * i] = make_uint4(ob[0], ob[1], ob[2], ob[3]);
+    pb[2 * i + 1] = make_uint4(ob[4], ob[5], ob[6], ob[7]);
+}
+
 inline Epilogue with_finite_scale(Epilogue e) {
     e.rq = requant_scale_finite(e.rq);
     return e;
@@ -220,11 +240,24 @@ int decode_planes(const uint8_t *w4, int K, int N, void *planes, hipStream_t st)
     return check_launch("shift layer (weight decode)");
 }
 
+// Both weight matrices of an MLP ([N0, K0] and [N1, K1]) to their planes in one launch.
+int decode_planes_pair(const uint8_t *w4_0, int K0, int N0, void *planes0, const uint8_t *w4_1, int K1, int N1, void *planes1,
+                       hipStream_t st) {
+    int8_t *a0 = static_cast<int8_t *>(planes0), *b0 = a0 + (size_t)N0 * K0;
+    int8_t *a1 = static_cast<int8_t *>(planes1), *b1 = a1 + (size_t)N1 * K1;
+    const long n0 = (long)N0 * K0 / 32, n1 = (long)N1 * K1 / 32;
+    decode_w4_pair_kernel<<<dim3((unsigned)((n0 + n1 + 255) / 256)), dim3(256), 0, st>>>(
+        reinterpret_cast<const uint4 *>(w4_0), n0, reinterpret_cast<uint4 *>(a0), reinterpret_cast<uint4 *>(b0),
+        reinterpret_cast<const uint4 *>(w4_1), n1, reinterpret_cast<uint4 *>(a1), reinterpret_cast<uint4 *>(b1));
+    return check_launch("shift layers (weight decode)");
+}
+
 // planes: workspace of planes_bytes(K, N) for the MFMA variant (unused by the VALU and the
 // prepared variant; for the latter w4 already points at decoded planes).
+// decoded: the planes of w4 are already in `planes` (decoded earlier in this call).
 template <int MODE>
 int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &sel, bool gather, int K,
-                 int N, const Epilogue &epi, void *planes, hipStream_t st) {
+                 int N, const Epilogue &epi, void *planes, hipStream_t st, bool decoded = false) {
     if (sel.max_rows == 0 || N == 0) return SA_OK;
     if (variant == SA_VARIANT_AUTO) variant = (K % kMfmaK == 0) ? SA_VARIANT_MFMA : SA_VARIANT_VALU;
     if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED) {
@@ -233,8 +266,10 @@ int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &
         if (variant == SA_VARIANT_MFMA_PREPARED) {
             pa = reinterpret_cast<const int8_t *>(w4);      // the caller decoded the weights beforehand
         } else {
-            int rc = decode_planes(w4, K, N, planes, st);
-            if (rc != SA_OK) return rc;
+            if (!decoded) {
+                int rc = decode_planes(w4, K, N, planes, st);
+                if (rc != SA_OK) return rc;
+            }
             pa = static_cast<const int8_t *>(planes);
         }
         pb = pa + (size_t)N * K;
@@ -535,12 +570,19 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     uint8_t *planes1 = static_cast<uint8_t *>(workspace) + (((size_t)sel.max_rows * hid) + 255) / 256 * 256;
     uint8_t *planes2 = planes1 + planes_bytes(E, hid);
 
+    // both layers in this call on the matrix cores: their 4-bit weights are decoded by one launch
+    const int v_eff = variant == SA_VARIANT_AUTO ? SA_VARIANT_MFMA : variant;      // E and hid are multiples of 64
+    const bool pair = v_eff == SA_VARIANT_MFMA && (stages & 3) == 3;
+    if (pair) {
+        rc = decode_planes_pair(w1, E, hid, planes1, w2, hid, E, planes2, st);
+        if (rc != SA_OK) return rc;
+    }
     if (stages & 1) {
         sa::Epilogue e1;
         e1.h = hbuf;
         e1.rq = requant_scale;
         e1.lut = lut;
-        rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, planes1, st);
+        rc = launch_shift<sa::kEpiRequantLut>(variant, xq, w1, sel, true, E, hid, e1, planes1, st, pair);
         if (rc != SA_OK) return rc;
     }
     if (!(stages & 2)) return SA_OK;
@@ -548,7 +590,7 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
     if (y2_or_null) {
         sa::Epilogue e2;
         e2.y = y2_or_null;
-        rc = launch_shift<sa::kEpiInt32>(variant, hbuf, w2, sel, false, hid, E, e2, planes2, st);
+        rc = launch_shift<sa::kEpiInt32>(variant, hbuf, w2, sel, false, hid, E, e2, planes2, st, pair);
         if (rc != SA_OK) return rc;
     }
     if (y_or_null) {
@@ -557,7 +599,7 @@ extern "C" int sa_shift_mlp(const int8_t *xq, const sa_rows *rows, int E, int hi
         e3.gate = gate_or_null;
         e3.out_scale = out_scale;
         e3.accumulate = (stages & SA_MLP_ACCUMULATE) != 0;
-        rc = launch_shift<sa::kEpiScatterI32>(variant, hbuf, w2, sel, false, hid, E, e3, planes2, st);
+        rc = launch_shift<sa::kEpiScatterI32>(variant, hbuf, w2, sel, false, hid, E, e3, planes2, st, pair || y2_or_null != nullptr);
         if (rc != SA_OK) return rc;
     }
     return SA_OK;
