@@ -579,14 +579,17 @@ def bench_sweep(args, sa, wl, torch, np):
                 e = g.integers(0, 8, size=(N, K), dtype=np.uint8)
                 w4 = torch.from_numpy(wl.pack_w4(neg, e)).cuda()
                 y32 = torch.empty((M, N), dtype=torch.int32, device="cuda")
-                variants = {"valu": 0}
+                # vector-ALU shift-and-accumulate; matrix cores with the 4-bit weights decoded in every call (two launches);
+                # matrix cores on planes decoded once beforehand (the matrix-core variants need K % 64 == 0)
+                variants = {"valu": (0, w4)}
                 if K % 64 == 0:
-                    variants["mfma"] = 1
+                    variants["mfma"] = (1, w4)
+                    variants["mfma_prepared"] = (3, sa.sa_shift_planes_prepare(w4))
                 t = {}
-                for vn, vid in variants.items():
+                for vn, (vid, wv) in variants.items():
                     wsl = torch.empty(max(16, lib.sa_shift_linear_workspace_bytes(sa._l(M), K, N, vid)), dtype=torch.uint8, device="cuda")
-                    t[vn] = _time_us_graph(torch, lambda: sa.sa_shift_linear(x8, w4, variant=vid, y=y32, workspace=wsl),
-                                           reps=20 if vn == "mfma" else 5)
+                    t[vn] = _time_us_graph(torch, lambda: sa.sa_shift_linear(x8, wv, variant=vid, y=y32, workspace=wsl),
+                                           reps=5 if vn == "valu" else 20)
                 xf = x8.float()
                 wf = torch.from_numpy((np.where(neg == 1, -1.0, 1.0) * np.exp2(e.astype(np.float64))).astype(np.float32)).cuda().t().contiguous()
                 yf = torch.empty((M, N), device="cuda")

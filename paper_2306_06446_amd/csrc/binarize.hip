@@ -75,6 +75,12 @@ extern "C" int sa_binarize_pair(const float *q, const float *k, int B, int N, in
                                 int nbits, uint64_t *q_codes, uint64_t *k_codes, void *stream) {
     sa::clear_error();
     const long rows = (long)B * N * H;
+    // both tensors are checked before anything is launched for either
+    if (rows > 0) {
+        SA_REQUIRE(q && k && q_codes && k_codes, SA_ERR_INVALID, "sa_binarize_pair: NULL buffer");
+        SA_REQUIRE(sa::aligned16(q) && sa::aligned16(k) && sa::aligned16(q_codes) && sa::aligned16(k_codes), SA_ERR_ALIGN,
+                   "sa_binarize_pair: pointers must be 16-byte aligned");
+    }
     // one launch when the matrix-core kernel takes the shape; otherwise simply one call per tensor
     if (proj != nullptr && B > 0 && N > 0 && H > 0 && rows < (1L << 31) && sa::binarize_mfma_supported(d, nbits) &&
         nbits <= 4096 && q && k && q_codes && k_codes && sa::aligned16(q) && sa::aligned16(k) && sa::aligned16(proj) &&

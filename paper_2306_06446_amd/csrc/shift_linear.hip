@@ -286,8 +286,10 @@ int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &
     }
     const long gy = (sel.max_rows + kValuRows - 1) / kValuRows;
     SA_REQUIRE(gy < 65536, SA_ERR_SHAPE, "shift layer: too many rows for one launch");
-    const dim3 grid((N + 255) / 256, (unsigned)gy);
-    shift_valu_kernel<MODE><<<grid, dim3(256), 0, st>>>(x, w4, sel, gather, K, N, epi);
+    // narrow layers: a workgroup no wider than the columns need (whole wavefronts), so that lanes are not idle
+    const int threads = N >= 256 ? 256 : (N + 63) / 64 * 64;
+    const dim3 grid((N + threads - 1) / threads, (unsigned)gy);
+    shift_valu_kernel<MODE><<<grid, dim3(threads), 0, st>>>(x, w4, sel, gather, K, N, epi);
     return check_launch("shift layer (VALU)");
 }
 
