@@ -65,6 +65,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="kernel sweep over pyramid-ViT stage shapes at batch 1 and 32: the Add kernels (K^T V, Q(K^T V)) and "
                          "the Shift linear layers, each beside a dense fp32 library GEMM of the same contraction")
+    ap.add_argument("--cu-split", type=float, default=0.0,
+                    help="with --experts: also run the two experts side by side on two streams that each own a share of the "
+                         "compute units (this fraction to the Mult expert, the rest to the Shift expert; HIP stream CU masks)")
     ap.add_argument("--experts", action="store_true",
                     help="the two experts of the MoE MLP one after the other on one stream and side by side on two, with the "
                          "paper's modularized figure (slower expert alone) beside the wall-clock ones")
@@ -513,7 +516,35 @@ def bench_experts(args, sa, wl, torch, np, cfg):
         torch.cuda.synchronize()
     us = {"mult_alone": _time_us(torch, mult, args.steps), "shift_alone": _time_us(torch, shift, args.steps),
           "sequential": _time_us(torch, sequential, args.steps), "concurrent": _time_us(torch, concurrent, args.steps)}
-    us = {k: round(v, 2) for k, v in us.items()}
+    if args.cu_split > 0.0:
+        # the chip partitioned between the experts: each stream may only use its own compute units
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        n_m = max(1, min(n_cu - 1, int(round(args.cu_split * n_cu))))
+        words = (n_cu + 31) // 32
+
+        def masked_stream(lo, hi):
+            mask = (ctypes.c_uint32 * words)()
+            for cu in range(lo, hi):
+                mask[cu // 32] |= 1 << (cu % 32)
+            handle = ctypes.c_void_p()
+            rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(handle), ctypes.c_uint32(words), mask)
+            assert rc == 0 and handle.value, "hipExtStreamCreateWithCUMask failed: %d" % rc
+            return torch.cuda.ExternalStream(handle.value)
+
+        s_m, s_s = masked_stream(0, n_m), masked_stream(n_m, n_cu)
+        y.zero_()
+        concurrent()
+        torch.cuda.synchronize()
+        same = same and bool(torch.equal(y, y_seq))
+        with torch.cuda.stream(s_m):
+            us["mult_alone_on_its_cus"] = _time_us(torch, mult, args.steps)
+        with torch.cuda.stream(s_s):
+            us["shift_alone_on_its_cus"] = _time_us(torch, shift, args.steps)
+        us["concurrent_cu_split"] = _time_us(torch, concurrent, args.steps)
+        us["cu_split"] = {"mult_cus": n_m, "shift_cus": n_cu - n_m}
+    us = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in us.items()}
     out = {"metric": "MoE MLP tokens/s (Mult and Shift expert after the dispatch) at 1 GPU",
            "value": round(T / (us["sequential"] * 1e-6), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": 3,
            "ms_per_step": round(us["sequential"] * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,

@@ -89,9 +89,10 @@ __global__ __launch_bounds__(kOneTok) void route_scatter_kernel(const float *__r
     int below[kMaxE], all[kMaxE];
 #pragma unroll
     for (int e = 0; e < kMaxE; ++e) below[e] = all[e] = 0;
+    float2 own = make_float2(0.0f, 0.0f);                       // E == 2: the logits of this thread's own token, met in pass 1
     if (E_FIXED == 2) {
         const float2 *l2 = reinterpret_cast<const float2 *>(logits);
-        constexpr int kBatch = 8;                               // independent loads in flight per thread
+        constexpr int kBatch = 16;                              // independent loads in flight per thread: 16384 tokens per round trip
         for (long t0 = tid; t0 < T; t0 += (long)kBatch * kOneTok) {
             float2 l[kBatch];
 #pragma unroll
@@ -105,6 +106,7 @@ __global__ __launch_bounds__(kOneTok) void route_scatter_kernel(const float *__r
                 const int one = (t < T && l[i].y > l[i].x) ? 1 : 0;     // expert 1 only if strictly larger
                 all[1] += one;
                 below[1] += t < first ? one : 0;
+                if (t == first + tid) own = l[i];
             }
         }
         const int mine_all = T > tid ? (int)((T - tid + kOneTok - 1) / kOneTok) : 0;    // tokens this thread looked at
@@ -151,13 +153,21 @@ __global__ __launch_bounds__(kOneTok) void route_scatter_kernel(const float *__r
     const long t = first + tid;
     int mine = -1;
     if (t < T) {
-        const float *l = logits + (size_t)t * E;
-        mine = top1(l, E);
-        const float lb = l[mine];
-        float den = 0.0f;
-        for (int e = 0; e < E; ++e) den += __expf(l[e] - lb);
-        expert_of[t] = mine;
-        gate[t] = 1.0f / den;
+        if (E_FIXED == 2) {
+            mine = own.y > own.x ? 1 : 0;
+            const float lb = mine ? own.y : own.x;
+            const float den = __expf(own.x - lb) + __expf(own.y - lb);      // the same sum, in the same order, as the general path
+            expert_of[t] = mine;
+            gate[t] = 1.0f / den;
+        } else {
+            const float *l = logits + (size_t)t * E;
+            mine = top1(l, E);
+            const float lb = l[mine];
+            float den = 0.0f;
+            for (int e = 0; e < E; ++e) den += __expf(l[e] - lb);
+            expert_of[t] = mine;
+            gate[t] = 1.0f / den;
+        }
     }
     int rank = 0;
     for (int e = 0; e < E; ++e) {
