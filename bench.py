@@ -611,11 +611,8 @@ def bench_sweep(args, sa, wl, torch, np):
                 w4 = torch.from_numpy(wl.pack_w4(neg, e)).cuda()
                 y32 = torch.empty((M, N), dtype=torch.int32, device="cuda")
                 # vector-ALU shift-and-accumulate; matrix cores with the 4-bit weights decoded in every call (two launches);
-                # matrix cores on planes decoded once beforehand (the matrix-core variants need K % 64 == 0)
-                variants = {"valu": (0, w4)}
-                if K % 64 == 0:
-                    variants["mfma"] = (1, w4)
-                    variants["mfma_prepared"] = (3, sa.sa_shift_planes_prepare(w4))
+                # matrix cores on planes decoded once beforehand
+                variants = {"valu": (0, w4), "mfma": (1, w4), "mfma_prepared": (3, sa.sa_shift_planes_prepare(w4))}
                 t = {}
                 for vn, (vid, wv) in variants.items():
                     wsl = torch.empty(max(16, lib.sa_shift_linear_workspace_bytes(sa._l(M), K, N, vid)), dtype=torch.uint8, device="cuda")

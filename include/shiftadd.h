@@ -157,16 +157,17 @@ int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes,
  * Shift layer (Eq. 3, O_Shift = sum X * s * 2^P) on int8 activations with
  * int32 accumulation:  y[m,n] = bias[n] + sum_k s[n,k] * (x[m,k] << e[n,k]).
  *   x [M,K] int8, w4 [N,K/2] packed 4-bit, bias [N] int32 or NULL, y [M,N] int32.
- * K % 32 == 0 (16-byte weight rows); the MFMA variant needs K % 64 == 0 (AUTO
- * falls back to VALU).
+ * K % 32 == 0 (16-byte weight rows), for both variants.
  * Both variants are bit-exact.  The MFMA variant decodes the weights to two
- * int8 planes in the workspace (2*N*K bytes) before the matrix-core pass.
+ * int8 planes in the workspace before the matrix-core pass (2*N*Kp bytes, Kp = K
+ * rounded up to a multiple of 64: plane rows are padded with zeros to whole
+ * 64-byte stages; the activation rows are read as they are).
  *
  * The planes depend on the weights only (s * 2^min(e,6) and s * 64 * [e == 7],
  * which sum to s * 2^e of Eq. 3), so a caller with fixed weights decodes them
  * once: sa_shift_planes_prepare writes them to `planes` (device memory of
  * sa_shift_planes_bytes(K, N) bytes, 16-byte aligned, owned by the caller;
- * K % 64 == 0).  With variant SA_VARIANT_MFMA_PREPARED the weight arguments of
+ * layout [2, N, Kp] int8; K % 32 == 0).  With variant SA_VARIANT_MFMA_PREPARED the weight arguments of
  * sa_shift_linear, sa_shift_mlp and sa_block_forward (w4, w1, w2) point at such
  * planes instead of packed nibbles, and no decode runs.
  */

@@ -245,15 +245,17 @@ def sa_shift_weights_from_float(w):
 
 
 def sa_shift_planes_prepare(w4):
-    """Packed 4-bit weights [N, K/2] -> the two int8 operand planes [2, N, K] of the prepared MFMA variant."""
+    """Packed 4-bit weights [N, K/2] -> the two int8 operand planes [2, N, Kp] of the prepared MFMA variant
+    (Kp = K rounded up to a multiple of 64, zero padded)."""
     lib = load_library()
     N, K = w4.shape[0], 2 * w4.shape[1]
     nbytes = lib.sa_shift_planes_bytes(K, N)
     if nbytes == 0:
-        raise SAError(-2, "sa_shift_planes_prepare: K must be a multiple of 64")
+        raise SAError(-2, "sa_shift_planes_prepare: K must be a multiple of 32")
     flat = torch.empty(nbytes, dtype=torch.int8, device=w4.device)
     _check(lib.sa_shift_planes_prepare(_ptr(w4), K, N, _ptr(flat), _z(nbytes), _stream()))
-    return flat[:2 * N * K].view(2, N, K)
+    Kp = (K + 63) // 64 * 64
+    return flat[:2 * N * Kp].view(2, N, Kp)
 
 
 def _out_width(w, variant):

@@ -49,6 +49,18 @@ __device__ inline void split_bf16(float f, __bf16 &hi, __bf16 &lo) {
     lo = (__bf16)(f - (float)hi);
 }
 
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+
+// The same split for a pair (a in the lower half of each dword, b in the upper): one packed conversion per term.
+__device__ inline void split_bf16_pair(float a, float b, uint32_t &upper, uint32_t &lower) {
+    v2f r = {a, b};
+    upper = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2bf));
+    r[0] -= __builtin_bit_cast(float, upper << 16);
+    r[1] -= __builtin_bit_cast(float, upper & 0xFFFF0000u);
+    lower = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2bf));
+}
+
 // Re-runs the defining chain for one parked (row, bit) entry and flips the stored bit where the
 // pre-pass had it wrong.
 // Up to two tensors of the same shape are hashed by one launch (Q and K of a block).
@@ -204,17 +216,16 @@ __global__ __launch_bounds__(256, 2) void binarize_mfma_kernel(Tensors ts, const
         const float keep = nx2 < __builtin_inff() ? __builtin_sqrtf(__builtin_fmaxf(kKeepFactor * nx2, kKeepFloor))
                                                   : __builtin_inff();
 
-        // the two bf16 terms of the row, once for all column groups
+        // the two bf16 terms of the row, once for all column groups; two elements per conversion
         v8bf xh[S], xl[S];
 #pragma unroll
-        for (int s = 0; s < S; ++s)
+        for (int s = 0; s < S; ++s) {
+            uint32_t up[4], lo[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                __bf16 hi, lo;
-                split_bf16(xv[s * 8 + e], hi, lo);
-                xh[s][e] = hi;
-                xl[s][e] = lo;
-            }
+            for (int e2 = 0; e2 < 4; ++e2) split_bf16_pair(xv[s * 8 + 2 * e2], xv[s * 8 + 2 * e2 + 1], up[e2], lo[e2]);
+            xh[s] = __builtin_bit_cast(v8bf, make_uint4(up[0], up[1], up[2], up[3]));
+            xl[s] = __builtin_bit_cast(v8bf, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+        }
         const bool row_ok = (r0 + i_loc) < rows;
 
 #pragma unroll 1

@@ -73,8 +73,12 @@ struct GemmArgs {
     const void *b[2];       // planes, each [N, K] elements, row-major
     RowSel sel;             // which rows of A / of the scattered output
     bool gather_a;          // A rows are sel.rows[m] (else compact m)
-    int K, N;
+    int K, N;               // K: extent of the contraction, a whole number of 64-byte stages; row length of the B planes
     int col_groups = 1;     // 1, 2, 4 or 8: set by the launcher
+    // A rows may be shorter than K (int8 only, 64-byte stages): a_valid elements, a multiple of 16 bytes, at a row
+    // pitch of a_ld elements; 0 = K.  The B planes must then hold zeros from a_valid on: the kernel multiplies
+    // those zeros with bytes it re-reads from inside the row, so it never reads past a row's end.
+    int a_ld = 0, a_valid = 0;
 };
 
 // Physical 16-byte chunk of logical chunk c in LDS row r, for rows of CPR chunks.
@@ -160,6 +164,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
     const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
     const int N = g.N;
     const size_t row_bytes = (size_t)g.K * T::kElemBytes;
+    const size_t a_row_bytes = (size_t)(g.a_ld > 0 ? g.a_ld : g.K) * T::kElemBytes;
+    const int a_valid_bytes = (g.a_valid > 0 ? g.a_valid : g.K) * T::kElemBytes;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
 
     // ---- what each lane fetches.  Wavefront w issues load i for LDS rows
@@ -173,8 +179,14 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
         long m = m0 + r;
         m = m < n_rows ? m : n_rows - 1;
         const long src = (g.gather_a && rows) ? (long)rows[m] : m;
-        a_src[i] = static_cast<const uint8_t *>(g.a) + (size_t)src * row_bytes + c * 16;
+        a_src[i] = static_cast<const uint8_t *>(g.a) + (size_t)src * a_row_bytes + c * 16;
     }
+    // The furthest stage offset at which this lane's chunk still lies inside an A row (64-byte stages: every load of
+    // a lane has the same physical chunk, rows 16 apart swizzle alike).  Beyond it the lane re-reads the row's last
+    // 16 bytes; with whole rows (a_valid == K) no stage offset gets that far.
+    int a_klim = 0;
+    if constexpr (SB == 64)
+        a_klim = a_valid_bytes - 16 - swizzle<kChunksPerRow>(lane / kChunksPerRow, lane % kChunksPerRow) * 16;
     const uint8_t *b_src[NP][B_INSTR];
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i) {
@@ -190,7 +202,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_nt_kernel(GemmArgs g, Store sto
     auto issue_load = [&](int q, int buf, int kbyte) {
         const uint32_t base = lds_base + buf * STAGE;
         if (q < A_INSTR) {
-            load_to_lds_16(a_src[q] + kbyte, base + (wave * A_INSTR + q) * 1024);
+            load_to_lds_16(a_src[q] + (SB == 64 ? min(kbyte, a_klim) : kbyte), base + (wave * A_INSTR + q) * 1024);
         } else {
             const int p = (q - A_INSTR) / B_INSTR, i = (q - A_INSTR) % B_INSTR;
             load_to_lds_16(b_src[p][i] + kbyte, base + A_BYTES + p * B_BYTES + (wave * B_INSTR + i) * 1024);
@@ -504,9 +516,12 @@ int launch_gemm(const GemmArgs &g, const Store &store, hipStream_t st, const cha
     if (g.sel.max_rows == 0 || g.N == 0) return SA_OK;
     const size_t row_bytes = (size_t)g.K * T::kElemBytes;
     SA_REQUIRE(row_bytes % 64 == 0 && row_bytes > 0, SA_ERR_SHAPE, "%s: rows of %zu bytes are not a multiple of 64", what, row_bytes);
+    const bool short_a = g.a_valid > 0 && g.a_valid != g.K;
+    SA_REQUIRE(!short_a || (T::kPlanes == 2 && g.a_valid > 0 && g.a_valid < g.K && g.a_valid % 16 == 0), SA_ERR_SHAPE,
+               "%s: A rows of %d valid elements in a contraction of %d", what, g.a_valid, g.K);
     SA_REQUIRE(Store::kBytes == 4 || (size_t)g.N * Store::kBytes % 16 == 0, SA_ERR_SHAPE,
                "%s: narrow output rows of %d elements are not whole 16-byte chunks", what, g.N);
-    const bool lines = row_bytes % 128 == 0, long_rows = row_bytes >= 2048;
+    const bool lines = row_bytes % 128 == 0 && !short_a, long_rows = row_bytes >= 2048;
     const long blocks256 = ((g.sel.max_rows + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (T::kPlanes == 2) {
         if (lines && long_rows) return launch_gemm_tile<T, 256, 128, 128, 2, 2, 1, Store>(g, store, st, what);

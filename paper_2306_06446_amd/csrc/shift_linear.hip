@@ -145,12 +145,26 @@ __device__ inline void decode8(uint32_t x, uint32_t outA[2], uint32_t outB[2]) {
     outB[1] = perm(b[1], b[0], 0x07030602u);
 }
 
-// One thread per 16 bytes of packed weights (32 weights): 32 B out to each plane.
+// One thread per 32 weights of a padded plane row (row_chunks of them, the first valid_chunks from 16 bytes of
+// packed weights each, the others zero): 32 B out to each plane.
 __global__ __launch_bounds__(256) void decode_w4_kernel(const uint4 *__restrict__ w4, long n_chunks,
-                                                        uint4 *__restrict__ plane_a, uint4 *__restrict__ plane_b) {
+                                                        uint4 *__restrict__ plane_a, uint4 *__restrict__ plane_b,
+                                                        int valid_chunks, int row_chunks) {
     const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_chunks) return;
-    const uint4 wv = w4[i];
+    uint4 wv;
+    if (valid_chunks == row_chunks) {
+        wv = w4[i];
+    } else {
+        const long n = i / row_chunks;
+        const int kc = (int)(i - n * row_chunks);
+        if (kc >= valid_chunks) {
+            const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+            plane_a[2 * i] = plane_a[2 * i + 1] = plane_b[2 * i] = plane_b[2 * i + 1] = zero;
+            return;
+        }
+        wv = w4[n * valid_chunks + kc];
+    }
     const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
     uint32_t oa[8], ob[8];
 #pragma unroll
@@ -228,15 +242,18 @@ struct ShiftStore {
     }
 };
 
-size_t planes_bytes(int K, int N) { return ((size_t)2 * N * K + 255) / 256 * 256; }
-
-constexpr int kMfmaK = 64;   // K granularity of the MFMA variant (one LDS stage)
+constexpr int kMfmaK = 32;   // K granularity of the MFMA variant (16 bytes of packed weights, 32 of activations)
+// Plane rows are padded with zeros to whole 64-byte LDS stages.
+int padded_k(int K) { return (K + 63) / 64 * 64; }
+size_t planes_bytes(int K, int N) { return ((size_t)2 * N * padded_k(K) + 255) / 256 * 256; }
 
 int decode_planes(const uint8_t *w4, int K, int N, void *planes, hipStream_t st) {
-    int8_t *pa = static_cast<int8_t *>(planes), *pb = pa + (size_t)N * K;
-    const long n_chunks = (long)N * K / 32;
+    const int Kp = padded_k(K);
+    int8_t *pa = static_cast<int8_t *>(planes), *pb = pa + (size_t)N * Kp;
+    const long n_chunks = (long)N * Kp / 32;
     decode_w4_kernel<<<dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st>>>(
-        reinterpret_cast<const uint4 *>(w4), n_chunks, reinterpret_cast<uint4 *>(pa), reinterpret_cast<uint4 *>(pb));
+        reinterpret_cast<const uint4 *>(w4), n_chunks, reinterpret_cast<uint4 *>(pa), reinterpret_cast<uint4 *>(pb), K / 32,
+        Kp / 32);
     return check_launch("shift layer (weight decode)");
 }
 
@@ -261,7 +278,8 @@ int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &
     if (sel.max_rows == 0 || N == 0) return SA_OK;
     if (variant == SA_VARIANT_AUTO) variant = (K % kMfmaK == 0) ? SA_VARIANT_MFMA : SA_VARIANT_VALU;
     if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED) {
-        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "shift layer: the MFMA variant needs K %% 64 == 0 (K = %d)", K);
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "shift layer: the MFMA variant needs K %% 32 == 0 (K = %d)", K);
+        const int Kp = padded_k(K);
         const int8_t *pa, *pb;
         if (variant == SA_VARIANT_MFMA_PREPARED) {
             pa = reinterpret_cast<const int8_t *>(w4);      // the caller decoded the weights beforehand
@@ -272,14 +290,16 @@ int launch_shift(int variant, const int8_t *x, const uint8_t *w4, const RowSel &
             }
             pa = static_cast<const int8_t *>(planes);
         }
-        pb = pa + (size_t)N * K;
+        pb = pa + (size_t)N * Kp;
         GemmArgs g;
         g.a = x;
         g.b[0] = pa;
         g.b[1] = pb;
         g.sel = sel;
         g.gather_a = gather;
-        g.K = K;
+        g.K = Kp;           // the planes' rows are padded with zeros to whole stages; the activation rows are not
+        g.a_ld = K;
+        g.a_valid = K;
         g.N = N;
         ShiftStore<MODE> store(epi);
         return launch_gemm<I8Traits>(g, store, st, "shift layer (MFMA)");
@@ -361,7 +381,7 @@ extern "C" int sa_shift_planes_prepare(const uint8_t *w4, int K, int N, void *pl
                                        void *stream) {
     sa::clear_error();
     SA_REQUIRE(K > 0 && N > 0, SA_ERR_INVALID, "sa_shift_planes_prepare: K and N must be positive");
-    SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_planes_prepare: K (%d) must be a multiple of 64", K);
+    SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_planes_prepare: K (%d) must be a multiple of 32", K);
     SA_REQUIRE(w4 && planes, SA_ERR_INVALID, "sa_shift_planes_prepare: NULL buffer");
     SA_REQUIRE(sa::aligned16(w4) && sa::aligned16(planes), SA_ERR_ALIGN,
                "sa_shift_planes_prepare: pointers must be 16-byte aligned");
@@ -408,7 +428,7 @@ extern "C" int sa_shift_linear(const int8_t *x, const uint8_t *w4, const int32_t
                SA_ERR_ALIGN, "sa_shift_linear: pointers must be 16-byte aligned");
     SA_REQUIRE(K % 32 == 0, SA_ERR_SHAPE, "sa_shift_linear: K (%d) must be a multiple of 32 (16-byte weight rows)", K);
     if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED)
-        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear: the MFMA variants need K %% 64 == 0 (K = %d)", K);
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear: the MFMA variants need K %% 32 == 0 (K = %d)", K);
     const size_t need = sa_shift_linear_workspace_bytes(M, K, N, variant);
     SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
                "sa_shift_linear: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
@@ -448,7 +468,7 @@ extern "C" int sa_shift_linear_f32(const int8_t *x, const uint8_t *w4, long M, i
                    sa::aligned16(residual_or_null) && sa::aligned16(workspace),
                SA_ERR_ALIGN, "sa_shift_linear_f32: pointers must be 16-byte aligned");
     if (variant == SA_VARIANT_MFMA || variant == SA_VARIANT_MFMA_PREPARED)
-        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear_f32: the MFMA variants need K %% 64 == 0 (K = %d)", K);
+        SA_REQUIRE(K % kMfmaK == 0, SA_ERR_SHAPE, "sa_shift_linear_f32: the MFMA variants need K %% 32 == 0 (K = %d)", K);
     const size_t need = sa_shift_linear_workspace_bytes(M, K, N, variant);
     SA_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), SA_ERR_WORKSPACE,
                "sa_shift_linear_f32: workspace of %zu bytes needed, %zu given", need, workspace_bytes);

@@ -42,12 +42,13 @@ int main(void) {
     /* shift layers */
     EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 33, 8, 0, NULL, 0, NULL), SA_ERR_SHAPE);
     EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 64, 8, 7, NULL, 0, NULL), SA_ERR_INVALID);
-    EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 96, 8, 1, NULL, 0, NULL), SA_ERR_SHAPE);
+    EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 48, 8, 1, NULL, 0, NULL), SA_ERR_SHAPE);
+    EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 96, 8, 1, NULL, 0, NULL), SA_ERR_WORKSPACE);
     EXPECT(sa_shift_linear(NULL, fake, NULL, fake, 4, 64, 8, 0, NULL, 0, NULL), SA_ERR_INVALID);
     EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 64, 8, 1, NULL, 0, NULL), SA_ERR_WORKSPACE);
     EXPECT(sa_shift_linear(fake, fake, NULL, fake, 1L << 40, 64, 8, 0, NULL, 0, NULL), SA_ERR_SHAPE);
     EXPECT(sa_shift_linear(fake, fake, NULL, fake, 4, 262144, 8, 0, NULL, 0, NULL), SA_ERR_SHAPE);
-    if (sa_shift_planes_bytes(64, 8) != 1024 || sa_shift_planes_bytes(96, 8) != 0) ++failures;
+    if (sa_shift_planes_bytes(64, 8) != 1024 || sa_shift_planes_bytes(96, 8) != 2048 || sa_shift_planes_bytes(48, 8) != 0) ++failures;
     EXPECT(sa_shift_planes_prepare(fake, 64, 8, fake, 16, NULL), SA_ERR_WORKSPACE);
     EXPECT(sa_shift_weights_from_float(fake, 4, 12, fake, NULL), SA_ERR_SHAPE);
     EXPECT(sa_shift_linear_f32(fake, fake, 4, 64, 12, 0, 1.0f, fake, 3, fake, fake, fake, NULL, 0, NULL), SA_ERR_INVALID);

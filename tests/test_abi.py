@@ -80,12 +80,14 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.sa_hamming_attention(fake, fake, fake, fake, 1, 1, 4, 0, 64, 64, f, null, null) == -2
     assert lib.sa_hamming_attention(fake, fake, fake, fake, 1, 1, 4, 4, 64, 64, ctypes.c_float(float("nan")),
                                     null, null) == -1
-    # shift linear: odd K, unknown variant, MFMA with K % 64 != 0
+    # shift linear: odd K, K that is not a multiple of 32 (any variant), unknown variant
     M = ctypes.c_long(4)
     z0 = ctypes.c_size_t(0)
     assert lib.sa_shift_linear(fake, fake, null, fake, M, 33, 8, 0, null, z0, null) == -2
     assert lib.sa_shift_linear(fake, fake, null, fake, M, 64, 8, 7, null, z0, null) == -1
-    assert lib.sa_shift_linear(fake, fake, null, fake, M, 96, 8, 1, null, z0, null) == -2
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 48, 8, 1, null, z0, null) == -2
+    assert lib.sa_shift_linear(fake, fake, null, fake, M, 96, 8, 1, null, z0, null) == -4   # planes workspace (96 -> 128 per row)
+    assert lib.sa_shift_planes_bytes(96, 8) == 2 * 8 * 128 and lib.sa_shift_planes_bytes(48, 8) == 0
     assert lib.sa_shift_linear(null, fake, null, fake, M, 64, 8, 0, null, z0, null) == -1
     assert lib.sa_shift_linear(fake, fake, null, fake, M, 64, 8, 1, null, z0, null) == -4   # planes workspace
     # dispatch: E out of range, missing workspace

@@ -263,7 +263,7 @@ def test_shift_linear_random_shapes(sa, seed):
     128, stages of 64 and 128 bytes), weights decoded per call and prepared planes."""
     g = np.random.default_rng([77, seed])
     M = int(g.choice([1, 63, 127, 129, 255, 257, 511, 700, 1025])) + int(g.integers(0, 3))
-    K = 64 * int(g.choice([1, 2, 3, 5, 8, 12, 32, 33, 48]))
+    K = 32 * int(g.choice([1, 2, 3, 4, 5, 6, 10, 16, 24, 64, 66, 67, 96]))
     N = int(g.choice([1, 31, 127, 128, 129, 200, 383, 640, 1300]))
     neg = g.integers(0, 2, size=(N, K), dtype=np.uint8)
     e = g.integers(0, 8, size=(N, K), dtype=np.uint8)
@@ -275,11 +275,26 @@ def test_shift_linear_random_shapes(sa, seed):
     assert np.array_equal(host(sa.sa_shift_linear(dev(x), planes, variant=3)), ref), (M, K, N)
 
 
-def test_shift_linear_auto_falls_back_when_k_not_multiple_of_64(sa):
-    M, K, N = 40, 96, 33
+@pytest.mark.parametrize("M,K,N", [(40, 96, 33), (3136, 32, 32), (777, 32, 256), (196, 160, 640), (1300, 160, 160),
+                                   (130, 224, 129), (257, 32, 1)])
+def test_shift_linear_rows_that_end_inside_a_stage(sa, M, K, N):
+    """K a multiple of 32 but not of 64: the matrix-core variants pad the weight planes with zeros to whole 64-byte
+    stages and read the activation rows as they are (the last stage re-reads bytes from inside the row against
+    those zeros).  Every variant, with extreme activations in the last columns and rows."""
     w4 = wl.shift_weights(3, 5, N, K)
     x = wl.int8_activations(3, M, K, extra=5)
-    assert np.array_equal(host(sa.sa_shift_linear(dev(x), dev(w4), variant=2)), oracle.shift_linear(x, w4))
+    x[-1, :] = 127
+    x[:, -1] = -127
+    x[0, K - 32:] = 127
+    ref = oracle.shift_linear(x, w4)
+    planes = sa.sa_shift_planes_prepare(dev(w4))
+    assert planes.shape == (2, N, (K + 63) // 64 * 64)
+    assert not host(planes)[:, :, K:].any()
+    for variant, w in ((0, dev(w4)), (1, dev(w4)), (2, dev(w4)), (3, planes)):
+        assert np.array_equal(host(sa.sa_shift_linear(dev(x), w, variant=variant)), ref), variant
+    # the last activation row is the last bytes of its buffer: a second call on a buffer that ends there
+    tight = dev(x.reshape(-1)).clone().view(M, K)
+    assert np.array_equal(host(sa.sa_shift_linear(tight, dev(w4), variant=1)), ref)
 
 
 # -------------------------------------------------------- quantisation glue ----
