@@ -9,13 +9,15 @@
 // The second MatMul P * V is the dense contraction of this kernel and runs on the bf16
 // matrix cores (v_mfma_f32_32x32x16_bf16) as three products with fp32 accumulation,
 //     P * V ~ ph * vh + ph * vl + pl * vh,        v ~ vh + vl likewise,
-// which drops only terms below 2^-17 of each p * v (the output tolerance is 1e-4).  The A
-// operand of one MFMA is 8 numerators per lane - query (lane % 32), keys k0 + 8 * (lane / 32)
-// .. + 7 - exactly the pairs whose distances the lane has just computed, so P never exists
-// in memory.  A workgroup owns one (batch, head) and up to 256 queries (one 32-query tile per
-// wavefront); key codes and V rows are staged through LDS in chunks of 128 keys, V
-// transposed and split into its two bf16 planes, so that a B operand (8 consecutive keys of
-// one column) is one 16-byte read.  Row sums ride along in the lanes and meet in the epilogue.
+// which drops only terms below 2^-17 of each p * v (the output tolerance is 1e-4).  The products
+// are issued transposed, O^T = V^T * P^T: the P operand of one MFMA is 8 numerators per lane -
+// query (lane % 32), keys k0 + 8 * (lane / 32) .. + 7 - exactly the pairs whose distances the lane
+// has just computed, so P never exists in memory, and the accumulators end up holding, per lane,
+// whole 16-byte pieces of that lane's own query row (no transposes, no staging in the epilogue).
+// A workgroup owns one (batch, head) and up to 256 queries (one 32-query tile per wavefront); key
+// codes and V rows are staged through LDS in chunks of 128 keys, V transposed and split into its
+// two bf16 planes, so that a V operand (8 consecutive keys of one column) is one 16-byte read.
+// Row sums ride along in the lanes and meet in the epilogue.
 //
 // softmax(scale*S)_j = exp2(c2 * (dist_j - dist_ref)) / sum, c2 = -2*scale*log2(e),
 // dist_ref = the distance of the largest score.  When scale >= 0 and the exponent
@@ -60,29 +62,6 @@ __device__ inline uint32_t split_bf16(float f) {
 }
 
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
-
-// x[j] of lane q (q = lane % 4) <-> x[q] of lane j, inside each group of four lanes: two butterfly
-// stages, lane bit b against register-index bit b.
-__device__ inline void transpose_in_quad(float (&x)[4], int q4) {
-    constexpr int kXor1 = 0xB1, kXor2 = 0x4E;           // DPP quad_perm [1,0,3,2] and [2,3,0,1]
-    const bool odd = q4 & 1, upper = q4 & 2;
-#pragma unroll
-    for (int p = 0; p < 4; p += 2) {                     // pairs (0,1) and (2,3)
-        const float send = odd ? x[p] : x[p + 1];
-        const float recv = __builtin_bit_cast(
-            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), kXor1, 0xF, 0xF, false));
-        x[p] = odd ? recv : x[p];
-        x[p + 1] = odd ? x[p + 1] : recv;
-    }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {                        // pairs (0,2) and (1,3)
-        const float send = upper ? x[p] : x[p + 2];
-        const float recv = __builtin_bit_cast(
-            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), kXor2, 0xF, 0xF, false));
-        x[p] = upper ? recv : x[p];
-        x[p + 2] = upper ? x[p + 2] : recv;
-    }
-}
 
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
@@ -161,82 +140,93 @@ struct TableEntry {
     float p;
 };
 
-// Row sums meet, then every output form leaves in whole 16-byte pieces of a row.  The fp32 rows go out
-// straight from the registers (after the transpose a quad-aligned group of lanes covers 128 contiguous
-// bytes of a row).  The int8 and fp16 forms are narrower than that: they are collected per wavefront in
-// LDS (`stage_q`, `stage_h`: the V planes, free by now), 16 rows at a time, and leave as 16 bytes per lane,
-// so that a store covers a head's whole 64- or 128-byte row piece instead of 4- and 8-byte crumbs.
+// Epilogue.  The accumulators hold the TRANSPOSED output tile (the P * V products are issued as V^T * P^T):
+// register r of accumulator jt in lane (i, kg) is column jt * 32 + 8 * (r / 4) + 4 * kg + r % 4 of query i, so a
+// lane owns 16-byte pieces of its own query's row and the row sum it needs is its own plus its partner's (lane
+// i + 32, which summed the other keys).  Stored straight from the registers those pieces would reach memory as
+// 16- and 32-byte requests, several times as many as the bytes need (measured: 45-48 us against 39-40 us for the
+// DeiT-Base shape).  So the wavefront writes 16 queries at a time into `stage`, an area in LDS of its own (16 rows
+// of DV floats, row pitch stage_pitch), and reads them back with consecutive lanes on consecutive columns of a
+// row: fp32 rows leave as 16 bytes per lane (DV / 4 lanes cover a head's row piece), the int8 codes of the
+// activation quantiser as 16 columns per lane, the fp16 rounding as 8 columns per lane.  Only this wavefront
+// touches its `stage`, and the LDS operations of a wavefront execute in order: no barrier inside.
 template <int DV>
-__device__ inline void write_outputs(v16f (&acc)[DV / 32], float den, float *den_s, float *__restrict__ out,
-                                     int8_t *__restrict__ xq, _Float16 *__restrict__ xh, float act_inv_scale, int b,
-                                     int h, int H, int Nq, int chunk, int wave, int lane, uint8_t *stage_q,
-                                     uint8_t *stage_h) {
+constexpr int stage_pitch() { return DV * 4 + (DV >= 64 ? 16 : 8); }
+template <int DV>
+constexpr int stage_bytes_per_wave() { return 16 * stage_pitch<DV>(); }
+
+template <int DV>
+__device__ inline void write_outputs(v16f (&acc)[DV / 32], float den, uint8_t *stage, float *__restrict__ out,
+                                            int8_t *__restrict__ xq, _Float16 *__restrict__ xh, float act_inv_scale, int b,
+                                            int h, int H, int Nq, int chunk, int wave, int lane) {
     constexpr int JT = DV / 32;
+    constexpr int PITCH = stage_pitch<DV>();
     const int i_loc = lane & 31, kg = lane >> 5;
-    // row sums: the two half-wavefronts hold different keys of the same 32 queries
     den += __shfl_xor(den, 32);
-    if (lane < 32) den_s[wave * 32 + lane] = den;
-    // A lane holds one column of four consecutive rows per register quartet; after a 4 x 4
-    // transpose inside each quad of lanes it holds four consecutive columns of one row.
+    const float inv = 1.0f / den;
     const int q_tile0 = chunk * (kMaxWaves * 32) + wave * 32;
-    const int q4 = lane & 3;
-    uint8_t *my_q = stage_q + wave * 16 * DV;
-    uint8_t *my_h = stage_h + wave * 16 * DV * 2;
+    const size_t row_elems = (size_t)H * DV;
+    const size_t tile_at = (((size_t)b * Nq + q_tile0) * H + h) * DV;      // element (q_tile0, column 0 of the head)
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        __syncthreads();                                      // row sums are there; the staging rows are free
+        if ((i_loc >> 4) == half) {
+            uint8_t *row = stage + (i_loc & 15) * PITCH;
 #pragma unroll
-        for (int gg = 0; gg < 2; ++gg) {
-            const int g = 2 * half + gg;
-            const int row16 = 8 * gg + 4 * kg + q4;               // row inside this half
-            const int row = 16 * half + row16;                    // the row this lane holds after the transpose
-            const int qo = q_tile0 + row;
-            const float inv = 1.0f / den_s[wave * 32 + row];
-            const size_t at = (((size_t)b * Nq + min(qo, Nq - 1)) * H + h) * DV + (i_loc & ~3);
+            for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
-            for (int jt = 0; jt < JT; ++jt) {
-                float x[4] = {acc[jt][4 * g], acc[jt][4 * g + 1], acc[jt][4 * g + 2], acc[jt][4 * g + 3]};
-                transpose_in_quad(x, q4);
-                const float4 val = make_float4(x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv);
-                if (out && qo < Nq) *reinterpret_cast<float4 *>(out + at + jt * 32) = val;
-                // what the MLP reads: the int8 codes of the activation quantiser, and the fp16 rounding
-                const int col = jt * 32 + (i_loc & ~3);
-                if (xq) {
-                    const uint32_t c0 = sa::requant_byte(val.x * act_inv_scale);
-                    const uint32_t c1 = sa::requant_byte(val.y * act_inv_scale);
-                    const uint32_t c2b = sa::requant_byte(val.z * act_inv_scale);
-                    const uint32_t c3 = sa::requant_byte(val.w * act_inv_scale);
-                    *reinterpret_cast<uint32_t *>(my_q + row16 * DV + col) = c0 | (c1 << 8) | (c2b << 16) | (c3 << 24);
-                }
-                if (xh) {
-                    v4h hv;
-                    hv[0] = (_Float16)val.x; hv[1] = (_Float16)val.y; hv[2] = (_Float16)val.z; hv[3] = (_Float16)val.w;
-                    *reinterpret_cast<v4h *>(my_h + (row16 * DV + col) * 2) = hv;
-                }
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4 *>(row + (jt * 32 + 8 * g + 4 * kg) * 4) =
+                        make_float4(acc[jt][4 * g] * inv, acc[jt][4 * g + 1] * inv, acc[jt][4 * g + 2] * inv,
+                                    acc[jt][4 * g + 3] * inv);
+        }
+        const int q_half0 = q_tile0 + 16 * half;
+        if (out) {
+            constexpr int LPR = DV / 4;                   // lanes per row, 16 bytes each
+            constexpr int RPP = 64 / LPR;                 // rows per pass
+#pragma unroll
+            for (int p = 0; p < 16 / RPP; ++p) {
+                const int r = p * RPP + lane / LPR, c = (lane % LPR) * 4;
+                const float4 val = *reinterpret_cast<const float4 *>(stage + r * PITCH + c * 4);
+                if (q_half0 + r < Nq) *reinterpret_cast<float4 *>(out + tile_at + (size_t)(16 * half + r) * row_elems + c) = val;
             }
         }
-        if (xq == nullptr && xh == nullptr) continue;
-        __syncthreads();
         if (xq) {
-            constexpr int CPR = DV / 16;                          // 16-byte pieces per row
+            constexpr int LPR = DV / 16;                  // lanes per row, 16 columns each
+            constexpr int RPP = 64 / LPR;
 #pragma unroll
-            for (int c = lane; c < 16 * CPR; c += 64) {
-                const int r = c / CPR, cc = c % CPR;
-                const int qo = q_tile0 + 16 * half + r;
-                if (qo < Nq)
-                    *reinterpret_cast<uint4 *>(xq + (((size_t)b * Nq + qo) * H + h) * DV + cc * 16) =
-                        *reinterpret_cast<const uint4 *>(my_q + r * DV + cc * 16);
+            for (int p = 0; p < (16 + RPP - 1) / RPP; ++p) {
+                const int r = p * RPP + lane / LPR, c = (lane % LPR) * 16;
+                if (r < 16) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const float4 val = *reinterpret_cast<const float4 *>(stage + r * PITCH + (c + 4 * e4) * 4);
+                        w[e4] = sa::requant_byte(val.x * act_inv_scale) | (sa::requant_byte(val.y * act_inv_scale) << 8) |
+                                (sa::requant_byte(val.z * act_inv_scale) << 16) | (sa::requant_byte(val.w * act_inv_scale) << 24);
+                    }
+                    if (q_half0 + r < Nq)
+                        *reinterpret_cast<uint4 *>(xq + tile_at + (size_t)(16 * half + r) * row_elems + c) =
+                            make_uint4(w[0], w[1], w[2], w[3]);
+                }
             }
         }
         if (xh) {
-            constexpr int CPR = DV / 8;
+            constexpr int LPR = DV / 8;                   // lanes per row, 8 columns each
+            constexpr int RPP = 64 / LPR;
 #pragma unroll
-            for (int c = lane; c < 16 * CPR; c += 64) {
-                const int r = c / CPR, cc = c % CPR;
-                const int qo = q_tile0 + 16 * half + r;
-                if (qo < Nq)
-                    *reinterpret_cast<uint4 *>(xh + (((size_t)b * Nq + qo) * H + h) * DV + cc * 8) =
-                        *reinterpret_cast<const uint4 *>(my_h + (r * DV + cc * 8) * 2);
+            for (int p = 0; p < (16 + RPP - 1) / RPP; ++p) {
+                const int r = p * RPP + lane / LPR, c = (lane % LPR) * 8;
+                if (r < 16) {
+                    const float4 v0 = *reinterpret_cast<const float4 *>(stage + r * PITCH + c * 4);
+                    const float4 v1 = *reinterpret_cast<const float4 *>(stage + r * PITCH + (c + 4) * 4);
+                    v4h h0, h1;
+                    h0[0] = (_Float16)v0.x; h0[1] = (_Float16)v0.y; h0[2] = (_Float16)v0.z; h0[3] = (_Float16)v0.w;
+                    h1[0] = (_Float16)v1.x; h1[1] = (_Float16)v1.y; h1[2] = (_Float16)v1.z; h1[3] = (_Float16)v1.w;
+                    const uint2 a2 = __builtin_bit_cast(uint2, h0), b2 = __builtin_bit_cast(uint2, h1);
+                    if (q_half0 + r < Nq)
+                        *reinterpret_cast<uint4 *>(xh + tile_at + (size_t)(16 * half + r) * row_elems + c) =
+                            make_uint4(a2.x, a2.y, b2.x, b2.y);
+                }
             }
         }
     }
@@ -250,10 +240,10 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
     constexpr int JT = DV / 32;
     constexpr int NBITS = W * 64;
     __shared__ __attribute__((aligned(16))) uint64_t kc_s[kKeyChunk * W];
-    __shared__ __attribute__((aligned(16))) uint16_t vth_s[DV * kVtStride];   // V^T, upper bf16 term
-    __shared__ __attribute__((aligned(16))) uint16_t vtl_s[DV * kVtStride];   // V^T, lower bf16 term
+    __shared__ __attribute__((aligned(16))) uint16_t vt_s[2][DV * kVtStride];  // V^T, upper and lower bf16 term; the
+    uint16_t *vth_s = vt_s[0], *vtl_s = vt_s[1];                                // epilogue stages the outputs here
+    static_assert(sizeof(vt_s) >= kMaxWaves * stage_bytes_per_wave<DV>(), "the planes hold every wavefront's staging rows");
     __shared__ __attribute__((aligned(8))) TableEntry tab_s[NBITS + 1];
-    __shared__ float den_s[kMaxWaves * 32];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -333,9 +323,9 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
             const int off = (jt * 32 + i_loc) * kVtStride + kb;
             const v8bf vh = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vth_s + off));
             const v8bf vl = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vtl_s + off));
-            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vh, acc[jt], 0, 0, 0);
-            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vl, acc[jt], 0, 0, 0);
-            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, vh, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, ph, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vl, ph, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, pl, acc[jt], 0, 0, 0);
         }
     };
 
@@ -351,8 +341,205 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mfma_kernel(
         if (n_full < n) step(n_full, n, std::true_type{});
     }
 
-    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane,
-                      reinterpret_cast<uint8_t *>(vth_s), reinterpret_cast<uint8_t *>(vtl_s));
+    __syncthreads();                               // every wavefront is through its steps: the planes become staging rows
+    write_outputs<DV>(acc, den, reinterpret_cast<uint8_t *>(&vt_s[0][0]) + wave * stage_bytes_per_wave<DV>(), out, xq, xh,
+                             act_inv_scale, b, h, H, Nq, chunk, wave, lane);
+}
+
+// ---- the same kernel as a pipeline over several (batch, head, query chunk) units per workgroup ------------
+// The kernel above runs its phases one after the other: load V, split it, multiply, store.  With every workgroup
+// of a launch resident at once (768 at the DeiT-Base shape, three per CU) the whole chip loads, then computes,
+// then stores.  Here a launch has only as many workgroups as fit the chip; each walks over its units
+// (u = blockIdx.x, + gridDim.x, ...) and over their 128-key chunks, and the NEXT chunk's V rows and key codes are
+// already on their way while the current chunk is multiplied: they arrive through direct global -> LDS loads
+// (no registers, no waiting wavefront) as raw fp32 rows, and are split into the two bf16 planes LDS -> LDS at the
+// chunk switch.  The output stores of a unit drain while the next unit is computed.  Same arithmetic, same
+// order, bit-identical results.  Row reference distances (ROWREF in the kernel above) need all key codes of a
+// unit before its first step and keep the kernel above.
+//
+// One wavefront-wide direct load: lane l's 16 (4) bytes at `src` land at LDS byte lds_base + 16 (4) * l.
+__device__ inline void async_load_16(const void *src, uint32_t lds_base) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, off\n\t"
+        :
+        : "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src)
+        : "memory");
+}
+__device__ inline void async_load_4(const void *src, uint32_t lds_base) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dword %1, off\n\t"
+        :
+        : "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src)
+        : "memory");
+}
+
+template <int DV, int W>
+__global__ __launch_bounds__(kMaxWaves *kWave, 4) void hamming_pipe_kernel(
+    const uint64_t *__restrict__ q_codes, const uint64_t *__restrict__ k_codes, const float *__restrict__ v,
+    float *__restrict__ out, int H, int Nq, int Nk, int q_chunks, float c2, int8_t *__restrict__ xq,
+    _Float16 *__restrict__ xh, float act_inv_scale, long n_units) {
+    constexpr int JT = DV / 32;
+    constexpr int NBITS = W * 64;
+    constexpr int RPI = 1024 / (DV * 4);           // V rows one wavefront-wide 16-byte load brings
+    constexpr int L4 = DV / 4;                     // lanes per V row
+    __shared__ __attribute__((aligned(1024))) float raw_s[kKeyChunk * DV];          // the next chunk's V rows as loaded
+    __shared__ __attribute__((aligned(1024))) uint64_t kc_s[2][kKeyChunk * W];      // key codes, this chunk's and the next's
+    __shared__ __attribute__((aligned(16))) uint16_t vt_s[2][DV * kVtStride];  // V^T, upper and lower bf16 term; the
+    uint16_t *vth_s = vt_s[0], *vtl_s = vt_s[1];                                // epilogue stages the outputs here
+    static_assert(sizeof(vt_s) >= kMaxWaves * stage_bytes_per_wave<DV>(), "the planes hold every wavefront's staging rows");
+    __shared__ __attribute__((aligned(8))) TableEntry tab_s[NBITS + 1];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_threads = blockDim.x, n_waves = n_threads >> 6;
+    const int i_loc = lane & 31, kg = lane >> 5;
+    const uint32_t raw_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)raw_s;
+    const uint32_t kc_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint64_t *)&kc_s[0][0];
+
+    // Chunk at key j of unit u -> raw_s and kc_s[buf].  Rows and code bytes past the last key are re-reads of
+    // the last valid ones (never used: the conversion zeroes those V rows, the last step masks those keys).
+    auto issue_chunk = [&](long u, int j, int buf) {
+        const long bh = u / q_chunks;
+        const int b = (int)(bh / H), h = (int)(bh % H);
+        const int n = min(kKeyChunk, Nk - j);
+        const int n_pad = (n + 15) & ~15;
+        const int v_instr = (n_pad + RPI - 1) / RPI;
+        for (int k = wave; k < v_instr; k += n_waves) {
+            const int key = min(k * RPI + lane / L4, n - 1);
+            const float *src = v + (((size_t)b * Nk + j + key) * H + h) * DV + (lane % L4) * 4;
+            async_load_16(src, raw_base + k * 1024);
+        }
+        const int code_bytes = n * W * 8, code_instr = (n_pad * W * 8 + 255) / 256;
+        const char *cg = reinterpret_cast<const char *>(k_codes + ((size_t)bh * Nk + j) * W);
+        for (int k = wave; k < code_instr; k += n_waves) {
+            const int off = min(k * 256 + lane * 4, code_bytes - 4);
+            async_load_4(cg + off, kc_base + buf * (kKeyChunk * W * 8) + k * 256);
+        }
+    };
+    auto load_query = [&](long u, uint64_t (&dst)[W]) {
+        const long bh = u / q_chunks;
+        const int chunk = (int)(u % q_chunks);
+        const int qi = min(chunk * (kMaxWaves * 32) + wave * 32 + i_loc, Nq - 1);
+#pragma unroll
+        for (int w = 0; w < W; ++w) dst[w] = q_codes[((size_t)bh * Nq + qi) * W + w];
+    };
+
+    long u = blockIdx.x;
+    if (u >= n_units) return;
+    issue_chunk(u, 0, 0);
+    uint64_t q[W], qn[W];
+    load_query(u, qn);
+
+    // numerators by distance: the exponent is c2 * dist (no row reference here)
+    const float c2n = c2 <= 0.0f ? c2 : -c2;
+    for (int t = tid; t <= NBITS; t += n_threads) {
+        const float pt = __builtin_amdgcn_exp2f(c2n * (float)t);
+        tab_s[t].hl = split_bf16(pt);
+        tab_s[t].p = pt;
+    }
+
+    v16f acc[JT];
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
+    float den = 0.0f;
+
+    // One step: 16 keys from k0 (8 per half-wavefront).  MASK: keys from n on do not count.
+    auto step = [&](const uint64_t *kc, int k0, int n, auto mask_c) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        const int kb = k0 + 8 * kg;                       // this lane's first key
+        uint32_t hl[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int t = distance<W>(q, kc + (kb + e) * W);      // padding keys hold arbitrary code bytes: still 0 .. NBITS
+            const TableEntry te = tab_s[t];
+            hl[e] = te.hl;
+            den += (!MASK || kb + e < n) ? te.p : 0.0f;
+        }
+        uint32_t ah[4], al[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            ah[e2] = __builtin_amdgcn_perm(hl[2 * e2 + 1], hl[2 * e2], 0x07060302u);   // upper halves
+            al[e2] = __builtin_amdgcn_perm(hl[2 * e2 + 1], hl[2 * e2], 0x05040100u);   // lower halves
+        }
+        const v8bf ph = __builtin_bit_cast(v8bf, make_uint4(ah[0], ah[1], ah[2], ah[3]));
+        const v8bf pl = __builtin_bit_cast(v8bf, make_uint4(al[0], al[1], al[2], al[3]));
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt) {
+            const int off = (jt * 32 + i_loc) * kVtStride + kb;
+            const v8bf vh = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vth_s + off));
+            const v8bf vl = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(vtl_s + off));
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, ph, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vl, ph, acc[jt], 0, 0, 0);
+            acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, pl, acc[jt], 0, 0, 0);
+        }
+    };
+
+    int j0 = 0, buf = 0;
+    for (;;) {
+        if (j0 == 0) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) q[w] = qn[w];
+        }
+        const int n = min(kKeyChunk, Nk - j0);
+        const int n_pad = (n + 15) & ~15;
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // this wavefront's direct loads of the chunk have landed
+        __syncthreads();                             // ... everyone's; the planes of the previous chunk have been consumed
+        // raw rows -> the two transposed bf16 planes; one task = eight consecutive keys of one column (a wavefront
+        // reads 64 consecutive floats of a row per instruction, and writes 16 bytes per lane and plane)
+        {
+            const int n_tasks = (n_pad / 8) * DV;
+            for (int t = tid; t < n_tasks; t += n_threads) {
+                const int col = t % DV, j = 8 * (t / DV);
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = (j + e < n) ? raw_s[(j + e) * DV + col] : 0.0f;
+                uint32_t up[4], lo[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) split_bf16_pair(x[2 * e2], x[2 * e2 + 1], up[e2], lo[e2]);
+                const int off = col * kVtStride + j;
+                *reinterpret_cast<uint4 *>(vth_s + off) = make_uint4(up[0], up[1], up[2], up[3]);
+                *reinterpret_cast<uint4 *>(vtl_s + off) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            }
+        }
+        __syncthreads();                             // planes ready; raw_s is free again
+        long u2 = u;
+        int j2 = j0 + kKeyChunk;
+        if (j2 >= Nk) {
+            u2 = u + gridDim.x;
+            j2 = 0;
+        }
+        const bool has_next = u2 < n_units;
+        if (has_next) {
+            issue_chunk(u2, j2, buf ^ 1);
+            if (j2 == 0) load_query(u2, qn);
+        }
+        const uint64_t *kc = kc_s[buf];
+        const int n_full = n & ~15;                  // whole steps first, then at most one masked step
+        for (int k0 = 0; k0 < n_full; k0 += 16) step(kc, k0, n, std::false_type{});
+        if (n_full < n) step(kc, n_full, n, std::true_type{});
+        if (j2 == 0) {                               // last chunk of the unit
+            const long bh = u / q_chunks;
+            __syncthreads();                         // every wavefront is through its steps: the planes become staging rows
+            write_outputs<DV>(acc, den, reinterpret_cast<uint8_t *>(&vt_s[0][0]) + wave * stage_bytes_per_wave<DV>(), out,
+                                     xq, xh, act_inv_scale, (int)(bh / H), (int)(bh % H), H, Nq, (int)(u % q_chunks), wave,
+                                     lane);
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[jt][r] = 0.0f;
+            den = 0.0f;
+        }
+        if (!has_next) break;
+        u = u2;
+        j0 = j2;
+        buf ^= 1;
+    }
 }
 
 // ---- the same attention with the scores on the matrix cores as well ------------------------------
@@ -374,13 +561,16 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mm_kernel(
     constexpr int KS = NBITS / 16;                 // MFMA steps of a score tile
     constexpr int kVtStride8 = kKeyChunk + 4;     // 264-byte V^T rows: the 8-byte operand reads of 32 columns cover the 64 banks once
     constexpr int KSTRIDE = NBITS + 8;             // bf16 elements per key row of signs (16-byte multiple, conflict-free)
-    __shared__ __attribute__((aligned(16))) uint16_t ksign_s[kKeyChunk * KSTRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t vth_s[DV * kVtStride8];   // V^T, upper bf16 term
-    __shared__ __attribute__((aligned(16))) uint16_t vtl_s[DV * kVtStride8];   // V^T, lower bf16 term
+    // one pool: the sign rows of the keys, then the two V^T planes; the epilogue stages the outputs from its start
+    constexpr int kSignBytes = kKeyChunk * KSTRIDE * 2, kPlaneBytes = DV * kVtStride8 * 2;
+    __shared__ __attribute__((aligned(16))) uint8_t pool_s[kSignBytes + 2 * kPlaneBytes];
+    uint16_t *ksign_s = reinterpret_cast<uint16_t *>(pool_s);
+    uint16_t *vth_s = reinterpret_cast<uint16_t *>(pool_s + kSignBytes);              // V^T, upper bf16 term
+    uint16_t *vtl_s = reinterpret_cast<uint16_t *>(pool_s + kSignBytes + kPlaneBytes);   // V^T, lower bf16 term
+    static_assert(sizeof(pool_s) >= kMaxWaves * stage_bytes_per_wave<DV>(), "the pool holds every wavefront's staging rows");
     __shared__ __attribute__((aligned(8))) TableEntry tab_s[NBITS + 1];
     __shared__ __attribute__((aligned(16))) uint4 sign_s[256];
-    __shared__ float den_s[kMaxWaves * 32];
-    static_assert(sizeof(ksign_s) >= kKeyChunk * W * 8, "the first pass keeps the raw key codes there");
+    static_assert(kSignBytes >= kKeyChunk * W * 8, "the first pass keeps the raw key codes there");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -493,9 +683,9 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mm_kernel(
                 const uint2 l0 = *reinterpret_cast<const uint2 *>(vtl_s + off), l1 = *reinterpret_cast<const uint2 *>(vtl_s + off + 8);
                 const v8bf vh = __builtin_bit_cast(v8bf, make_uint4(h0.x, h0.y, h1.x, h1.y));
                 const v8bf vl = __builtin_bit_cast(v8bf, make_uint4(l0.x, l0.y, l1.x, l1.y));
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vh, acc[jt], 0, 0, 0);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph, vl, acc[jt], 0, 0, 0);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl, vh, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, ph, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vl, ph, acc[jt], 0, 0, 0);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vh, pl, acc[jt], 0, 0, 0);
             }
         }
     };
@@ -524,8 +714,9 @@ __global__ __launch_bounds__(kMaxWaves *kWave) void hamming_mm_kernel(
         if (n_full < n) step(n_full, n, std::true_type{});
     }
 
-    write_outputs<DV>(acc, den, den_s, out, xq, xh, act_inv_scale, b, h, H, Nq, chunk, wave, lane,
-                      reinterpret_cast<uint8_t *>(vth_s), reinterpret_cast<uint8_t *>(vtl_s));
+    __syncthreads();                               // every wavefront is through its tiles: the pool becomes staging rows
+    write_outputs<DV>(acc, den, pool_s + wave * stage_bytes_per_wave<DV>(), out, xq, xh, act_inv_scale, b, h, H, Nq, chunk,
+                             wave, lane);
 }
 
 // Optional dump of the integer scores, one thread per (query, key) pair.
@@ -556,13 +747,51 @@ struct Launch {
     float c2;
     bool rowref;
     bool mm_scores;         // scores as sign dot products on the matrix cores (else XOR + popcount on the vector ALU)
+    bool pipeline;          // several units per workgroup, the next chunk in flight (popcount scores, no row reference)
+    long n_units;
     int8_t *xq;
     _Float16 *xh;
     float act_inv_scale;
 };
 
+// Workgroups of the pipelined kernel that fit the chip at once (what the LDS and the registers allow per CU,
+// times the CUs), asked from the runtime once per block size.
+template <int DV, int W>
+long pipeline_slots(int threads) {
+    static int per_cu[kMaxWaves + 1];          // by wavefronts per workgroup; 0 = not asked yet
+    static int n_cu = 0;
+    const int waves = threads / kWave;
+    if (n_cu == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+        n_cu = cus;
+    }
+    if (per_cu[waves] == 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, hamming_pipe_kernel<DV, W>, threads, 0) != hipSuccess || occ <= 0) {
+            (void)hipGetLastError();
+            occ = 1;
+        }
+        per_cu[waves] = occ;
+    }
+    return (long)per_cu[waves] * n_cu;
+}
+
 template <int DV, int W>
 void launch_hamming(const Launch &L) {
+    if constexpr (DV <= 64 && W <= 4) {
+        if (L.pipeline) {
+            const long slots = pipeline_slots<DV, W>((int)L.block.x);
+            const long wgs = L.n_units < slots ? L.n_units : slots;
+            hamming_pipe_kernel<DV, W><<<dim3((unsigned)wgs), L.block, 0, L.st>>>(L.q, L.k, L.v, L.out, L.H, L.Nq, L.Nk, L.q_chunks,
+                                                                                 L.c2, L.xq, L.xh, L.act_inv_scale, L.n_units);
+            return;
+        }
+    }
     // scores on the matrix cores on request, for codes up to 256 bits (the query's sign fragments live in registers)
     if constexpr (W <= 4) {
         if (L.mm_scores) {
@@ -650,6 +879,9 @@ extern "C" int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_
     // measured at the DeiT-Base shape: 38 us with popcount scores, 44 us with matrix-core scores (more LDS
     // traffic and MFMA time than the vector work it saves), so AUTO keeps the popcount
     L.mm_scores = (variant == SA_VARIANT_MFMA);
+    // AUTO: the pipelined popcount kernel where it is built (dv <= 64, nbits <= 256, no row reference)
+    L.pipeline = variant == SA_VARIANT_AUTO && !L.rowref && dv <= 64 && W <= 4;
+    L.n_units = blocks;
     SA_REQUIRE(variant != SA_VARIANT_MFMA || W <= 4, SA_ERR_UNSUPPORTED,
                "sa_hamming_attention: scores on the matrix cores need nbits <= 256 (got %d)", nbits);
     int rc;

@@ -221,8 +221,9 @@ def near_codes(seed, shape, nbits, max_flips):
     return codes
 
 
-@pytest.mark.parametrize("variant", [0, 1], ids=["popcount", "matrix-core"])
+@pytest.mark.parametrize("variant", [0, 1, 2], ids=["popcount", "matrix-core", "default"])
 @pytest.mark.parametrize("B,H,Nq,Nk,nbits,dv,scale,near", [
+    (2, 3, 70, 150, 128, 64, None, False),      # 64-wide heads: the default is the pipelined kernel here
     (2, 3, 70, 100, 128, 128, None, False),     # one ragged key chunk, c4 code width
     (1, 2, 40, 200, 64, 128, None, False),      # two key chunks, ragged tail (two passes over the keys)
     (1, 2, 300, 128, 128, 128, None, False),    # two query chunks

@@ -206,6 +206,38 @@ def test_hamming_attention_matches_oracle(sa, B, H, Nq, Nk, nbits, dv, scale):
         assert_close(host(o2), ref, ATTN_RTOL, ATTN_ATOL, "Hamming attention, variant %d" % variant)
 
 
+@pytest.mark.parametrize("B,H,Nq,Nk,nbits,dv", [
+    (50, 12, 40, 40, 128, 64),      # 600 units: more than fit the chip at once, so workgroups walk over several
+    (33, 12, 70, 150, 64, 64),      # two key chunks per unit, several units per workgroup, ragged tails
+    (40, 16, 33, 129, 256, 32),     # a chunk of one key; 256-bit codes; 32-wide heads
+    (3, 64, 300, 50, 128, 64),      # two query chunks per (batch, head): 384 units
+    (2, 3, 197, 197, 128, 64),      # fewer units than slots: one unit per workgroup
+    (9, 8, 100, 113, 128, 64),
+    (9, 8, 60, 272, 64, 64),        # three chunks, the last of 16 keys
+    (1, 1, 1, 1, 64, 32),
+])
+def test_hamming_pipeline_is_bit_identical_to_the_one_unit_kernel(sa, B, H, Nq, Nk, nbits, dv):
+    """What sa_hamming_attention runs by default (workgroups that walk over several (batch, head) units with the next
+    chunk of V and key codes in flight) against the kernel that takes one unit per workgroup: the same operations in
+    the same order, so all three output forms must agree bit for bit; the latter is checked against the oracle above,
+    and sampled (batch, head) pairs are checked against it here as well."""
+    q = wl.random_codes(21, (B, H, Nq), nbits)
+    k = wl.random_codes(22, (B, H, Nk), nbits)
+    v = np.random.default_rng([23, B, H, Nk, dv]).standard_normal((B, Nk, H, dv), dtype=np.float32)
+    scale = float(np.float32(1.0 / math.sqrt(nbits)))
+    dq, dk, dv_ = dev(q), dev(k), dev(v)
+    o_pipe, xq_pipe, xh_pipe = sa.sa_hamming_attention_fused(dq, dk, dv_, scale, nbits, 11.0, variant=2)
+    o_unit, xq_unit, xh_unit = sa.sa_hamming_attention_fused(dq, dk, dv_, scale, nbits, 11.0, variant=0)
+    assert torch.equal(o_pipe, o_unit) and torch.equal(xq_pipe, xq_unit) and torch.equal(xh_pipe, xh_unit)
+    # a second call into the same buffers (nothing of the first call's state may matter)
+    o_again, _, _ = sa.sa_hamming_attention_fused(dq, dk, dv_, scale, nbits, 11.0, variant=2, want_xq=False, want_xh=False)
+    assert torch.equal(o_again, o_unit)
+    got = host(o_pipe)
+    for b in sorted({0, B // 2, B - 1}):
+        ref = oracle.hamming_attention(q[b:b + 1], k[b:b + 1], v[b:b + 1], nbits, scale)
+        assert_close(got[b:b + 1], ref, ATTN_RTOL, ATTN_ATOL, "pipelined Hamming attention, batch %d" % b)
+
+
 # --------------------------------------------------------------- shift layer ----
 
 @pytest.mark.parametrize("variant", [0, 1])
