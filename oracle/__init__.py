@@ -331,6 +331,20 @@ def mlp_stage(x, logits, p):
     return combine(np.concatenate([out0, out1], axis=0), perm, gate)
 
 
+def moe_linear(x, logits, w4, w_half, act_inv_scale, out_scale):
+    """MoE form of one Linear layer (Sec. 4.1: the Linears of the attention module become Shift layers or MoEs;
+    Sec. 4.2: y = sum_i G(x) E_i(x) with one non-zero term).  x [T, K] fp32, logits [T, 2].  Expert 0 multiplies
+    (fp16 weights w_half [N, K] times the fp16 rounding of x, exact sums), expert 1 shifts (the int8 codes of
+    x * act_inv_scale times the shift weights w4, times out_scale).  Both experts are evaluated for every token and
+    the routed one is kept: the definition, not a schedule.  Returns y [T, N] fp64."""
+    x = _c(x, np.float32)
+    _, expert_of, _, gate = moe_dispatch(logits)
+    w = np.asarray(w_half, dtype=np.float16).astype(np.float64)
+    y_mult = round_to_half(x.astype(np.float64)) @ w.T
+    y_shift = np.float64(np.float32(out_scale)) * shift_linear(quantize_act(x, act_inv_scale), w4).astype(np.float64)
+    return gate[:, None] * np.where(expert_of[:, None] == 0, y_mult, y_shift)
+
+
 def block_forward(cfg, q, k, v, proj, scale, logits, p):
     """binarize -> (additive | Hamming) attention -> MLP / MoE.  Returns (O, y) in fp64."""
     qc = binarize(q, proj, cfg.nbits)
