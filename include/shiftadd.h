@@ -251,6 +251,27 @@ int sa_moe_dispatch_static(const float *logits, long T, int E, int32_t *perm, in
                            int32_t *counts, float *gate, void *stream);
 
 /*
+ * The MoE form of one Linear layer (Sec. 4.1: the Linear layers of the attention module become
+ * Shift layers or MoEs; Sec. 4.2: y = sum_i G(x) E_i(x), G = p_i * 1{p_i >= p_j}).  Top-1 routing
+ * by logits [T,2] between expert 0 (Mult: w_f16 [N,K] fp16 times xh, the fp16 form of the
+ * activations, fp32 accumulation) and expert 1 (Shift: w4 [N,K/2] packed 4-bit shift weights
+ * times xq, the int8 codes of the same activations, int32 accumulation, times out_scale):
+ *   y[t, :] = gate[t] * (xh[t, :] . W^T)                      t routed to expert 0
+ *   y[t, :] = gate[t] * out_scale * (xq[t, :] . Wshift^T)     t routed to expert 1
+ * xq [T,K] int8, xh [T,K] fp16, y [T,N] fp32, all device memory; every row of y is written once.
+ * expert_of_or_null [T] int32 and gate_or_null [T] fp32 receive the routing when given.  K % 32 == 0.
+ * variant as for sa_shift_linear (with SA_VARIANT_MFMA_PREPARED w4 points at prepared planes).
+ * The Shift rows are bit-exact up to the fp32 product with gate and out_scale; the Mult rows carry
+ * the rounding of fp32 accumulation.  Workspace (sa_moe_linear_workspace_bytes): routing lists and
+ * the decoded weight planes; nothing in it needs to be initialised.
+ */
+size_t sa_moe_linear_workspace_bytes(long T, int K, int N, int variant);
+int sa_moe_linear(const int8_t *xq, const void *xh, const float *logits, long T, int K, int N,
+                  const uint8_t *w4, const void *w_f16, float out_scale, float *y,
+                  int32_t *expert_of_or_null, float *gate_or_null, int variant, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
  * Forward value of the latency-aware load-balancing loss (Eq. 4):
  *   IMP_i  = alpha_i * sum_x p_i(x),   LOAD_i = alpha_i * sum_x q_i(x),   p = softmax(logits)
  *   q_i(x) = Phi((p_i(x) - max_{j != i} p_j(x)) / noise_std)     (normal noise on p_i as the proxy)

@@ -28,7 +28,7 @@ EXPORTS = [
     "sa_moe_balance_loss_workspace_bytes", "sa_moe_balance_loss", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
-    "sa_block_forward", "sa_layer_workspace_bytes", "sa_layer_forward",
+    "sa_block_forward", "sa_moe_linear_workspace_bytes", "sa_moe_linear", "sa_layer_workspace_bytes", "sa_layer_forward",
 ]
 
 
@@ -81,7 +81,7 @@ def load_library():
         for name in ("sa_moe_balance_loss_workspace_bytes", "sa_additive_attention_workspace_bytes", "sa_linear_attention_01_workspace_bytes", "sa_moe_dispatch_workspace_bytes",
                      "sa_shift_linear_workspace_bytes", "sa_shift_planes_bytes",
                      "sa_shift_mlp_workspace_bytes", "sa_mult_mlp_workspace_bytes",
-                     "sa_block_workspace_bytes", "sa_layer_workspace_bytes"):
+                     "sa_block_workspace_bytes", "sa_layer_workspace_bytes", "sa_moe_linear_workspace_bytes"):
             getattr(lib, name).restype = ctypes.c_size_t
         _lib = lib
     return _lib
@@ -363,6 +363,23 @@ def sa_moe_dispatch_static(logits, out=None):
     _check(lib.sa_moe_dispatch_static(_ptr(logits), _l(T), E, _ptr(perm), _ptr(expert_of), _ptr(counts), _ptr(gate),
                                       _stream()))
     return perm, expert_of, counts, gate
+
+
+def sa_moe_linear(xq, xh, logits, w4, w_half, out_scale, variant=SA_VARIANT_AUTO, y=None, want_routing=False,
+                  workspace=None):
+    """MoE form of one Linear layer: y [T, N] fp32 (and, on request, expert_of [T] int32 and gate [T] fp32)."""
+    lib = load_library()
+    T, K = xq.shape
+    N = w_half.shape[0]
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.float32, device=xq.device)
+    expert_of = torch.empty(T, dtype=torch.int32, device=xq.device) if want_routing else None
+    gate = torch.empty(T, dtype=torch.float32, device=xq.device) if want_routing else None
+    if workspace is None:
+        workspace = _workspace(lib.sa_moe_linear_workspace_bytes(_l(T), K, N, variant), xq.device)
+    _check(lib.sa_moe_linear(_ptr(xq), _ptr(xh), _ptr(logits), _l(T), K, N, _ptr(w4), _ptr(w_half), _f(out_scale), _ptr(y),
+                             _ptr(expert_of), _ptr(gate), variant, _ptr(workspace), _z(workspace.numel()), _stream()))
+    return (y, expert_of, gate) if want_routing else y
 
 
 def sa_moe_balance_loss(logits, alpha, noise_std):

@@ -48,6 +48,20 @@ __device__ inline void resolve_rows(const RowSel &sel, const int32_t *&rows, lon
 
 int validate_rows(const sa_rows *rows, RowSel *out);
 
+// One Linear layer on the rows an expert was given, gated and scattered (the two experts of sa_moe_linear):
+//   y[rows[i], :] = gate[rows[i]] * (xh[rows[i], :] . W^T)                      fp16 operands   (mult_mlp.hip)
+//   y[rows[i], :] = gate[rows[i]] * out_scale * (xq[rows[i], :] . Wshift^T)      int8 / 4-bit    (shift_linear.hip)
+// Arguments are checked by the caller; `planes` is shift_linear_rows_workspace_bytes(K, N, variant) bytes.
+int mult_linear_rows(const void *xh_all, const RowSel &sel, int K, int N, const void *w_f16, float *y, const float *gate,
+                     hipStream_t st);
+size_t shift_linear_rows_workspace_bytes(int K, int N, int variant);
+int shift_linear_rows(const int8_t *xq_all, const RowSel &sel, int K, int N, const uint8_t *w4, float out_scale, float *y,
+                      const float *gate, int variant, void *planes, hipStream_t st);
+// The routing of sa_moe_dispatch without its argument checks (moe.hip).
+size_t moe_dispatch_scratch_bytes(long T, int E);
+int moe_dispatch_launch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of, int32_t *counts, float *gate,
+                        void *scratch, hipStream_t st);
+
 // Hash pre-pass on the matrix cores with exact fallback (binarize_mfma.hip).
 bool binarize_mfma_supported(int d, int nbits);
 int launch_binarize_mfma(const float *x0, const float *x1_or_null, const float *proj, uint64_t *codes0,

@@ -440,6 +440,12 @@ int dispatch_check(const char *who, const float *logits, long T, int E, int32_t 
 
 extern "C" size_t sa_moe_dispatch_workspace_bytes(long T, int E) { return dispatch_scratch_bytes(T, E); }
 
+size_t sa::moe_dispatch_scratch_bytes(long T, int E) { return dispatch_scratch_bytes(T, E); }
+int sa::moe_dispatch_launch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of, int32_t *counts, float *gate,
+                            void *scratch, hipStream_t st) {
+    return dispatch_launch(logits, T, E, perm, expert_of, counts, gate, scratch, st);
+}
+
 extern "C" int sa_moe_dispatch(const float *logits, long T, int E, int32_t *perm, int32_t *expert_of,
                                int32_t *counts, float *gate, void *workspace, size_t workspace_bytes,
                                void *stream) {
@@ -576,4 +582,71 @@ extern "C" int sa_moe_balance_loss(const float *logits, long T, int E, const flo
     if (rc != SA_OK) return rc;
     balance_final_kernel<<<dim3(1), dim3(64), 0, st>>>(partial, n_blocks, E, alpha, losses, sums_or_null);
     return sa::check_launch("sa_moe_balance_loss(final)");
+}
+
+// ---- the MoE form of one Linear layer -----------------------------------------------------------------
+// Sec. 4.1 turns the Linear layers of the attention module into Shift layers or into MoEs; this is the MoE:
+// top-1 routing between a Mult expert (fp16 weights, fp16 activations) and a Shift expert (4-bit shift weights,
+// int8 activations), each a single layer, y[t, :] = gate[t] * E_i(x[t, :]) (Sec. 4.2).  Three launches: the
+// routing, then one tiled GEMM per expert over the rows it was given (gathered by row id on the way into LDS,
+// scattered with the gate on the way out), plus the decode of the shift weights where the variant needs one.
+namespace {
+
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct MoeLinearLayout {
+    size_t perm, expert_of, counts, gate, scratch, planes, total;
+};
+
+MoeLinearLayout moe_linear_layout(long T, int K, int N, int variant) {
+    MoeLinearLayout L;
+    size_t off = 0;
+    L.perm = off; off += up256((size_t)T * 4);
+    L.expert_of = off; off += up256((size_t)T * 4);
+    L.counts = off; off += 256;
+    L.gate = off; off += up256((size_t)T * 4);
+    L.scratch = off; off += up256(dispatch_scratch_bytes(T, 2));
+    L.planes = off; off += up256(sa::shift_linear_rows_workspace_bytes(K, N, variant));
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+extern "C" size_t sa_moe_linear_workspace_bytes(long T, int K, int N, int variant) {
+    if (T <= 0 || K <= 0 || N <= 0 || K % 32 != 0 || variant < 0 || variant > 3) return 0;
+    return moe_linear_layout(T, K, N, variant).total;
+}
+
+extern "C" int sa_moe_linear(const int8_t *xq, const void *xh, const float *logits, long T, int K, int N, const uint8_t *w4,
+                             const void *w_f16, float out_scale, float *y, int32_t *expert_of_or_null, float *gate_or_null,
+                             int variant, void *workspace, size_t workspace_bytes, void *stream) {
+    sa::clear_error();
+    SA_REQUIRE(T >= 0 && K > 0 && N > 0, SA_ERR_INVALID, "sa_moe_linear: T < 0, or K or N not positive");
+    SA_REQUIRE(variant >= 0 && variant <= 3, SA_ERR_INVALID, "sa_moe_linear: unknown variant %d", variant);
+    SA_REQUIRE(K % 32 == 0, SA_ERR_SHAPE, "sa_moe_linear: K (%d) must be a multiple of 32", K);
+    SA_REQUIRE(K <= 131072, SA_ERR_SHAPE, "sa_moe_linear: K too large for int32 accumulation");
+    SA_REQUIRE(T < (1L << 31), SA_ERR_SHAPE, "sa_moe_linear: T >= 2^31");
+    if (T == 0) return SA_OK;
+    SA_REQUIRE(xq && xh && logits && w4 && w_f16 && y, SA_ERR_INVALID, "sa_moe_linear: NULL buffer");
+    SA_REQUIRE(sa::aligned16(xq) && sa::aligned16(xh) && sa::aligned16(logits) && sa::aligned16(w4) && sa::aligned16(w_f16) &&
+                   sa::aligned16(y) && sa::aligned16(expert_of_or_null) && sa::aligned16(gate_or_null) &&
+                   sa::aligned16(workspace),
+               SA_ERR_ALIGN, "sa_moe_linear: pointers must be 16-byte aligned");
+    const MoeLinearLayout L = moe_linear_layout(T, K, N, variant);
+    SA_REQUIRE(workspace != nullptr && workspace_bytes >= L.total, SA_ERR_WORKSPACE,
+               "sa_moe_linear: workspace of %zu bytes needed, %zu given", L.total, workspace_bytes);
+    hipStream_t st = sa::as_stream(stream);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + L.perm);
+    int32_t *expert_of = expert_of_or_null ? expert_of_or_null : reinterpret_cast<int32_t *>(ws + L.expert_of);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
+    float *gate = gate_or_null ? gate_or_null : reinterpret_cast<float *>(ws + L.gate);
+    int rc = dispatch_launch(logits, T, 2, perm, expert_of, counts, gate, ws + L.scratch, st);
+    if (rc != SA_OK) return rc;
+    // every token belongs to exactly one expert, so the two scatters write every row of y exactly once
+    const sa::RowSel mult_rows{perm, counts, 0, T}, shift_rows{perm, counts, 1, T};
+    rc = sa::mult_linear_rows(xh, mult_rows, K, N, w_f16, y, gate, st);
+    if (rc != SA_OK) return rc;
+    return sa::shift_linear_rows(xq, shift_rows, K, N, w4, out_scale, y, gate, variant, ws + L.planes, st);
 }

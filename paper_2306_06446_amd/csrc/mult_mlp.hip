@@ -155,6 +155,23 @@ int check_mult_args(const void *x, const sa_rows *rows, sa::RowSel *sel, int E, 
 
 }  // namespace
 
+int sa::mult_linear_rows(const void *xh_all, const RowSel &sel, int K, int N, const void *w_f16, float *y, const float *gate,
+                         hipStream_t st) {
+    sa::GemmArgs g;
+    g.a = xh_all;
+    g.gather_a = true;
+    g.b[0] = w_f16;
+    g.b[1] = nullptr;
+    g.sel = sel;
+    g.K = K;
+    g.N = N;
+    sa::Epilogue e;
+    e.yf = y;
+    e.gate = gate;
+    MultStore<sa::kEpiScatterF32> store(e);
+    return sa::launch_gemm<sa::F16Traits>(g, store, st, "sa_moe_linear(mult expert)");
+}
+
 extern "C" int sa_mult_mlp_f16(const float *x, const sa_rows *rows, int E, int hid, const void *w1_f16,
                                const void *w2_f16, float *out_or_null, float *y_or_null,
                                const float *gate_or_null, int stages, void *workspace,

@@ -553,6 +553,21 @@ extern "C" int sa_requant_lut(const int32_t *y, long n, float s, const int8_t *l
 }
 
 // workspace layout of sa_shift_mlp: hidden int8 [max_rows, hid] | planes of w1 | planes of w2
+size_t sa::shift_linear_rows_workspace_bytes(int K, int N, int variant) {
+    return (variant == SA_VARIANT_VALU || variant == SA_VARIANT_MFMA_PREPARED) ? 0 : planes_bytes(K, N);
+}
+
+int sa::shift_linear_rows(const int8_t *xq_all, const RowSel &sel, int K, int N, const uint8_t *w4, float out_scale, float *y,
+                          const float *gate, int variant, void *planes, hipStream_t st) {
+    SA_REQUIRE((sel.max_rows + kValuRows - 1) / kValuRows < 65536 || variant != SA_VARIANT_VALU, SA_ERR_SHAPE,
+               "sa_moe_linear: too many rows for the VALU variant in one call");
+    sa::Epilogue e;
+    e.yf = y;
+    e.gate = gate;
+    e.out_scale = out_scale;
+    return launch_shift<sa::kEpiScatterI32>(variant, xq_all, w4, sel, true, K, N, e, planes, st);
+}
+
 extern "C" size_t sa_shift_mlp_workspace_bytes(long max_rows, int E, int hid) {
     if (max_rows <= 0 || hid <= 0 || E <= 0) return 0;
     const size_t hidden = (((size_t)max_rows * hid) + 255) / 256 * 256;

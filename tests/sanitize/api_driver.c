@@ -67,6 +67,13 @@ int main(void) {
     EXPECT(sa_moe_dispatch_static(fake, 100, 9, fake, fake, fake, fake, NULL), SA_ERR_SHAPE);
     EXPECT(sa_moe_balance_loss(fake, 0, 2, fake, 0.1f, fake, NULL, fake, 1024, NULL), SA_ERR_INVALID);
     EXPECT(sa_moe_balance_loss(fake, 10, 2, fake, -1.0f, fake, NULL, fake, 1024, NULL), SA_ERR_INVALID);
+    /* the MoE form of a Linear layer */
+    EXPECT(sa_moe_linear(fake, fake, fake, 10, 48, 8, fake, fake, 1.0f, fake, NULL, NULL, 1, fake, 1 << 20, NULL), SA_ERR_SHAPE);
+    EXPECT(sa_moe_linear(fake, fake, NULL, 10, 64, 8, fake, fake, 1.0f, fake, NULL, NULL, 1, fake, 1 << 20, NULL), SA_ERR_INVALID);
+    EXPECT(sa_moe_linear(fake, fake, fake, 10, 64, 8, fake, fake, 1.0f, fake, NULL, NULL, 1, fake, 16, NULL), SA_ERR_WORKSPACE);
+    EXPECT(sa_moe_linear(fake, fake, fake, 10, 64, 8, fake, fake, 1.0f, fake, NULL, NULL, 9, fake, 1 << 20, NULL), SA_ERR_INVALID);
+    EXPECT(sa_moe_linear(fake, fake, fake, 0, 64, 8, fake, fake, 1.0f, fake, NULL, NULL, 1, NULL, 0, NULL), SA_OK);
+    if (sa_moe_linear_workspace_bytes(10, 48, 8, 1) != 0 || sa_moe_linear_workspace_bytes(10, 64, 8, 1) < 2 * 8 * 64) ++failures;
     /* experts and row movement */
     sa_rows rows = {NULL, fake, 0, 10};                      /* counts without a list */
     EXPECT(sa_shift_mlp(fake, &rows, 64, 64, fake, fake, 1.0f, fake, fake, NULL, NULL, 1.0f, 1, 3, fake, 1 << 20, NULL), SA_ERR_INVALID);

@@ -710,3 +710,52 @@ def test_block_forward_on_two_streams_in_turn_is_bit_identical(sa):
         torch.cuda.synchronize()
         for blk, (o_ref, y_ref) in zip(blocks, refs):
             assert torch.equal(blk.o, o_ref) and torch.equal(blk.y, y_ref), "rep %d" % rep
+
+
+# ------------------------------------------------------- MoE form of a Linear ----
+
+@pytest.mark.parametrize("variant", [0, 1, 3], ids=["valu", "mfma", "prepared"])
+@pytest.mark.parametrize("T,K,N,shift_frac", [
+    (1576, 768, 768, 0.7),        # a DeiT-Base attention Linear on 8 images
+    (300, 192, 576, 0.5),         # DeiT-Tiny Q/K/V width, ragged row tiles
+    (777, 160, 160, 0.9),         # K not a multiple of 64: the padded last stage
+    (64, 32, 20, 0.0),            # every token to the Mult expert; N not a multiple of 4 chunks
+    (65, 64, 36, 1.0),            # every token to the Shift expert
+    (1, 32, 4, 0.5),
+])
+def test_moe_linear_matches_oracle(sa, variant, T, K, N, shift_frac):
+    """Sec. 4.1's MoE option for a Linear layer.  Routing and gate bit-exact / 1e-6; Shift rows are exact integers
+    times two fp32 factors (relative 3e-7 covers the two roundings); Mult rows carry fp32 accumulation of fp16
+    products (2e-3 relative to the row scale, as for the Mult expert of the MLP)."""
+    g = np.random.default_rng([17, T, K, N])
+    x = (g.standard_normal((T, K)) * 2).astype(np.float32)
+    # logits whose second entry exceeds the first for about shift_frac of the tokens
+    margin = g.standard_normal(T).astype(np.float32)
+    cut = np.quantile(margin, 1.0 - shift_frac) if 0.0 < shift_frac < 1.0 else (np.inf if shift_frac == 0.0 else -np.inf)
+    base = g.standard_normal(T).astype(np.float32)
+    logits = np.stack([base, base + np.where(margin > cut, 1.0, -1.0) * (0.1 + np.abs(margin))], axis=1).astype(np.float32)
+    neg = g.integers(0, 2, size=(N, K), dtype=np.uint8)
+    e = g.integers(0, 8, size=(N, K), dtype=np.uint8)
+    w4 = wl.pack_w4(neg, e)
+    w_half = (g.standard_normal((N, K)) / np.sqrt(K)).astype(np.float16)
+    inv, out_scale = 20.0, 1.0 / (128.0 * K)
+    ref = oracle.moe_linear(x, logits, w4, w_half, inv, out_scale)
+    _, expert_ref, counts_ref, gate_ref = oracle.moe_dispatch(logits)
+    xq = dev(oracle.quantize_act(x, inv))
+    xh = dev(x.astype(np.float16))
+    d_w = dev(w4)
+    if variant == 3:
+        d_w = sa.sa_shift_planes_prepare(d_w)
+    y, expert_of, gate = sa.sa_moe_linear(xq, xh, dev(logits), d_w, dev(w_half), out_scale, variant=variant, want_routing=True)
+    assert np.array_equal(host(expert_of), expert_ref)
+    assert np.allclose(host(gate), gate_ref, rtol=1e-6, atol=0)
+    got = host(y).astype(np.float64)
+    shift_rows, mult_rows = expert_ref == 1, expert_ref == 0
+    assert int(shift_rows.sum()) == int(counts_ref[1])
+    if shift_rows.any():
+        err = np.abs(got[shift_rows] - ref[shift_rows])
+        assert np.all(err <= 3e-7 * np.abs(ref[shift_rows]) + 1e-30), "Shift rows: %g" % err.max()
+    if mult_rows.any():
+        rms = float(np.sqrt(np.mean(ref[mult_rows] ** 2)))
+        err = np.abs(got[mult_rows] - ref[mult_rows])
+        assert np.all(err <= 2e-3 * np.abs(ref[mult_rows]) + 1e-3 * rms), "Mult rows: %g (rms %g)" % (err.max(), rms)
