@@ -545,6 +545,32 @@ def bench_experts(args, sa, wl, torch, np, cfg):
         us["concurrent_cu_split"] = _time_us(torch, concurrent, args.steps)
         us["cu_split"] = {"mult_cus": n_m, "shift_cus": n_cu - n_m}
     us = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in us.items()}
+    # For scale only, never part of the path: the vendor library's GEMM behind torch at the shapes of the four expert
+    # layers, on compact operands (no gather, no activation, no gate, no scatter), fp16 for the Mult expert and ONE
+    # int8 plane with int32 output for the Shift expert (the library's own layers run two planes each).
+    library = {}
+    try:
+        n_m, n_s = counts[0], (counts[1] + 7) // 8 * 8
+        for name, M, K, N, kind in (("mult_fc1_f16", n_m, E, hid, "f16"), ("mult_fc2_f16", n_m, hid, E, "f16"),
+                                    ("shift_fc1_one_int8_plane", n_s, E, hid, "i8"), ("shift_fc2_one_int8_plane", n_s, hid, E, "i8")):
+            if M == 0:
+                continue
+            if kind == "f16":
+                a = torch.randn((M, K), device="cuda", dtype=torch.float16)
+                b = (torch.randn((N, K), device="cuda", dtype=torch.float16) / 32).t()
+                o = torch.empty((M, N), device="cuda", dtype=torch.float16)
+                fn = lambda a=a, b=b, o=o: torch.matmul(a, b, out=o)
+                peak = 2.5e15
+            else:
+                a = torch.randint(-127, 128, (M, K), device="cuda", dtype=torch.int8)
+                b = torch.randint(-127, 128, (N, K), device="cuda", dtype=torch.int8).t()
+                fn = lambda a=a, b=b: torch._int_mm(a, b)
+                peak = 5.0e15
+            t = _time_us_graph(torch, fn)
+            library[name] = {"M": M, "K": K, "N": N, "us": round(t, 2), "frac_of_peak": round(2.0 * M * K * N / (t * 1e-6) / peak, 3)}
+            del a, b
+    except Exception as exc:      # noqa: BLE001 - a reference that is not available is left out
+        library["unavailable"] = str(exc)[:200]
     out = {"metric": "MoE MLP tokens/s (Mult and Shift expert after the dispatch) at 1 GPU",
            "value": round(T / (us["sequential"] * 1e-6), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": 3,
            "ms_per_step": round(us["sequential"] * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -552,6 +578,7 @@ def bench_experts(args, sa, wl, torch, np, cfg):
            "config": {"workload": cfg.name + "-experts", "T": T, "E": E, "hid": hid, "tokens_mult": counts[0], "tokens_shift": counts[1],
                       "shift_variant": var},
            "experts_us": us, "modularized_us": max(us["mult_alone"], us["shift_alone"]),
+           "vendor_library_gemm_for_scale": library,
            "concurrent_output_identical": same,
            "note": "sequential = both experts on one stream (what sa_block_forward does); concurrent = two streams forked after "
                    "the dispatch and joined; modularized = the slower expert alone, the figure the paper's tables report for "
