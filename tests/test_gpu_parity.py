@@ -214,6 +214,7 @@ def test_hamming_attention_matches_oracle(sa, B, H, Nq, Nk, nbits, dv, scale):
     (2, 3, 197, 197, 128, 64),      # fewer units than slots: one unit per workgroup
     (9, 8, 100, 113, 128, 64),
     (9, 8, 60, 272, 64, 64),        # three chunks, the last of 16 keys
+    (6, 16, 50, 140, 256, 64),      # 256-bit codes at 64-wide heads
     (1, 1, 1, 1, 64, 32),
 ])
 def test_hamming_pipeline_is_bit_identical_to_the_one_unit_kernel(sa, B, H, Nq, Nk, nbits, dv):
@@ -721,6 +722,7 @@ def test_block_forward_on_two_streams_in_turn_is_bit_identical(sa):
     (777, 160, 160, 0.9),         # K not a multiple of 64: the padded last stage
     (64, 32, 20, 0.0),            # every token to the Mult expert; N not a multiple of 4 chunks
     (65, 64, 36, 1.0),            # every token to the Shift expert
+    (40000, 64, 32, 0.6),         # more tokens than the one-launch routing takes
     (1, 32, 4, 0.5),
 ])
 def test_moe_linear_matches_oracle(sa, variant, T, K, N, shift_frac):
