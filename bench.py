@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--additive-valu", action="store_true",
                     help="linear attention: run the sign-select-and-accumulate kernels on the vector ALU instead of the "
                          "matrix cores (the measured alternative; per-kernel timings and profiles of both back the choice)")
+    ap.add_argument("--probe", action="store_true",
+                    help="no workload: a register-only loop of matrix instructions (sa_probe_mfma) on every CU, to read off the "
+                         "rate and the shader clock the matrix cores sustain with low-toggle, random and Shift-layer-like operands")
     ap.add_argument("--sweep", action="store_true",
                     help="kernel sweep over pyramid-ViT stage shapes at batch 1 and 32: the Add kernels (K^T V, Q(K^T V)) and "
                          "the Shift linear layers, each beside a dense fp32 library GEMM of the same contraction")
@@ -167,6 +170,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     sa.load_library()
+    if args.probe:
+        return bench_probe(args, sa, torch)
     if args.sweep:
         return bench_sweep(args, sa, wl, torch, np)
     if args.config == "c3":
@@ -585,6 +590,50 @@ def bench_experts(args, sa, wl, torch, np, cfg):
                    "experts counted as perfectly parallel",
            "roofline": None, "cpu_baseline": None}
     print(json.dumps(out))
+
+
+def bench_probe(args, sa, torch):
+    """What the matrix cores sustain before any kernel design enters: sa_probe_mfma runs 8 independent accumulator
+    chains per wavefront, 4 wavefronts per workgroup, operands in registers, nothing else.  Rate from HIP events
+    around one launch; clock = shader cycles / 100 MHz wall ticks of workgroup 0's loop, read inside the kernel."""
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    iters = 20000
+    out = torch.zeros(4, dtype=torch.int64, device="cuda")
+    rows = []
+    cases = [("int8 32x32x32", 0, 65536.0, 5.0e15, [(0, "one non-zero element per register"), (1, "random bits"),
+                                                    (2, "Shift-layer-like: random int8 x powers of two / 7/8 zeros")]),
+             ("fp16 32x32x16", 1, 32768.0, 2.5e15, [(0, "one non-zero element per register"), (1, "random finite halves")]),
+             ("bf16 32x32x16", 2, 32768.0, 2.5e15, [(0, "one non-zero element per register"), (1, "random finite values")])]
+    for name, kind, ops, peak, modes in cases:
+        for operands, what in modes:
+            for wgs in (1, n_cu // 8, n_cu, 2 * n_cu):
+                for _ in range(2):                    # the first launch warms the clocks of this case
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    sa.sa_probe_mfma(kind, operands, wgs, iters, out=out)
+                    e1.record()
+                    torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                cyc, ticks = int(out[0]), int(out[1])
+                n_inst = wgs * 4 * iters * 8
+                rate = n_inst * ops / (ms * 1e-3)
+                rows.append({"instruction": name, "operands": what, "workgroups": wgs, "ms": round(ms, 3),
+                             "rate_pops": round(rate / 1e15, 3), "frac_of_published_peak": round(rate / peak, 3),
+                             "shader_mhz": round(cyc / ticks * 100.0, 0) if ticks else None,
+                             "cycles_per_instruction_of_a_wavefront": round(cyc / (iters * 8), 1)})
+    print("| instruction | operands | workgroups | P op/s | of peak | MHz | cycles per MFMA of a wavefront |", file=sys.stderr)
+    print("|---|---|---|---|---|---|---|", file=sys.stderr)
+    for r in rows:
+        print("| %s | %s | %d | %.2f | %.2f | %s | %s |" % (r["instruction"], r["operands"], r["workgroups"], r["rate_pops"],
+                                                          r["frac_of_published_peak"], r["shader_mhz"],
+                                                          r["cycles_per_instruction_of_a_wavefront"]), file=sys.stderr)
+    like = [r for r in rows if r["operands"].startswith("Shift") and r["workgroups"] == n_cu][0]
+    out_line = {"metric": "int8 matrix-instruction rate sustained by a register-only loop on all CUs, Shift-layer-like operands",
+                "value": like["rate_pops"] * 1e3, "unit": "TOP/s", "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": like["ms"],
+                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+                "config": {"workload": "matrix-core-probe", "compute_units": n_cu, "iterations": iters},
+                "probe": rows, "roofline": None, "cpu_baseline": None}
+    print(json.dumps(out_line))
 
 
 # Stage shapes of a small pyramid ViT at 224 x 224 input (tokens per image, embedding width, heads, MLP ratio): the

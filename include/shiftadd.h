@@ -50,6 +50,21 @@ extern "C" {
 #define SA_VARIANT_MFMA_PREPARED 3 /* shift layers only: as MFMA, but the weight pointers
                                       hold planes made by sa_shift_planes_prepare         */
 
+/*
+ * Measurement helper, not a step of the path: a register-only loop of matrix instructions (no memory
+ * traffic), 4 wavefronts per workgroup, 8 * iters instructions per wavefront, so that a caller can
+ * read off the instruction rate and the shader clock the matrix cores sustain (the peaks the roofline
+ * of this library is priced against are the published ones; this shows what part of them is reachable).
+ *   kind      0 = int8 32x32x32 (65536 operations each), 1 = fp16 32x32x16, 2 = bf16 32x32x16 (32768)
+ *   operands  0 = one non-zero element per register, 1 = random bits, 2 = (int8) random activations
+ *             against powers of two and a plane that is 7/8 zeros, as in a Shift layer
+ *   out       device memory, 3 x uint64, 16-byte aligned: [0] shader cycles and [1] ticks of the 100 MHz
+ *             wall clock that the loop of workgroup 0 took ([2] is scratch)
+ * The caller times the launch (events on `stream`) for the rate.
+ */
+int sa_probe_mfma(int kind, int operands, int workgroups, int iters, unsigned long long *out,
+                  void *stream);
+
 int sa_version(void);
 /* Host string describing the last error returned on this thread ("" if none). */
 const char *sa_last_error(void);

@@ -28,7 +28,7 @@ EXPORTS = [
     "sa_moe_balance_loss_workspace_bytes", "sa_moe_balance_loss", "sa_quantize_act", "sa_quantize_act_half", "sa_requant_lut",
     "sa_shift_mlp_workspace_bytes", "sa_shift_mlp", "sa_mult_mlp_workspace_bytes",
     "sa_mult_mlp_f16", "sa_mult_mlp_f16_half", "sa_gather_rows", "sa_combine_rows", "sa_block_workspace_bytes",
-    "sa_block_forward", "sa_moe_linear_workspace_bytes", "sa_moe_linear", "sa_layer_workspace_bytes", "sa_layer_forward",
+    "sa_block_forward", "sa_moe_linear_workspace_bytes", "sa_moe_linear", "sa_probe_mfma", "sa_layer_workspace_bytes", "sa_layer_forward",
 ]
 
 
@@ -122,6 +122,15 @@ def _rows(rows=None, counts=None, expert=0, max_rows=0):
 
 def _workspace(nbytes, device):
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def sa_probe_mfma(kind, operands, workgroups, iters, out=None):
+    """Register-only matrix-instruction loop (measurement helper): returns the 3 x uint64 device tensor
+    [shader cycles, 100 MHz wall ticks, scratch] of workgroup 0."""
+    if out is None:
+        out = torch.zeros(4, dtype=torch.int64, device="cuda")
+    _check(load_library().sa_probe_mfma(kind, operands, workgroups, iters, _ptr(out), _stream()))
+    return out
 
 
 def sa_version():

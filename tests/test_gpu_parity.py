@@ -761,3 +761,17 @@ def test_moe_linear_matches_oracle(sa, variant, T, K, N, shift_frac):
         rms = float(np.sqrt(np.mean(ref[mult_rows] ** 2)))
         err = np.abs(got[mult_rows] - ref[mult_rows])
         assert np.all(err <= 2e-3 * np.abs(ref[mult_rows]) + 1e-3 * rms), "Mult rows: %g (rms %g)" % (err.max(), rms)
+
+
+# ------------------------------------------------------------ measurement helper ----
+
+def test_probe_runs_and_reports_its_clock(sa):
+    """sa_probe_mfma is not a step of the path; the check is that it runs, takes the time its instruction count
+    implies within wide bounds, and reports a plausible shader clock."""
+    out = sa.sa_probe_mfma(0, 2, 8, 2000)
+    torch.cuda.synchronize()
+    cycles, ticks = int(out[0]), int(out[1])
+    assert cycles > 2000 * 8 * 16 and ticks > 0                      # at least 16 cycles per instruction
+    assert 500.0 < cycles / ticks * 100.0 < 3500.0                    # MHz
+    with pytest.raises(sa.SAError):
+        sa.sa_probe_mfma(1, 2, 8, 10)                                 # Shift-like operands are int8 only
