@@ -159,10 +159,13 @@ int sa_hamming_attention(const uint64_t *q_codes, const uint64_t *k_codes, const
  * codes sa_quantize_act(out, act_inv_scale) would give, and xh_or_null fp16 [B*Nq, H*dv],
  * out rounded to nearest.  Either may be NULL, and so may `out` when one of them is given
  * (a consumer that reads only the quantised form saves the fp32 write).
- * variant: SA_VARIANT_VALU computes the scores by XOR + popcount on the vector ALU;
- * SA_VARIANT_MFMA as the dot product of the +-1 sign vectors on the matrix cores (the same
- * integers, nbits <= 256); SA_VARIANT_AUTO (what sa_hamming_attention uses) takes the
- * faster one, which at the measured shapes is the popcount. */
+ * variant: SA_VARIANT_VALU computes the scores by XOR + popcount on the vector ALU, one
+ * (batch, head, 256 queries) unit per workgroup; SA_VARIANT_MFMA as the dot product of the
+ * +-1 sign vectors on the matrix cores (the same integers, nbits <= 256); SA_VARIANT_AUTO
+ * (what sa_hamming_attention uses) is the popcount form again, for dv <= 64, nbits <= 256 and
+ * scales that need no per-row reference as a launch whose workgroups walk over several units
+ * with the next chunk of V and key codes loading meanwhile (bit-identical to
+ * SA_VARIANT_VALU), else as SA_VARIANT_VALU. */
 int sa_hamming_attention_fused(const uint64_t *q_codes, const uint64_t *k_codes, const float *v,
                                float *out, int B, int H, int Nq, int Nk, int nbits, int dv,
                                float scale, int16_t *scores_or_null, int8_t *xq_or_null,
