@@ -122,3 +122,64 @@ def test_full_size_layer_on_sampled_batches(sa, cfg, batches):
         err_branches = float(np.linalg.norm((y[rows] - x[rows]) - (r["y"] - x[rows])) / np.linalg.norm(r["y"] - x[rows]))
         print("layer %s batch %d: output error %.3g, both branches %.3g" % (cfg.name, b, err, err_branches))
         assert err < 1e-2 and err_branches < 3e-2
+
+
+def test_full_size_hamming_pipeline_equals_the_one_unit_kernel(sa):
+    """Config-4 attention as bench.py launches it (768 units on 512 workgroups: half of them walk over two units):
+    all three output forms bit-identical to the one-unit-per-workgroup kernel, and sampled batch elements
+    against the oracle."""
+    import torch
+    cfg = wl.C4
+    q, k, v = wl.qkv(cfg)
+    pr, scale, p = wl.proj(cfg), wl.attention_scale(cfg), wl.mlp_params(cfg)
+    qc, kc = sa.sa_binarize_pair(dev(q), dev(k), dev(pr), cfg.nbits)
+    dv_ = dev(v)
+    o2, xq2, xh2 = sa.sa_hamming_attention_fused(qc, kc, dv_, scale, cfg.nbits, p.act_inv_scale, variant=2)
+    o0, xq0, xh0 = sa.sa_hamming_attention_fused(qc, kc, dv_, scale, cfg.nbits, p.act_inv_scale, variant=0)
+    assert torch.equal(o2, o0) and torch.equal(xq2, xq0) and torch.equal(xh2, xh0)
+    got, hq, hk = host(o2), host(qc), host(kc)
+    for b in (0, 40, 63):
+        ref = oracle.hamming_attention(hq[b:b + 1], hk[b:b + 1], v[b:b + 1], cfg.nbits, scale)
+        assert_close(got[b:b + 1], ref, ATTN_RTOL, ATTN_ATOL, "Hamming attention, batch %d" % b)
+
+
+def test_full_size_moe_linear_on_sampled_tokens(sa):
+    """The MoE form of a DeiT-Base attention Linear on all 12608 tokens of config 4 (70 % to the Shift expert):
+    the routing of every token, and the outputs of sampled tokens, against the oracle (a token's row depends on
+    its own activations and logits only)."""
+    T, K, N = wl.C4.T, 768, 768
+    g = np.random.default_rng([19, T])
+    x = (g.standard_normal((T, K)) * 1.5).astype(np.float32)
+    logits = wl.router_logits(wl.C4)
+    neg = g.integers(0, 2, size=(N, K), dtype=np.uint8)
+    e = g.integers(0, 8, size=(N, K), dtype=np.uint8)
+    w4 = wl.pack_w4(neg, e)
+    w_half = (g.standard_normal((N, K)) / np.sqrt(K)).astype(np.float16)
+    inv, out_scale = 25.0, 1.0 / (128.0 * K)
+    y, expert_of, gate = sa.sa_moe_linear(dev(oracle.quantize_act(x, inv)), dev(x.astype(np.float16)), dev(logits), dev(w4),
+                                          dev(w_half), out_scale, variant=1, want_routing=True)
+    _, expert_ref, counts_ref, gate_ref = oracle.moe_dispatch(logits)
+    assert np.array_equal(host(expert_of), expert_ref)
+    assert np.allclose(host(gate), gate_ref, rtol=1e-6, atol=0)
+    tokens = np.sort(g.choice(T, size=400, replace=False))
+    ref = oracle.moe_linear(x[tokens], logits[tokens], w4, w_half, inv, out_scale)
+    got = host(y).astype(np.float64)[tokens]
+    shift_rows = expert_ref[tokens] == 1
+    err = np.abs(got - ref)
+    assert shift_rows.any() and (~shift_rows).any()
+    assert np.all(err[shift_rows] <= 3e-7 * np.abs(ref[shift_rows]) + 1e-30), "Shift rows: %g" % err[shift_rows].max()
+    rms = float(np.sqrt(np.mean(ref[~shift_rows] ** 2)))
+    assert np.all(err[~shift_rows] <= 2e-3 * np.abs(ref[~shift_rows]) + 1e-3 * rms), "Mult rows: %g" % err[~shift_rows].max()
+
+
+def test_full_size_narrow_shift_layer_on_sampled_rows(sa):
+    """A stage-1 layer of a pyramid ViT at batch 32 (100352 rows, K = 32: half a 64-byte stage, the padded last
+    stage of the matrix-core variants): sampled rows, the first and the last ones included, bit-exact."""
+    M, K, N = 100352, 32, 256
+    w4 = wl.shift_weights(3, 8, N, K)
+    x = wl.int8_activations(3, M, K, extra=8)
+    rows = np.unique(np.concatenate([np.arange(300), np.arange(M - 300, M), np.random.default_rng(4).choice(M, 2000, replace=False)]))
+    ref = oracle.shift_linear(x[rows], w4)
+    for variant, w in ((1, dev(w4)), (3, sa.sa_shift_planes_prepare(dev(w4)))):
+        got = host(sa.sa_shift_linear(dev(x), w, variant=variant))
+        assert np.array_equal(got[rows], ref), variant
